@@ -1,0 +1,157 @@
+/*
+ * fusionrag.h -- C ABI of the MI355X (gfx950) selective-prefill library.
+ *
+ * One transformer layer of FusionRAG's online reprocessing stage (arXiv 2601.12904):
+ *
+ *   fr_rope_shift           stitch the cached chunks: move each chunk's keys from the positions
+ *                           they were cached at to their positions in the assembled prompt
+ *   fr_score_select         Query-Guided Selection: critical score per context token, top-k,
+ *                           and the Q index (critical tokens, then question tokens)
+ *   fr_sparse_prefill_attn  causal attention of the Q-index rows only, over the whole K/V
+ *   fr_kv_scatter           place the recomputed K/V rows in the cache
+ *
+ * Conventions shared by every entry point
+ *   - Tensors are token-major [tokens, heads, head_dim], head_dim contiguous, no padding, element
+ *     type fr_layer_desc.dtype.  "dev" pointers are device (HBM) addresses, 16-byte aligned;
+ *     "host" pointers are ordinary host memory read before the call returns.
+ *   - The caller owns every tensor.  The library owns only the workspace allocated by fr_create.
+ *   - Every call enqueues its kernels on the given HIP stream (a hipStream_t passed as void*,
+ *     NULL = the default stream) and returns without synchronising it.  Calls that share a
+ *     context share its workspace and must be stream-ordered with respect to each other.
+ *   - Positions and token indices are 0-based (the paper counts from 1).
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).  Logits are scaled by
+ *     1/sqrt(head_dim).
+ *   - Arguments are validated on the host before anything is launched; on an invalid argument
+ *     nothing is enqueued and FR_ERR_INVALID_ARG / FR_ERR_UNSUPPORTED is returned.  The contents
+ *     of device buffers (for example that q_index is ascending) are preconditions and are not
+ *     checked.  No call throws or aborts.
+ */
+#ifndef FUSIONRAG_H
+#define FUSIONRAG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fr_ctx fr_ctx; /* opaque: layer description + device workspace */
+
+typedef enum {
+    FR_OK = 0,
+    FR_ERR_INVALID_ARG = 1, /* null / misaligned pointer, bad size, offsets not ascending, ...   */
+    FR_ERR_UNSUPPORTED = 2, /* a shape or mode this build has no kernel for                      */
+    FR_ERR_WORKSPACE = 3,   /* the call needs more workspace than fr_create was sized for        */
+    FR_ERR_DEVICE = 4       /* no GPU, or a HIP call failed (message in fr_last_error)           */
+} fr_status;
+
+typedef enum { FR_F32 = 0, FR_BF16 = 1 } fr_dtype;
+
+/* How the two members of a rotary pair are laid out in the head dimension.
+ * INTERLEAVED: pairs (0,1), (2,3), ... -- the paper's definition (Appendix A:
+ * rotate(k) = [-k2, k1, -k4, k3, ...], theta repeated pairwise).  HALF: pairs (p, p + d/2). */
+typedef enum { FR_ROPE_INTERLEAVED = 0, FR_ROPE_HALF = 1 } fr_rope_layout;
+
+/* What "attention weight" means when the critical scores are summed (Sec. 3.2).
+ * PER_CHUNK: softmax over the keys of the token's own chunk (the matrix is built per chunk).
+ * GLOBAL:    one softmax over all context keys.
+ * RAW:       no softmax, the scaled logits themselves.                                         */
+typedef enum { FR_NORM_PER_CHUNK = 0, FR_NORM_GLOBAL = 1, FR_NORM_RAW = 2 } fr_score_norm;
+
+typedef struct {
+    int32_t n_q_heads;       /* Hq                                                               */
+    int32_t n_kv_heads;      /* Hkv, divides Hq                                                  */
+    int32_t head_dim;        /* d: 64 or 128                                                     */
+    int32_t dtype;           /* fr_dtype: storage type of Q, K, V and O                          */
+    double rope_base;        /* theta_p = rope_base^(-2 (p + rope_index_base) / d)               */
+    int32_t rope_layout;     /* fr_rope_layout                                                   */
+    int32_t rope_index_base; /* 0: p = 0..d/2-1 (usual); 1: the appendix's printed i = 1..d/2    */
+} fr_layer_desc;
+
+#define FR_MAX_CHUNKS 256 /* chunk tables travel as kernel arguments                           */
+
+/* Create a context for one layer shape.  max_tokens bounds L (context + question tokens),
+ * max_chunks (<= FR_MAX_CHUNKS) the number of chunks, max_question_tokens bounds nq.  Allocates
+ * the device workspace on the current device; with no GPU present the context is still created
+ * (argument validation works) and every launching call returns FR_ERR_DEVICE.
+ * *out is set to NULL on failure. */
+fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_chunks,
+                    int32_t max_question_tokens, fr_ctx** out);
+
+/* Free the workspace.  The caller must have synchronised every stream the context was used on. */
+void fr_destroy(fr_ctx* ctx);
+
+/* Message of the last failing call on this context (valid until the next call on it). */
+const char* fr_last_error(const fr_ctx* ctx);
+
+/* Bytes of device workspace the context holds (0 without a GPU). */
+int64_t fr_workspace_bytes(const fr_ctx* ctx);
+
+/* Number of context tokens a recompute ratio selects: floor(ratio * L_ctx + 0.5) clamped to
+ * [0, L_ctx].  The ratio counts context tokens; question tokens are always computed (Sec. 4.3).
+ * Pure host function. */
+int64_t fr_topk_count(int64_t L_ctx, double ratio);
+
+/* Position recovery while stitching chunk caches (Sec. 2.2.1 footnote, Appendix A).
+ * For chunk c (rows chunk_offsets[c] .. chunk_offsets[c+1]-1) every key is rotated by
+ * Delta_c = dst_pos0[c] - src_pos0[c] positions: pair (a, b) of rotary index p becomes
+ * (a cos(Delta_c theta_p) - b sin(..), b cos(..) + a sin(..)).  RoPE is additive, so a key cached
+ * at position s lands at position s + Delta_c.  Values are not touched.
+ *   k_src, k_dst   dev [n_batch][L_ctx, Hkv, d]; batch b starts at b * batch_stride elements
+ *                  (n_batch > 1 is the all-layers case: the same chunk table for every layer);
+ *                  k_dst may equal k_src (in place), otherwise the two must not overlap
+ *   chunk_offsets  host [n_chunks + 1], [0] = 0, non-decreasing, [n_chunks] = L_ctx
+ *   chunk_src_pos0 host [n_chunks]: position the chunk's first token was cached at
+ *   chunk_dst_pos0 host [n_chunks], or NULL: chunk c lands at chunk_offsets[c] + dst_base
+ * Arithmetic: fp32 on cos/sin rounded from fp64; output rounded to dtype (nearest-even). */
+fr_status fr_rope_shift(fr_ctx* ctx, const void* k_src, void* k_dst, const int32_t* chunk_offsets,
+                        const int32_t* chunk_src_pos0, const int32_t* chunk_dst_pos0,
+                        int32_t dst_base, int32_t n_chunks, int32_t n_batch,
+                        int64_t src_batch_stride, int64_t dst_batch_stride, void* stream);
+
+/* Query-Guided Selection (Sec. 3.2) and the Q index (Sec. 4.3).
+ * score[j] = sum over query heads h and question tokens i of w[h, i, j], where w is the attention
+ * weight of question query (i, h) on context key j under `norm`; then the k highest scores are
+ * chosen (equal scores: lower index first) and
+ *   q_index_out = ascending(chosen) ++ [L_ctx, L_ctx + 1, ..., L_ctx + nq - 1].
+ *   q_question  dev [nq, Hq, d]: the question's queries, already rotated at positions L_ctx..
+ *   k_ctx       dev [L_ctx, Hkv, d]: context keys at their global positions (fr_rope_shift output)
+ *   chunk_offsets host [n_chunks + 1] as above (used by FR_NORM_PER_CHUNK; L_ctx = last entry)
+ *   k           number of context tokens to choose, 0 <= k <= L_ctx
+ *   scores_out  dev [L_ctx] fp32, or NULL
+ *   q_index_out dev [k + nq] int32
+ * No causal mask is involved: every context key precedes every question token. */
+fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const void* k_ctx,
+                          const int32_t* chunk_offsets, int32_t n_chunks, int64_t k, int32_t norm,
+                          float* scores_out, int32_t* q_index_out, void* stream);
+
+/* Only the selection half of the call above, over scores the caller already has (any selector:
+ * for example the KV deviation of eq. 7-8).  scores dev [n] fp32 (finite), q_index_out dev [k + nq]. */
+fr_status fr_select_topk(fr_ctx* ctx, const float* scores, int64_t n, int64_t k, int32_t nq,
+                         int32_t* q_index_out, void* stream);
+
+/* Sparse prefill attention (eq. 9, Sec. 4.3).  Row r holds the query of the token at position
+ * q_index[r]; it attends to every key at a position <= q_index[r].  The key/value at a position
+ * listed in q_index is the recomputed one (k_new/v_new row of that token), every other position
+ * reads the cache: the stale cache entries of recomputed tokens are never read.
+ *   q_rows   dev [R, Hq, d]
+ *   q_index  dev [R] int32, strictly ascending, every entry < L
+ *   k_cache, v_cache dev [L, Hkv, d] (read only)
+ *   k_new, v_new     dev [R, Hkv, d], or both NULL: the cache already holds the fresh rows
+ *   out      dev [R, Hq, d]
+ *   lse_out  dev [R, Hq] fp32 natural-log-sum-exp of the scaled logits, or NULL
+ * Arithmetic: products of dtype inputs accumulated in fp32, softmax in fp32, out rounded to dtype. */
+fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
+                                 const void* k_cache, const void* v_cache, int64_t L,
+                                 const void* k_new, const void* v_new, void* out, float* lse_out,
+                                 void* stream);
+
+/* Write-back (Sec. 4.3): k_cache[q_index[r]] = k_new[r], v_cache[q_index[r]] = v_new[r],
+ * bit-exact copies; other rows are not touched.  Shapes as above. */
+fr_status fr_kv_scatter(fr_ctx* ctx, const void* k_new, const void* v_new, const int32_t* q_index,
+                        int32_t R, void* k_cache, void* v_cache, int64_t L, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FUSIONRAG_H */

@@ -1,0 +1,344 @@
+// C ABI of libfusionrag: argument validation, workspace, dispatch.  No kernels here.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include <new>
+
+#include "fr_internal.hpp"
+
+using namespace fr;
+
+namespace {
+
+fr_status fail(fr_ctx* ctx, fr_status st, const char* fmt, ...) {
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof(buf), fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return st;
+}
+
+fr_status hip_fail(fr_ctx* ctx, const char* what, hipError_t e) {
+    return fail(ctx, FR_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Validates a host chunk table and copies it into the by-value form.
+fr_status read_chunks(fr_ctx* ctx, const int32_t* offs, int32_t n_chunks, int64_t max_ctx, ChunkTable* ct,
+                      int* max_len) {
+    if (!offs) return fail(ctx, FR_ERR_INVALID_ARG, "chunk_offsets is NULL");
+    if (n_chunks < 0) return fail(ctx, FR_ERR_INVALID_ARG, "n_chunks = %d is negative", n_chunks);
+    if (n_chunks > ctx->max_chunks)
+        return fail(ctx, FR_ERR_WORKSPACE, "n_chunks = %d exceeds the context's max_chunks = %d", n_chunks,
+                    ctx->max_chunks);
+    if (offs[0] != 0) return fail(ctx, FR_ERR_INVALID_ARG, "chunk_offsets[0] = %d, must be 0", offs[0]);
+    int ml = 0;
+    ct->n = n_chunks;
+    ct->off[0] = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        if (offs[c + 1] < offs[c])
+            return fail(ctx, FR_ERR_INVALID_ARG, "chunk_offsets not ascending at %d: %d then %d", c, offs[c],
+                        offs[c + 1]);
+        ct->off[c + 1] = offs[c + 1];
+        if (offs[c + 1] - offs[c] > ml) ml = offs[c + 1] - offs[c];
+    }
+    if ((int64_t)offs[n_chunks] > max_ctx)
+        return fail(ctx, FR_ERR_WORKSPACE, "L_ctx = %d exceeds the context's max_tokens = %lld", offs[n_chunks],
+                    (long long)max_ctx);
+    if (max_len) *max_len = ml;
+    return FR_OK;
+}
+
+fr_status need_device(fr_ctx* ctx) {
+    if (!ctx->has_device) return fail(ctx, FR_ERR_DEVICE, "no HIP device: this context can only validate arguments");
+    return FR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t fr_topk_count(int64_t L_ctx, double ratio) {
+    if (L_ctx <= 0 || !(ratio > 0.0)) return 0;
+    const double v = floor(ratio * (double)L_ctx + 0.5);
+    if (v >= (double)L_ctx) return L_ctx;
+    return (int64_t)v;
+}
+
+fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_chunks, int32_t max_question_tokens,
+                    fr_ctx** out) {
+    if (!out) return FR_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!desc) return FR_ERR_INVALID_ARG;
+    if (desc->n_q_heads <= 0 || desc->n_kv_heads <= 0 || desc->n_q_heads % desc->n_kv_heads != 0)
+        return FR_ERR_INVALID_ARG;
+    if (desc->dtype != FR_F32 && desc->dtype != FR_BF16) return FR_ERR_INVALID_ARG;
+    if (desc->rope_layout != FR_ROPE_INTERLEAVED && desc->rope_layout != FR_ROPE_HALF) return FR_ERR_INVALID_ARG;
+    if (desc->rope_index_base != 0 && desc->rope_index_base != 1) return FR_ERR_INVALID_ARG;
+    if (!(desc->rope_base > 1.0) || !isfinite(desc->rope_base)) return FR_ERR_INVALID_ARG;
+    if (max_tokens <= 0 || max_tokens > (int64_t)1 << 30) return FR_ERR_INVALID_ARG;
+    if (max_chunks <= 0 || max_question_tokens < 0 || max_question_tokens > max_tokens) return FR_ERR_INVALID_ARG;
+    if (desc->head_dim != 64 && desc->head_dim != 128) return FR_ERR_UNSUPPORTED;
+    if (max_chunks > FR_MAX_CHUNKS) return FR_ERR_UNSUPPORTED;
+    if (desc->n_q_heads > 1024) return FR_ERR_UNSUPPORTED;
+
+    fr_ctx* ctx = new (std::nothrow) fr_ctx();
+    if (!ctx) return FR_ERR_WORKSPACE;
+    Shape& s = ctx->shape;
+    s.Hq = desc->n_q_heads;
+    s.Hkv = desc->n_kv_heads;
+    s.d = desc->head_dim;
+    s.G = s.Hq / s.Hkv;
+    s.dtype = desc->dtype;
+    s.esize = desc->dtype == FR_BF16 ? 2 : 4;
+    s.rope_base = desc->rope_base;
+    s.rope_layout = desc->rope_layout;
+    s.rope_index_base = desc->rope_index_base;
+    ctx->max_tokens = max_tokens;
+    ctx->max_chunks = max_chunks;
+    ctx->max_q = max_question_tokens;
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        ctx->has_device = false;
+        *out = ctx;
+        return FR_OK;
+    }
+    if (hipGetDevice(&ctx->device) != hipSuccess) {
+        delete ctx;
+        return FR_ERR_DEVICE;
+    }
+
+    // carve the workspace
+    Workspace& w = ctx->ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t o = off;
+        off += round_up(bytes, 256);
+        return o;
+    };
+    const size_t o_table = take((size_t)max_chunks * (s.d / 2) * sizeof(float2));
+    const size_t o_lse = take((size_t)s.Hq * (max_chunks + 1) * (size_t)(max_question_tokens > 0 ? max_question_tokens : 1) * 4);
+    const size_t o_col = take((size_t)s.Hkv * max_tokens * 4);
+    const size_t o_scores = take((size_t)max_tokens * 4);
+    const size_t o_inv = take((size_t)max_tokens * 4);
+    const size_t o_sel = take(4096);
+    // split-key partials of the tiled attention kernel: at most two parts per row
+    w.attn_part_o_elems = (size_t)2 * max_tokens * s.Hq * s.d;
+    w.attn_part_ml_elems = (size_t)2 * 2 * max_tokens * s.Hq;
+    const size_t o_po = take(w.attn_part_o_elems * 4);
+    const size_t o_pml = take(w.attn_part_ml_elems * 4);
+    w.bytes = off;
+    hipError_t e = hipMalloc((void**)&w.base, w.bytes);
+    if (e != hipSuccess) {
+        delete ctx;
+        return FR_ERR_WORKSPACE;
+    }
+    w.rope_table = (float2*)(w.base + o_table);
+    w.lse = (float*)(w.base + o_lse);
+    w.col_partial = (float*)(w.base + o_col);
+    w.scores = (float*)(w.base + o_scores);
+    w.inv_index = (int32_t*)(w.base + o_inv);
+    w.select_tmp = (uint32_t*)(w.base + o_sel);
+    w.attn_part_o = (float*)(w.base + o_po);
+    w.attn_part_ml = (float*)(w.base + o_pml);
+    ctx->has_device = true;
+    *out = ctx;
+    return FR_OK;
+}
+
+void fr_destroy(fr_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->ws.base) (void)hipFree(ctx->ws.base);
+    delete ctx;
+}
+
+const char* fr_last_error(const fr_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int64_t fr_workspace_bytes(const fr_ctx* ctx) { return ctx ? (int64_t)ctx->ws.bytes : 0; }
+
+fr_status fr_rope_shift(fr_ctx* ctx, const void* k_src, void* k_dst, const int32_t* chunk_offsets,
+                        const int32_t* chunk_src_pos0, const int32_t* chunk_dst_pos0, int32_t dst_base,
+                        int32_t n_chunks, int32_t n_batch, int64_t src_batch_stride, int64_t dst_batch_stride,
+                        void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    const Shape& s = ctx->shape;
+    ChunkTable ct;
+    int max_len = 0;
+    fr_status st = read_chunks(ctx, chunk_offsets, n_chunks, ctx->max_tokens, &ct, &max_len);
+    if (st != FR_OK) return st;
+    if (!chunk_src_pos0) return fail(ctx, FR_ERR_INVALID_ARG, "chunk_src_pos0 is NULL");
+    if (n_batch < 0 || n_batch > 65535) return fail(ctx, FR_ERR_INVALID_ARG, "n_batch = %d out of range", n_batch);
+    const int64_t L_ctx = ct.off[ct.n];
+    const int64_t layer_elems = L_ctx * s.Hkv * s.d;
+    if (n_batch > 1 && (src_batch_stride < layer_elems || dst_batch_stride < layer_elems))
+        return fail(ctx, FR_ERR_INVALID_ARG, "batch stride smaller than one layer (%lld elements)",
+                    (long long)layer_elems);
+    if (n_batch > 1 && ((src_batch_stride * s.esize) % 16 != 0 || (dst_batch_stride * s.esize) % 16 != 0))
+        return fail(ctx, FR_ERR_INVALID_ARG, "batch strides must keep 16-byte alignment");
+    if (L_ctx > 0 && n_batch > 0) {
+        if (!k_src || !k_dst) return fail(ctx, FR_ERR_INVALID_ARG, "k_src / k_dst is NULL");
+        if (!aligned16(k_src) || !aligned16(k_dst))
+            return fail(ctx, FR_ERR_INVALID_ARG, "k_src / k_dst must be 16-byte aligned");
+        if (k_src != k_dst) {
+            const char* a = (const char*)k_src;
+            const char* b = (const char*)k_dst;
+            const int64_t span_a = ((int64_t)(n_batch - 1) * src_batch_stride + layer_elems) * s.esize;
+            const int64_t span_b = ((int64_t)(n_batch - 1) * dst_batch_stride + layer_elems) * s.esize;
+            if (a < b + span_b && b < a + span_a)
+                return fail(ctx, FR_ERR_INVALID_ARG, "k_src and k_dst overlap without being equal");
+        }
+    }
+    ChunkDeltas dl;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t dst = chunk_dst_pos0 ? (int64_t)chunk_dst_pos0[c] : (int64_t)ct.off[c] + dst_base;
+        const int64_t delta = dst - (int64_t)chunk_src_pos0[c];
+        if (delta > INT32_MAX || delta < INT32_MIN) return fail(ctx, FR_ERR_INVALID_ARG, "position delta overflows");
+        dl.delta[c] = (int32_t)delta;
+    }
+    if (L_ctx == 0 || n_batch == 0) return FR_OK;
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    hipError_t e = launch_rope_table(s, dl, n_chunks, ctx->ws.rope_table, hs);
+    if (e != hipSuccess) return hip_fail(ctx, "rope table launch", e);
+    e = launch_rope_shift(s, k_src, k_dst, ct, max_len, ctx->ws.rope_table, n_batch, src_batch_stride,
+                          dst_batch_stride, hs);
+    if (e != hipSuccess) return hip_fail(ctx, "rope shift launch", e);
+    return FR_OK;
+}
+
+fr_status fr_select_topk(fr_ctx* ctx, const float* scores, int64_t n, int64_t k, int32_t nq, int32_t* q_index_out,
+                         void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    if (n < 0 || n > INT32_MAX - (int64_t)(nq > 0 ? nq : 0))
+        return fail(ctx, FR_ERR_INVALID_ARG, "n = %lld out of range", (long long)n);
+    if (nq < 0) return fail(ctx, FR_ERR_INVALID_ARG, "nq = %d is negative", nq);
+    if (k < 0 || k > n) return fail(ctx, FR_ERR_INVALID_ARG, "k = %lld outside [0, n = %lld]", (long long)k, (long long)n);
+    if (k + nq == 0) return FR_OK;
+    if (!q_index_out) return fail(ctx, FR_ERR_INVALID_ARG, "q_index_out is NULL");
+    if (n > 0 && k > 0 && !scores) return fail(ctx, FR_ERR_INVALID_ARG, "scores is NULL");
+    if ((reinterpret_cast<uintptr_t>(scores) & 3u) || (reinterpret_cast<uintptr_t>(q_index_out) & 3u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "scores / q_index_out must be 4-byte aligned");
+    fr_status st = need_device(ctx);
+    if (st != FR_OK) return st;
+    hipError_t e = launch_select(scores, n, k, nq, q_index_out, ctx->ws.select_tmp, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, "select launch", e);
+    return FR_OK;
+}
+
+fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const void* k_ctx,
+                          const int32_t* chunk_offsets, int32_t n_chunks, int64_t k, int32_t norm, float* scores_out,
+                          int32_t* q_index_out, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    const Shape& s = ctx->shape;
+    if (nq < 0) return fail(ctx, FR_ERR_INVALID_ARG, "nq = %d is negative", nq);
+    if (nq > ctx->max_q) return fail(ctx, FR_ERR_WORKSPACE, "nq = %d exceeds max_question_tokens = %d", nq, ctx->max_q);
+    ChunkTable ct;
+    fr_status st = read_chunks(ctx, chunk_offsets, n_chunks, ctx->max_tokens - nq, &ct, nullptr);
+    if (st != FR_OK) return st;
+    const int64_t L_ctx = ct.off[ct.n];
+    if (norm != FR_NORM_PER_CHUNK && norm != FR_NORM_GLOBAL && norm != FR_NORM_RAW)
+        return fail(ctx, FR_ERR_INVALID_ARG, "unknown score norm %d", norm);
+    if (k < 0 || k > L_ctx)
+        return fail(ctx, FR_ERR_INVALID_ARG, "k = %lld outside [0, L_ctx = %lld]", (long long)k, (long long)L_ctx);
+    if (k + nq > 0 && !q_index_out) return fail(ctx, FR_ERR_INVALID_ARG, "q_index_out is NULL");
+    if (nq > 0 && (!q_question || !aligned16(q_question)))
+        return fail(ctx, FR_ERR_INVALID_ARG, "q_question is NULL or not 16-byte aligned");
+    if (L_ctx > 0 && (!k_ctx || !aligned16(k_ctx)))
+        return fail(ctx, FR_ERR_INVALID_ARG, "k_ctx is NULL or not 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scores_out) & 3u) || (reinterpret_cast<uintptr_t>(q_index_out) & 3u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "scores_out / q_index_out must be 4-byte aligned");
+    if (L_ctx == 0 && nq == 0) return FR_OK;
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    float* scores = scores_out ? scores_out : ctx->ws.scores;
+    const bool need_scores = (scores_out != nullptr) || (k > 0 && k < L_ctx);
+    if (L_ctx > 0 && need_scores) {
+        hipError_t e;
+        if (score_mfma_supported(s) && nq > 0)
+            e = launch_score_mfma(s, q_question, nq, k_ctx, ct, norm, ctx->ws, scores, hs);
+        else
+            e = launch_score_simt(s, q_question, nq, k_ctx, ct, norm, ctx->ws, scores, hs);
+        if (e != hipSuccess) return hip_fail(ctx, "score launch", e);
+    }
+    hipError_t e = launch_select(scores, L_ctx, k, nq, q_index_out, ctx->ws.select_tmp, hs);
+    if (e != hipSuccess) return hip_fail(ctx, "select launch", e);
+    return FR_OK;
+}
+
+static fr_status check_rows(fr_ctx* ctx, int32_t R, int64_t L) {
+    if (R < 0) return fail(ctx, FR_ERR_INVALID_ARG, "R = %d is negative", R);
+    if (L < 0) return fail(ctx, FR_ERR_INVALID_ARG, "L = %lld is negative", (long long)L);
+    if (L > ctx->max_tokens)
+        return fail(ctx, FR_ERR_WORKSPACE, "L = %lld exceeds the context's max_tokens = %lld", (long long)L,
+                    (long long)ctx->max_tokens);
+    if (R > L) return fail(ctx, FR_ERR_INVALID_ARG, "R = %d rows but only L = %lld positions", R, (long long)L);
+    return FR_OK;
+}
+
+fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
+                                 const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
+                                 const void* v_new, void* out, float* lse_out, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    const Shape& s = ctx->shape;
+    fr_status st = check_rows(ctx, R, L);
+    if (st != FR_OK) return st;
+    if (R == 0) return FR_OK;
+    if (!q_rows || !q_index || !k_cache || !v_cache || !out)
+        return fail(ctx, FR_ERR_INVALID_ARG, "q_rows / q_index / k_cache / v_cache / out is NULL");
+    if ((k_new == nullptr) != (v_new == nullptr))
+        return fail(ctx, FR_ERR_INVALID_ARG, "k_new and v_new must both be given or both be NULL");
+    if (!aligned16(q_rows) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) || !aligned16(k_new) ||
+        !aligned16(v_new))
+        return fail(ctx, FR_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(q_index) & 3u) || (reinterpret_cast<uintptr_t>(lse_out) & 3u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "q_index / lse_out must be 4-byte aligned");
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    const int32_t* inv = nullptr;
+    if (k_new) {
+        hipError_t e = launch_inv_index(q_index, R, L, ctx->ws.inv_index, hs);
+        if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
+        inv = ctx->ws.inv_index;
+    }
+    hipError_t e;
+    if (attn_mfma_supported(s))
+        e = launch_attn_mfma(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, ctx->ws, hs);
+    else
+        e = launch_attn_simt(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, hs);
+    if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
+    return FR_OK;
+}
+
+fr_status fr_kv_scatter(fr_ctx* ctx, const void* k_new, const void* v_new, const int32_t* q_index, int32_t R,
+                        void* k_cache, void* v_cache, int64_t L, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    fr_status st = check_rows(ctx, R, L);
+    if (st != FR_OK) return st;
+    if (R == 0) return FR_OK;
+    if (!k_new || !v_new || !q_index || !k_cache || !v_cache)
+        return fail(ctx, FR_ERR_INVALID_ARG, "k_new / v_new / q_index / k_cache / v_cache is NULL");
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache))
+        return fail(ctx, FR_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(q_index) & 3u) return fail(ctx, FR_ERR_INVALID_ARG, "q_index must be 4-byte aligned");
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipError_t e = launch_kv_scatter(ctx->shape, k_new, v_new, q_index, R, k_cache, v_cache, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, "scatter launch", e);
+    return FR_OK;
+}
+
+}  // extern "C"

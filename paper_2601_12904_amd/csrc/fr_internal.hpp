@@ -1,0 +1,105 @@
+// Internal declarations shared by the translation units of libfusionrag (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "fusionrag.h"
+
+namespace fr {
+
+// Chunk boundaries travel to the kernels by value (kernel arguments are captured at launch, so a
+// call never depends on host memory or a staging buffer after it returns).
+struct ChunkTable {
+    int32_t n;
+    int32_t off[FR_MAX_CHUNKS + 1];
+};
+struct ChunkDeltas {
+    int32_t delta[FR_MAX_CHUNKS];
+};
+
+struct Shape {
+    int Hq, Hkv, d, G;
+    int dtype;       // fr_dtype
+    int esize;       // bytes per element
+    double rope_base;
+    int rope_layout;
+    int rope_index_base;
+};
+
+// Device workspace, carved from one allocation.
+struct Workspace {
+    char* base = nullptr;
+    size_t bytes = 0;
+    float2* rope_table = nullptr;   // [max_chunks][d/2] (cos, sin)
+    float* lse = nullptr;           // [Hq][max_chunks + 1][max_q]  natural-log row normalisers
+    float* col_partial = nullptr;   // [Hkv][max_ctx] per-KV-head column sums
+    float* scores = nullptr;        // [max_tokens]
+    int32_t* inv_index = nullptr;   // [max_tokens] position -> row of k_new / -1
+    uint32_t* select_tmp = nullptr; // small counters for the selection kernels
+    float* attn_part_o = nullptr;   // split-key partial outputs
+    float* attn_part_ml = nullptr;  // their running max / sum
+    size_t attn_part_o_elems = 0;
+    size_t attn_part_ml_elems = 0;
+};
+
+}  // namespace fr
+
+struct fr_ctx {
+    fr::Shape shape;
+    int64_t max_tokens = 0;
+    int32_t max_chunks = 0;
+    int32_t max_q = 0;
+    bool has_device = false;
+    int device = -1;
+    fr::Workspace ws;
+    std::string err;
+};
+
+namespace fr {
+
+// Launchers.  Each returns hipSuccess or the launch error; none synchronises.
+hipError_t launch_rope_table(const Shape& s, const ChunkDeltas& deltas, int n_chunks, float2* table,
+                             hipStream_t st);
+hipError_t launch_rope_shift(const Shape& s, const void* src, void* dst, const ChunkTable& ct,
+                             int max_chunk_len, const float2* table, int n_batch, int64_t src_stride,
+                             int64_t dst_stride, hipStream_t st);
+hipError_t launch_kv_scatter(const Shape& s, const void* k_new, const void* v_new, const int32_t* q_index,
+                             int R, void* k_cache, void* v_cache, hipStream_t st);
+
+hipError_t launch_score_simt(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct,
+                             int norm, const Workspace& ws, float* scores, hipStream_t st);
+bool score_mfma_supported(const Shape& s);
+hipError_t launch_score_mfma(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct,
+                             int norm, const Workspace& ws, float* scores, hipStream_t st);
+
+hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index,
+                         uint32_t* tmp, hipStream_t st);
+
+hipError_t launch_inv_index(const int32_t* q_index, int R, int64_t L, int32_t* inv, hipStream_t st);
+hipError_t launch_attn_simt(const Shape& s, const void* q_rows, const int32_t* q_index, int R,
+                            const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
+                            const void* v_new, const int32_t* inv, void* out, float* lse, hipStream_t st);
+bool attn_mfma_supported(const Shape& s);
+hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R,
+                            const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
+                            const void* v_new, const int32_t* inv, void* out, float* lse,
+                            const Workspace& ws, hipStream_t st);
+
+// ---- element helpers (device) ------------------------------------------------------------
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+    static __device__ __forceinline__ float to_f32(float v) { return v; }
+    static __device__ __forceinline__ float from_f32(float v) { return v; }
+};
+template <>
+struct Elem<__bf16> {
+    static __device__ __forceinline__ float to_f32(__bf16 v) { return (float)v; }
+    static __device__ __forceinline__ __bf16 from_f32(float v) { return (__bf16)v; }  // nearest-even
+};
+
+}  // namespace fr

@@ -1,0 +1,266 @@
+"""GPU parity: every entry point of the C-ABI library against the fp64 oracle, element by element,
+on seeded synthetic inputs that span several kernel tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fusionrag_oracle as orc
+from paper_2601_12904_amd import binding as B
+from paper_2601_12904_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+BF16_D64_G2 = synth.LayerShape(n_q_heads=4, n_kv_heads=2, head_dim=64, dtype="bf16", rope_base=10000.0)
+F32_D128_G4 = synth.LayerShape(n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="f32", rope_base=500000.0)
+
+
+def workloads():
+    return {
+        "tiny_f32": lambda seed: synth.config_tiny(seed=seed),
+        "small_bf16": lambda seed: synth.config_small_bf16(seed=seed),
+        "small_bf16_d64": lambda seed: synth.config_small_bf16(seed=seed, shape=BF16_D64_G2, chunk_lens=(70, 130, 3)),
+        "small_f32_d128": lambda seed: synth.make_workload("f32_d128", F32_D128_G4, [100, 1, 77], nq=9, ratio=0.2,
+                                                           seed=seed, focus_frac=0.05),
+    }
+
+
+CASES = [(n, s) for n in workloads() for s in (0, 1)]
+
+
+def staged(w: synth.Workload):
+    """Oracle results of every stage, each fed with the oracle's previous stage rounded to storage."""
+    dt = w.shape.dtype
+    k_ctx = synth.round_to_storage(orc.rope_shift(w.k_cached, w.chunk_offsets, w.src_pos0, None, w.shape.rope_base), dt)
+    scores = orc.critical_scores(w.q_question, k_ctx, w.chunk_offsets)
+    k = orc.topk_count(w.L_ctx, w.ratio)
+    qi = orc.select_q_index(scores, k, w.nq)
+    return k_ctx, scores, k, qi
+
+
+def assembled_cache(w: synth.Workload, k_ctx: np.ndarray, seed: int = 99):
+    """Per-query cache [L]: shifted stale keys / stale values, then nq reserved rows (arbitrary content)."""
+    rng = np.random.default_rng(seed)
+    pad = lambda: synth.round_to_storage(rng.standard_normal((w.nq,) + k_ctx.shape[1:]).astype(np.float32), w.shape.dtype)
+    return np.concatenate([k_ctx, pad()]), np.concatenate([w.v_cached, pad()])
+
+
+@pytest.mark.parametrize("name,seed", CASES)
+def test_rope_shift(name, seed):
+    w = workloads()[name](seed)
+    dt = w.shape.dtype
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    src = H.dev(w.k_cached, dt)
+    dst = torch.empty_like(src)
+    ctx.fr_rope_shift(src, dst, w.chunk_offsets, w.src_pos0)
+    torch.cuda.synchronize()
+    want = orc.rope_shift(w.k_cached, w.chunk_offsets, w.src_pos0, None, w.shape.rope_base)
+    got = H.host(dst)
+    H.assert_close(got, want, dt, "rope_shift")
+    # element-wise: the result is the fp64 value rounded once to storage, give or take one unit
+    ulp = 2.0 ** -7 if dt == "bf16" else 2.0 ** -21
+    assert np.all(np.abs(got - want) <= ulp * np.abs(want) + 1e-30 + (1e-6 if dt == "f32" else 1e-4) * np.abs(want).max())
+    # in place gives the same bits
+    ctx.fr_rope_shift(src, src, w.chunk_offsets, w.src_pos0)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    ctx.close()
+
+
+@pytest.mark.parametrize("layout,index_base", [(B.FR_ROPE_HALF, 0), (B.FR_ROPE_INTERLEAVED, 1), (B.FR_ROPE_HALF, 1)])
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
+def test_rope_shift_variants(name, layout, index_base):
+    w = workloads()[name](3)
+    dt = w.shape.dtype
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq, rope_layout=layout, rope_index_base=index_base)
+    rng = np.random.default_rng(5)
+    src_pos = rng.integers(0, 50, size=w.n_chunks)
+    dst_pos = rng.integers(0, 40000, size=w.n_chunks)
+    src = H.dev(w.k_cached, dt)
+    dst = torch.empty_like(src)
+    ctx.fr_rope_shift(src, dst, w.chunk_offsets, src_pos, dst_pos)
+    torch.cuda.synchronize()
+    want = orc.rope_shift(w.k_cached, w.chunk_offsets, src_pos, dst_pos, w.shape.rope_base,
+                          "half" if layout == B.FR_ROPE_HALF else "interleaved", index_base)
+    H.assert_close(H.host(dst), want, dt, "rope_shift variant")
+    ctx.close()
+
+
+def test_rope_shift_batched_layers_and_empty_chunk():
+    shape = synth.LLAMA3_8B_BF16
+    w = synth.make_workload("b", shape, [40, 0, 90, 33], nq=4, ratio=0.15, seed=4, sigma_q=1, sigma_kv=1)
+    ctx = H.make_ctx(shape, w.L, w.n_chunks, w.nq)
+    n_batch, pad = 3, 64
+    layer = w.L_ctx * shape.n_kv_heads * shape.head_dim
+    rng = np.random.default_rng(0)
+    layers = [synth.round_to_storage(rng.standard_normal(w.k_cached.shape).astype(np.float32), "bf16") for _ in range(n_batch)]
+    buf = torch.zeros(n_batch * (layer + pad), dtype=torch.bfloat16, device="cuda")
+    for b in range(n_batch):
+        buf[b * (layer + pad): b * (layer + pad) + layer] = H.dev(layers[b], "bf16").reshape(-1)
+    out = torch.full_like(buf, 7.0)
+    ctx.fr_rope_shift(buf, out, w.chunk_offsets, w.src_pos0, dst_base=1000, n_batch=n_batch,
+                      src_batch_stride=layer + pad, dst_batch_stride=layer + pad)
+    torch.cuda.synchronize()
+    for b in range(n_batch):
+        want = orc.rope_shift(layers[b], w.chunk_offsets, w.src_pos0, None, shape.rope_base, dst_base=1000)
+        got = H.host(out[b * (layer + pad): b * (layer + pad) + layer]).reshape(want.shape)
+        H.assert_close(got, want, "bf16", f"layer {b}")
+        assert torch.all(out[b * (layer + pad) + layer: (b + 1) * (layer + pad)] == 7.0)   # padding untouched
+    ctx.close()
+
+
+@pytest.mark.parametrize("norm", [B.FR_NORM_PER_CHUNK, B.FR_NORM_GLOBAL, B.FR_NORM_RAW])
+@pytest.mark.parametrize("name,seed", CASES)
+def test_score_select(name, seed, norm):
+    w = workloads()[name](seed)
+    dt = w.shape.dtype
+    k_ctx, _, k, _ = staged(w)
+    norm_name = {0: "per_chunk", 1: "global", 2: "raw"}[norm]
+    want_scores = orc.critical_scores(w.q_question, k_ctx, w.chunk_offsets, norm_name)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    scores = torch.empty(w.L_ctx, dtype=torch.float32, device="cuda")
+    qi = torch.full((k + w.nq,), -1, dtype=torch.int32, device="cuda")
+    ctx.fr_score_select(H.dev(w.q_question, dt), w.nq, H.dev(k_ctx, dt), w.chunk_offsets, k, norm, scores, qi)
+    torch.cuda.synchronize()
+    got = scores.cpu().numpy().astype(np.float64)
+    err = H.max_rel_err(got, want_scores)
+    assert err <= 1e-4, f"scores: max relative error {err:.2e}"
+    H.assert_index_set(qi.cpu().numpy(), want_scores, k, w.nq)
+    # the selection itself is exact on the scores the kernel saw
+    assert np.array_equal(qi.cpu().numpy(), orc.select_q_index(scores.cpu().numpy(), k, w.nq))
+    # scores_out = NULL gives the same index
+    qi2 = torch.full_like(qi, -1)
+    ctx.fr_score_select(H.dev(w.q_question, dt), w.nq, H.dev(k_ctx, dt), w.chunk_offsets, k, norm, None, qi2)
+    torch.cuda.synchronize()
+    assert torch.equal(qi, qi2)
+    ctx.close()
+
+
+@pytest.mark.parametrize("n,k,nq", [(1, 1, 0), (1, 0, 3), (7, 3, 2), (1000, 150, 5), (1024, 1024, 0), (4097, 1, 1),
+                                    (16384, 2458, 512), (50000, 7500, 17), (16384, 16383, 0)])
+def test_select_topk_exact(n, k, nq):
+    ctx = H.make_ctx(synth.TINY_F32, 70000, 4, 600)
+    rng = np.random.default_rng(n + k)
+    for kind in ("uniform", "ties", "signed", "constant"):
+        if kind == "uniform":
+            s = rng.random(n).astype(np.float32)
+        elif kind == "ties":
+            s = rng.integers(0, 8, size=n).astype(np.float32)          # heavy ties: lowest index must win
+        elif kind == "signed":
+            s = rng.standard_normal(n).astype(np.float32)
+        else:
+            s = np.full(n, 0.25, dtype=np.float32)
+        out = torch.full((k + nq,), -7, dtype=torch.int32, device="cuda")
+        ctx.fr_select_topk(torch.from_numpy(s).cuda(), n, k, nq, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), orc.select_q_index(s, k, nq)), kind
+    ctx.close()
+
+
+def run_attention(ctx, w, qi, k_cache, v_cache, with_new=True, want_lse=True):
+    dt = w.shape.dtype
+    R = len(qi)
+    q_rows = H.dev(w.q_full[qi], dt)
+    k_new, v_new = H.dev(w.k_full[qi], dt), H.dev(w.v_full[qi], dt)
+    out = torch.zeros((R, w.shape.n_q_heads, w.shape.head_dim), dtype=H.TORCH_DTYPE[dt], device="cuda")
+    lse = torch.zeros((R, w.shape.n_q_heads), dtype=torch.float32, device="cuda") if want_lse else None
+    qi_d = torch.from_numpy(qi.astype(np.int32)).cuda()
+    ctx.fr_sparse_prefill_attn(q_rows, qi_d, R, H.dev(k_cache, dt), H.dev(v_cache, dt), w.L,
+                               k_new if with_new else None, v_new if with_new else None, out, lse)
+    torch.cuda.synchronize()
+    return H.host(out), (lse.cpu().numpy().astype(np.float64) if want_lse else None)
+
+
+@pytest.mark.parametrize("name,seed", CASES)
+def test_sparse_prefill_attn(name, seed):
+    w = workloads()[name](seed)
+    dt = w.shape.dtype
+    k_ctx, _, k, qi = staged(w)
+    k_cache, v_cache = assembled_cache(w, k_ctx)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    got, lse = run_attention(ctx, w, qi, k_cache, v_cache)
+    want, want_lse = orc.sparse_prefill_attn(w.q_full[qi], qi, k_cache, v_cache, w.k_full[qi], w.v_full[qi])
+    H.assert_close(got, want, dt, "attention output")
+    assert np.max(np.abs(lse - want_lse)) <= (1e-4 if dt == "f32" else 2e-3), "lse"
+    # fresh rows already scattered into the cache + NULL k_new: same result
+    k_eff, v_eff = orc.kv_scatter(qi, w.k_full[qi], w.v_full[qi], k_cache, v_cache)
+    got2, _ = run_attention(ctx, w, qi, k_eff, v_eff, with_new=False, want_lse=False)
+    H.assert_close(got2, want, dt, "attention over scattered cache")
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
+@pytest.mark.parametrize("ratio", [0.0, 0.05, 0.30, 1.0])
+def test_ratio_extremes(name, ratio):
+    w = workloads()[name](2)
+    dt = w.shape.dtype
+    k_ctx, scores, _, _ = staged(w)
+    k = orc.topk_count(w.L_ctx, ratio)
+    qi = orc.select_q_index(scores, k, w.nq)
+    k_cache, v_cache = assembled_cache(w, k_ctx)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    got, _ = run_attention(ctx, w, qi, k_cache, v_cache)
+    if ratio == 1.0:      # recomputing everything is full causal prefill, whatever the stale cache holds
+        want = orc.full_causal_attention(w.q_full, w.k_full, w.v_full)
+    else:
+        want, _ = orc.sparse_prefill_attn(w.q_full[qi], qi, k_cache, v_cache, w.k_full[qi], w.v_full[qi])
+    H.assert_close(got, want, dt, f"ratio {ratio}")
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,seed", CASES)
+def test_kv_scatter_bit_exact(name, seed):
+    w = workloads()[name](seed)
+    dt = w.shape.dtype
+    k_ctx, _, _, qi = staged(w)
+    k_cache, v_cache = assembled_cache(w, k_ctx)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    kc, vc = H.dev(k_cache, dt), H.dev(v_cache, dt)
+    k_new, v_new = H.dev(w.k_full[qi], dt), H.dev(w.v_full[qi], dt)
+    qi_d = torch.from_numpy(qi.astype(np.int32)).cuda()
+    ctx.fr_kv_scatter(k_new, v_new, qi_d, len(qi), kc, vc, w.L)
+    torch.cuda.synchronize()
+    want_k, want_v = orc.kv_scatter(qi, w.k_full[qi], w.v_full[qi], k_cache, v_cache)
+    assert np.array_equal(H.host(kc), want_k.astype(np.float64)) and np.array_equal(H.host(vc), want_v.astype(np.float64))
+    before_k = kc.clone()
+    ctx.fr_kv_scatter(k_new, v_new, qi_d, len(qi), kc, vc, w.L)   # idempotent
+    torch.cuda.synchronize()
+    assert torch.equal(kc, before_k)
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,seed", CASES)
+def test_chained_layer(name, seed):
+    """The four calls back to back on one stream, no host work in between, against the oracle chain."""
+    w = workloads()[name](seed)
+    dt = w.shape.dtype
+    tdt = H.TORCH_DTYPE[dt]
+    Hq, Hkv, d = w.shape.n_q_heads, w.shape.n_kv_heads, w.shape.head_dim
+    k_ctx_o, scores_o, k, qi_o = staged(w)
+    R = k + w.nq
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    k_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_cache[: w.L_ctx] = H.dev(w.v_cached, dt)
+    qi = torch.empty(R, dtype=torch.int32, device="cuda")
+    # the harness stands in for the model's QKV projection of the chosen rows: gather from the full tensors
+    q_full, k_full, v_full = H.dev(w.q_full, dt), H.dev(w.k_full, dt), H.dev(w.v_full, dt)
+    ctx.fr_rope_shift(H.dev(w.k_cached, dt), k_cache, w.chunk_offsets, w.src_pos0)
+    ctx.fr_score_select(q_full[w.L_ctx:].contiguous(), w.nq, k_cache, w.chunk_offsets, k, B.FR_NORM_PER_CHUNK, None, qi)
+    idx = qi.long()
+    q_rows, k_new, v_new = q_full[idx].contiguous(), k_full[idx].contiguous(), v_full[idx].contiguous()
+    out = torch.empty((R, Hq, d), dtype=tdt, device="cuda")
+    ctx.fr_sparse_prefill_attn(q_rows, qi, R, k_cache, v_cache, w.L, k_new, v_new, out)
+    ctx.fr_kv_scatter(k_new, v_new, qi, R, k_cache, v_cache, w.L)
+    torch.cuda.synchronize()
+    qi_g = qi.cpu().numpy().astype(np.int64)
+    H.assert_index_set(qi_g, scores_o, k, w.nq)
+    # attention and cache are compared on the index set the GPU chose (identical to the oracle's apart from ties)
+    kc_o, vc_o = np.zeros((w.L, Hkv, d)), np.zeros((w.L, Hkv, d))
+    kc_o[: w.L_ctx], vc_o[: w.L_ctx] = k_ctx_o, w.v_cached
+    want, _ = orc.sparse_prefill_attn(w.q_full[qi_g], qi_g, kc_o, vc_o, w.k_full[qi_g], w.v_full[qi_g])
+    H.assert_close(H.host(out), want, dt, "chained attention")
+    want_k, want_v = orc.kv_scatter(qi_g, w.k_full[qi_g], w.v_full[qi_g], kc_o, vc_o)
+    H.assert_close(H.host(k_cache), want_k, dt, "chained K cache")
+    assert np.array_equal(H.host(v_cache), want_v)
+    ctx.close()
