@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the selective-prefill layer (rope shift -> score/select -> sparse attention -> scatter)
+on one MI355X, on synthetic inputs shaped like the paper's ~17k-token RAG prompts.
+
+A step is one pass of the four C-ABI calls over one prompt, inputs resident in HBM.  Prints ONE JSON
+line: the layer latency (the metric), per-call times measured with events on the launch stream, the
+roofline of the dominant kernel (sparse attention, bf16 matrix cores) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E peak
+
+# HBM traffic of one sparse-attention launch (bytes), from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`
+# runs of this script scaled by a copy kernel of known size; see profiles/.  None until measured.
+MEASURED_ATTN_TRAFFIC = {}
+
+
+def attention_pairs(q_index: np.ndarray) -> int:
+    """Number of (row, key) pairs the method must evaluate per query head: sum over rows of pos + 1."""
+    return int(np.sum(q_index.astype(np.int64) + 1))
+
+
+def cpu_baseline(w, k, sample_rows: int = 384):
+    """The oracle as it stands, on the host cores: the stages that are cheap run in full, the sparse
+    attention on an evenly spaced sample of rows, scaled by the share of (row, key) pairs covered."""
+    from oracle import fusionrag_oracle as orc
+    from paper_2601_12904_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    dt = w.shape.dtype
+    t = {}
+    t0 = time.perf_counter()
+    k_ctx = orc.rope_shift(w.k_cached, w.chunk_offsets, w.src_pos0, None, w.shape.rope_base)
+    t["rope_shift"] = time.perf_counter() - t0
+    k_ctx = synth.round_to_storage(k_ctx, dt)
+    t0 = time.perf_counter()
+    scores = orc.critical_scores(w.q_question, k_ctx, w.chunk_offsets)
+    t["score"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    qi = orc.select_q_index(scores, k, w.nq)
+    t["select"] = time.perf_counter() - t0
+    R = len(qi)
+    kc = np.concatenate([k_ctx, np.zeros((w.nq,) + k_ctx.shape[1:], np.float32)])
+    vc = np.concatenate([w.v_cached, np.zeros((w.nq,) + k_ctx.shape[1:], np.float32)])
+    rows = np.unique(np.linspace(0, R - 1, num=min(sample_rows, R)).round().astype(np.int64))
+    t0 = time.perf_counter()
+    orc.sparse_prefill_attn(w.q_full[qi], qi, kc, vc, w.k_full[qi], w.v_full[qi], rows=rows)
+    t_sample = time.perf_counter() - t0
+    share = len(rows) / R          # the oracle forms every row's logits over all L keys, then masks
+    t["attn_sample"] = t_sample
+    t["attn_scaled"] = t_sample / share
+    t0 = time.perf_counter()
+    orc.kv_scatter(qi, w.k_full[qi], w.v_full[qi], kc, vc)
+    t["scatter"] = time.perf_counter() - t0
+    total = t["rope_shift"] + t["score"] + t["select"] + t["attn_scaled"] + t["scatter"]
+    return {
+        "value": round(total * 1e3, 1), "unit": "ms/layer", "cores": int(cores), "kind": "oracle",
+        "sample": (f"rope shift, scoring, selection and scatter in full; sparse attention on {len(rows)} of {R} rows "
+                   f"evenly spaced over the Q index, scaled by the share of rows ({share * 100:.1f}%)"),
+        "stage_seconds": {a: round(b, 3) for a, b in t.items()},
+    }, qi, scores
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4])
+    ap.add_argument("--ratio", type=float, default=None)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rope-layers", type=int, default=32, help="layers in the batched rope-shift bandwidth run")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); the path has no multi-GPU part")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+
+    from paper_2601_12904_amd import binding as B
+    from paper_2601_12904_amd import synth
+    from tests import harness as H
+
+    torch.cuda.set_device(0)
+    w = synth.CONFIGS[args.config](seed=args.seed) if args.ratio is None else \
+        synth.CONFIGS[args.config](seed=args.seed, ratio=args.ratio)
+    dt, tdt = w.shape.dtype, H.TORCH_DTYPE[w.shape.dtype]
+    Hq, Hkv, d = w.shape.n_q_heads, w.shape.n_kv_heads, w.shape.head_dim
+    e = 2 if dt == "bf16" else 4
+    k = B.fr_topk_count(w.L_ctx, w.ratio)
+    R = k + w.nq
+
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    k_cached = H.dev(w.k_cached, dt)
+    k_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_cache[: w.L_ctx] = H.dev(w.v_cached, dt)
+    q_question = H.dev(w.q_question, dt)
+    qi = torch.empty(R, dtype=torch.int32, device="cuda")
+    out = torch.empty((R, Hq, d), dtype=tdt, device="cuda")
+
+    def step(rows=None, ev=None):
+        ctx.fr_rope_shift(k_cached, k_cache, w.chunk_offsets, w.src_pos0)
+        if ev: ev[1].record()
+        ctx.fr_score_select(q_question, w.nq, k_cache, w.chunk_offsets, k, B.FR_NORM_PER_CHUNK, None, qi)
+        if ev: ev[2].record()
+        if rows is not None:
+            ctx.fr_sparse_prefill_attn(rows[0], qi, R, k_cache, v_cache, w.L, rows[1], rows[2], out)
+            if ev: ev[3].record()
+            ctx.fr_kv_scatter(rows[1], rows[2], qi, R, k_cache, v_cache, w.L)
+            if ev: ev[4].record()
+
+    # The Q index is a function of the inputs alone, so one untimed selection pass fixes which rows the
+    # harness (standing in for the model's QKV projection of the chosen rows) has to provide.
+    step()
+    torch.cuda.synchronize()
+    idx = qi.long()
+    q_full, k_full, v_full = H.dev(w.q_full, dt), H.dev(w.k_full, dt), H.dev(w.v_full, dt)
+    rows = (q_full[idx].contiguous(), k_full[idx].contiguous(), v_full[idx].contiguous())
+    del q_full, k_full, v_full
+    qi_host = qi.cpu().numpy()
+
+    for _ in range(args.warmup):
+        step(rows)
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        evs[s][0].record()
+        step(rows, evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    names = ["rope_shift", "score_select", "sparse_prefill_attn", "kv_scatter"]
+    call_ms = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
+               for i, n in enumerate(names)}
+    assert np.array_equal(qi.cpu().numpy(), qi_host), "the Q index changed between steps"
+
+    # ---- algorithmic work -------------------------------------------------------------------
+    pairs = attention_pairs(qi_host)
+    attn_flops = 4.0 * d * Hq * pairs                      # QK^T and PV, 2 flop per multiply-add
+    attn_tflops = attn_flops / (call_ms["sparse_prefill_attn"] * 1e-3) / 1e12
+    kv_row = Hkv * d * e
+    bytes_rope = 2 * w.L_ctx * kv_row
+    bytes_score = w.L_ctx * kv_row + w.nq * Hq * d * e + 4 * w.L_ctx + 4 * R
+    bytes_scatter = 4 * R * kv_row
+    hbm = {"rope_shift": bytes_rope / (call_ms["rope_shift"] * 1e-3) / 1e9,
+           "score_select": bytes_score / (call_ms["score_select"] * 1e-3) / 1e9,
+           "kv_scatter": bytes_scatter / (call_ms["kv_scatter"] * 1e-3) / 1e9}
+
+    # ---- streaming bandwidth of the position shift over all layers of a request --------------
+    nl = args.rope_layers
+    big_src = torch.randn((nl, w.L_ctx, Hkv, d), device="cuda").to(tdt)
+    big_dst = torch.empty_like(big_src)
+    stride = w.L_ctx * Hkv * d
+    for _ in range(3):
+        ctx.fr_rope_shift(big_src, big_dst, w.chunk_offsets, w.src_pos0, n_batch=nl, src_batch_stride=stride,
+                          dst_batch_stride=stride)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 10
+    a.record()
+    for _ in range(reps):
+        ctx.fr_rope_shift(big_src, big_dst, w.chunk_offsets, w.src_pos0, n_batch=nl, src_batch_stride=stride,
+                          dst_batch_stride=stride)
+    b.record()
+    torch.cuda.synchronize()
+    rope_all_ms = a.elapsed_time(b) / reps
+    rope_all_gbps = nl * bytes_rope / (rope_all_ms * 1e-3) / 1e9
+    del big_src, big_dst
+
+    result = {
+        "metric": "selective-prefill layer latency (ms) + attn TFLOP/s + HBM GB/s, 17k ctx 15% recompute",
+        "value": round(ms_per_step, 4), "unit": "ms/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "config": {"workload": w.name, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "context_tokens": w.L_ctx,
+                   "question_tokens": w.nq, "chunks": w.n_chunks, "recompute_ratio": w.ratio, "selected": k,
+                   "rows": R, "seed": args.seed},
+        "call_ms": {n: round(v, 4) for n, v in call_ms.items()},
+        "attn_tflops": round(attn_tflops, 2),
+        "attn_flops": attn_flops,
+        "hbm_gbps": {n: round(v, 1) for n, v in hbm.items()},
+        "rope_shift_all_layers": {"layers": nl, "ms": round(rope_all_ms, 4), "gbps": round(rope_all_gbps, 1),
+                                  "frac_of_hbm_peak": round(rope_all_gbps / PEAK_HBM_GBPS, 4)},
+        "roofline": {"kernel": "sparse_prefill_attn", "bound": "mfma", "achieved": round(attn_tflops, 2),
+                     "peak": PEAK_BF16_TFLOPS if dt == "bf16" else 157.3, "unit": "TFLOP/s",
+                     "frac": round(attn_tflops / (PEAK_BF16_TFLOPS if dt == "bf16" else 157.3), 4),
+                     "traffic": MEASURED_ATTN_TRAFFIC.get(w.name)},
+    }
+    if not args.no_cpu_baseline:
+        base, qi_o, scores_o = cpu_baseline(w, k)
+        result["cpu_baseline"] = base
+        # the oracle ran on its own shifted keys; the GPU's index may differ inside the tie window only
+        result["index_set_tie_window"] = H.assert_index_set(qi_host.astype(np.int64), scores_o, k, w.nq)
+    print(json.dumps(result))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()
