@@ -267,7 +267,7 @@ fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const
     const bool need_scores = (scores_out != nullptr) || (k > 0 && k < L_ctx);
     if (L_ctx > 0 && need_scores) {
         hipError_t e;
-        if (score_mfma_supported(s) && nq > 0)
+        if (score_mfma_supported(s) && nq > 0 && norm != FR_NORM_RAW)
             e = launch_score_mfma(s, q_question, nq, k_ctx, ct, norm, ctx->ws, scores, hs);
         else
             e = launch_score_simt(s, q_question, nq, k_ctx, ct, norm, ctx->ws, scores, hs);

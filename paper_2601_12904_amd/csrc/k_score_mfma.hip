@@ -1,6 +1,275 @@
+// Query-Guided Selection, critical scores (Sec. 3.2) on the gfx950 matrix cores: bf16, head_dim 128.
+//
+// The score of context token j is the column sum, over all question rows and query heads, of the
+// softmax-normalised attention weights.  A column sum needs every row's normaliser first, so the
+// logits are formed twice (recomputing a 128-deep bf16 product is far cheaper than storing and
+// re-reading nq x Hq x L_ctx fp32 values):
+//   pass A  per (KV head, chunk, 256 query columns): S^T = K Q^T tile by tile, running max / sum per
+//           query column -> base-2 log-sum-exp of the scaled logits, lse2[g][chunk][column]
+//   pass B  per (KV head, 256 keys of one chunk): S = Q K^T over all query columns of the group,
+//           p = exp2(s * c - lse2), summed down the rows -> col_partial[g][key]
+//   reduce  scores[j] = sum over KV heads g of col_partial[g][j], in a fixed order.
+// A "query column" n of KV head g is the pair (question token i = n / G, query head g*G + n % G).
+// Orientation is chosen so that each reduction runs inside a lane: pass A puts keys on the
+// accumulator's register dimension and query columns on lanes; pass B the other way round.
+// All sums run in a fixed order: the scores are reproducible bit for bit.
 #include "fr_internal.hpp"
+
 namespace fr {
-bool score_mfma_supported(const Shape&) { return false; }
-hipError_t launch_score_mfma(const Shape&, const void*, int, const void*, const ChunkTable&, int, const Workspace&,
-                             float*, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int D = 128;
+constexpr int PITCH = D + 8;   // bf16 elements per LDS row (272 B)
+constexpr float NEG_BIG = -1.0e30f;
+
+__device__ __forceinline__ bf16x8 zero8() {
+    bf16x8 z;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.0f;
+    return z;
+}
+
+// ---- pass A -------------------------------------------------------------------------------------
+// grid (query-column tiles of 256, chunk, KV head), 256 threads.
+template <int G>
+__global__ __launch_bounds__(256) void score_lse_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                                                             ChunkTable ct, int nq, int Hq, int Hkv,
+                                                             float scale_log2e, float* __restrict__ lse2) {
+    __shared__ __attribute__((aligned(16))) __bf16 ks_lds[64 * PITCH];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int c = blockIdx.y, g = blockIdx.z;
+    const int c0 = ct.off[c], c1 = ct.off[c + 1];
+    const int NQG = nq * G;
+    const int n_base = (blockIdx.x * 4 + wave) * 64;
+
+    bf16x8 qf[2][8];
+    int col_n[2];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int n = n_base + 32 * nb + x;
+        col_n[nb] = n;
+        const __bf16* qp = q + ((size_t)(n / G) * Hq + g * G + (n % G)) * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = (n < NQG) ? *reinterpret_cast<const bf16x8*>(qp + 16 * ks) : zero8();
+    }
+    float m2[2] = {NEG_BIG, NEG_BIG}, lsum[2] = {0.f, 0.f};
+    const int st_vec = tid & 15, st_key = tid >> 4;
+    const int n_kt = (c1 - c0 + 63) / 64;
+    for (int kt = 0; kt < n_kt; ++kt) {
+        const int key0 = c0 + kt * 64;
+        u32x4 kreg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = key0 + st_key + 16 * i;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            kreg[i] = (j < c1) ? *reinterpret_cast<const u32x4*>(k + ((size_t)j * Hkv + g) * D + 8 * st_vec) : z;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&ks_lds[(st_key + 16 * i) * PITCH + 8 * st_vec]) = kreg[i];
+        __syncthreads();
+
+        f32x16 s[2][2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[mb][nb][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ks_lds[(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s[mb][nb], 0, 0, 0);
+            }
+        if (key0 + 64 > c1) {   // ragged tail of the chunk
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (key0 + 32 * mb + 8 * (v >> 2) + 4 * h + (v & 3) >= c1) s[mb][nb][v] = -INFINITY;
+        }
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            float mx = NEG_BIG;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[mb][nb][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m2[nb], mx * scale_log2e);
+            float psum = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    psum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][nb][v], scale_log2e, -m_new));
+            lsum[nb] = lsum[nb] * __builtin_amdgcn_exp2f(m2[nb] - m_new) + psum;
+            m2[nb] = m_new;
+        }
+    }
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const float l = lsum[nb] + __shfl_xor(lsum[nb], 32);
+        if (h == 0 && col_n[nb] < NQG)
+            lse2[((size_t)g * (ct.n + 1) + c) * NQG + col_n[nb]] = (l > 0.f) ? m2[nb] + __builtin_amdgcn_logf(l) : -INFINITY;
+    }
+}
+
+// Global scope: lse2[g][C][n] = base-2 log-sum-exp over the chunks.  grid (ceil(NQG / 256), Hkv).
+__global__ void score_lse2_global_kernel(int n_chunks, int NQG, float* __restrict__ lse2) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= NQG) return;
+    float* base = lse2 + (size_t)blockIdx.y * (n_chunks + 1) * NQG;
+    float m = -INFINITY;
+    for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, base[(size_t)c * NQG + n]);
+    float l = 0.f;
+    for (int c = 0; c < n_chunks; ++c) {
+        const float v = base[(size_t)c * NQG + n];
+        if (v != -INFINITY) l += exp2f(v - m);
+    }
+    base[(size_t)n_chunks * NQG + n] = m + log2f(l);
+}
+
+// ---- pass B -------------------------------------------------------------------------------------
+// grid (key tiles of 256 inside a chunk, chunk, KV head), 256 threads.  scope_global: use lse2[g][C].
+template <int G>
+__global__ __launch_bounds__(256) void score_colsum_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                                                                ChunkTable ct, int nq, int Hq, int Hkv,
+                                                                float scale_log2e, int scope_global,
+                                                                const float* __restrict__ lse2,
+                                                                float* __restrict__ col_partial) {
+    __shared__ __attribute__((aligned(16))) __bf16 q_lds[64 * PITCH];
+    __shared__ __attribute__((aligned(16))) float lse_lds[64];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int c = blockIdx.y, g = blockIdx.z;
+    const int c0 = ct.off[c], c1 = ct.off[c + 1];
+    const int kbase = c0 + blockIdx.x * 256;
+    if (kbase >= c1) return;
+    const int NQG = nq * G;
+    const int L_ctx = ct.off[ct.n];
+    const float* lrow = lse2 + ((size_t)g * (ct.n + 1) + (scope_global ? ct.n : c)) * NQG;
+
+    bf16x8 kf[2][8];   // B operand: this wave's 64 keys
+    int col_key[2];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int j = kbase + 64 * wave + 32 * nb + x;
+        col_key[nb] = j;
+        const __bf16* kp = k + ((size_t)j * Hkv + g) * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kf[nb][ks] = (j < c1) ? *reinterpret_cast<const bf16x8*>(kp + 16 * ks) : zero8();
+    }
+    float csum[2] = {0.f, 0.f};
+    const int st_vec = tid & 15, st_row = tid >> 4;
+    const int n_qt = (NQG + 63) / 64;
+    for (int qt = 0; qt < n_qt; ++qt) {
+        const int n0 = qt * 64;
+        u32x4 qreg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int n = n0 + st_row + 16 * i;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            qreg[i] = (n < NQG) ? *reinterpret_cast<const u32x4*>(q + ((size_t)(n / G) * Hq + g * G + (n % G)) * D + 8 * st_vec) : z;
+        }
+        float lv = 0.f;
+        if (tid < 64) lv = (n0 + tid < NQG) ? lrow[n0 + tid] : INFINITY;   // rows past the end contribute exp2(-inf) = 0
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&q_lds[(st_row + 16 * i) * PITCH + 8 * st_vec]) = qreg[i];
+        if (tid < 64) lse_lds[tid] = lv;
+        __syncthreads();
+
+        f32x16 s[2][2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[mb][nb][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&q_lds[(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[nb][ks], s[mb][nb], 0, 0, 0);
+            }
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 lz = *reinterpret_cast<const f32x4*>(&lse_lds[32 * mb + 8 * q4 + 4 * h]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                        csum[nb] += __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][nb][4 * q4 + e], scale_log2e, -lz[e]));
+            }
+    }
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const float t = csum[nb] + __shfl_xor(csum[nb], 32);
+        if (h == 0 && col_key[nb] < c1) col_partial[(size_t)g * L_ctx + col_key[nb]] = t;
+    }
+}
+
+__global__ void score_reduce_heads_kernel(const float* __restrict__ col_partial, int L_ctx, int Hkv,
+                                          float* __restrict__ scores) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= L_ctx) return;
+    float t = 0.f;
+    for (int g = 0; g < Hkv; ++g) t += col_partial[(size_t)g * L_ctx + j];
+    scores[j] = t;
+}
+
+template <int G>
+hipError_t run(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct, int norm,
+               const Workspace& ws, float* scores, hipStream_t st) {
+    const int L_ctx = ct.off[ct.n];
+    const float c = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
+    const int NQG = nq * G;
+    int max_len = 0;
+    for (int i = 0; i < ct.n; ++i) max_len = ct.off[i + 1] - ct.off[i] > max_len ? ct.off[i + 1] - ct.off[i] : max_len;
+    score_lse_mfma_kernel<G><<<dim3((NQG + 255) / 256, ct.n, s.Hkv), dim3(256), 0, st>>>(
+        (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, c, ws.lse);
+    if (norm == FR_NORM_GLOBAL)
+        score_lse2_global_kernel<<<dim3((NQG + 255) / 256, s.Hkv), dim3(256), 0, st>>>(ct.n, NQG, ws.lse);
+    score_colsum_mfma_kernel<G><<<dim3((max_len + 255) / 256, ct.n, s.Hkv), dim3(256), 0, st>>>(
+        (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, c, norm == FR_NORM_GLOBAL ? 1 : 0, ws.lse,
+        ws.col_partial);
+    score_reduce_heads_kernel<<<dim3((L_ctx + 255) / 256), dim3(256), 0, st>>>(ws.col_partial, L_ctx, s.Hkv, scores);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool score_mfma_supported(const Shape& s) {
+    return s.dtype == FR_BF16 && s.d == 128 && (s.G == 1 || s.G == 2 || s.G == 4 || s.G == 8);
+}
+
+// Softmax scopes only; the caller routes FR_NORM_RAW to the generic kernels.
+hipError_t launch_score_mfma(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct, int norm,
+                             const Workspace& ws, float* scores, hipStream_t st) {
+    if (ct.off[ct.n] == 0 || nq == 0) return hipSuccess;
+    switch (s.G) {
+        case 1: return run<1>(s, q, nq, k_ctx, ct, norm, ws, scores, st);
+        case 2: return run<2>(s, q, nq, k_ctx, ct, norm, ws, scores, st);
+        case 4: return run<4>(s, q, nq, k_ctx, ct, norm, ws, scores, st);
+        default: return run<8>(s, q, nq, k_ctx, ct, norm, ws, scores, st);
+    }
+}
+
 }  // namespace fr
