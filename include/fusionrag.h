@@ -87,6 +87,14 @@ const char* fr_last_error(const fr_ctx* ctx);
 /* Bytes of device workspace the context holds (0 without a GPU). */
 int64_t fr_workspace_bytes(const fr_ctx* ctx);
 
+/* Tuning / test switches.  FR_OPT_ATTN_SOFTMAX chooses how the tiled bf16 attention kernel keeps exp() in
+ * range: AUTO (default) fixes each row's exponent reference at the maximum over its first 32 visible keys
+ * and recomputes, with a running maximum, only the workgroups whose sums overflowed; RUNNING_MAX uses the
+ * running maximum everywhere.  Both give the same softmax; the option exists so that tests reach both. */
+typedef enum { FR_OPT_ATTN_SOFTMAX = 1 } fr_option;
+typedef enum { FR_ATTN_SOFTMAX_AUTO = 0, FR_ATTN_SOFTMAX_RUNNING_MAX = 1 } fr_attn_softmax;
+fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value);
+
 /* Number of context tokens a recompute ratio selects: floor(ratio * L_ctx + 0.5) clamped to
  * [0, L_ctx].  The ratio counts context tokens; question tokens are always computed (Sec. 4.3).
  * Pure host function. */

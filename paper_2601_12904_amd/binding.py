@@ -19,7 +19,9 @@ FR_NORM_PER_CHUNK, FR_NORM_GLOBAL, FR_NORM_RAW = 0, 1, 2
 FR_MAX_CHUNKS = 256
 STATUS_NAMES = {0: "FR_OK", 1: "FR_ERR_INVALID_ARG", 2: "FR_ERR_UNSUPPORTED", 3: "FR_ERR_WORKSPACE",
                 4: "FR_ERR_DEVICE"}
-EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_topk_count", "fr_rope_shift",
+FR_OPT_ATTN_SOFTMAX = 1
+FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
+EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_topk_count", "fr_rope_shift",
            "fr_score_select", "fr_select_topk", "fr_sparse_prefill_attn", "fr_kv_scatter")
 
 
@@ -57,6 +59,8 @@ def load() -> ctypes.CDLL:
     lib.fr_last_error.restype = ctypes.c_char_p
     lib.fr_workspace_bytes.argtypes = [vp]
     lib.fr_workspace_bytes.restype = i64
+    lib.fr_set_option.argtypes = [vp, i32, i64]
+    lib.fr_set_option.restype = i32
     lib.fr_topk_count.argtypes = [i64, f64]
     lib.fr_topk_count.restype = i64
     lib.fr_rope_shift.argtypes = [vp, vp, vp, pi32, pi32, pi32, i32, i32, i32, i64, i64, vp]
@@ -135,6 +139,9 @@ class Context:
 
     def workspace_bytes(self) -> int:
         return int(self._lib.fr_workspace_bytes(self._h))
+
+    def fr_set_option(self, option: int, value: int):
+        self._check(self._lib.fr_set_option(self._h, int(option), int(value)))
 
     def fr_rope_shift(self, k_src, k_dst, chunk_offsets, chunk_src_pos0, chunk_dst_pos0=None, dst_base: int = 0,
                       n_batch: int = 1, src_batch_stride: int = 0, dst_batch_stride: int = 0, stream=None):

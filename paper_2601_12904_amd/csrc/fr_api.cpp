@@ -132,11 +132,8 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_scores = take((size_t)max_tokens * 4);
     const size_t o_inv = take((size_t)max_tokens * 4);
     const size_t o_sel = take(4096);
-    // split-key partials of the tiled attention kernel: at most two parts per row
-    w.attn_part_o_elems = (size_t)2 * max_tokens * s.Hq * s.d;
-    w.attn_part_ml_elems = (size_t)2 * 2 * max_tokens * s.Hq;
-    const size_t o_po = take(w.attn_part_o_elems * 4);
-    const size_t o_pml = take(w.attn_part_ml_elems * 4);
+    w.attn_flags_elems = (size_t)(max_tokens / 32 + 1) * s.Hkv;   // one per (row tile of >= 32 rows, KV head)
+    const size_t o_flags = take(w.attn_flags_elems * 4);
     w.bytes = off;
     hipError_t e = hipMalloc((void**)&w.base, w.bytes);
     if (e != hipSuccess) {
@@ -149,8 +146,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.scores = (float*)(w.base + o_scores);
     w.inv_index = (int32_t*)(w.base + o_inv);
     w.select_tmp = (uint32_t*)(w.base + o_sel);
-    w.attn_part_o = (float*)(w.base + o_po);
-    w.attn_part_ml = (float*)(w.base + o_pml);
+    w.attn_flags = (int32_t*)(w.base + o_flags);
     ctx->has_device = true;
     *out = ctx;
     return FR_OK;
@@ -165,6 +161,20 @@ void fr_destroy(fr_ctx* ctx) {
 const char* fr_last_error(const fr_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
 int64_t fr_workspace_bytes(const fr_ctx* ctx) { return ctx ? (int64_t)ctx->ws.bytes : 0; }
+
+fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    switch (option) {
+        case FR_OPT_ATTN_SOFTMAX:
+            if (value != FR_ATTN_SOFTMAX_AUTO && value != FR_ATTN_SOFTMAX_RUNNING_MAX)
+                return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_ATTN_SOFTMAX: unknown value %lld", (long long)value);
+            ctx->attn_softmax_mode = (int)value;
+            return FR_OK;
+        default:
+            return fail(ctx, FR_ERR_INVALID_ARG, "unknown option %d", option);
+    }
+}
 
 fr_status fr_rope_shift(fr_ctx* ctx, const void* k_src, void* k_dst, const int32_t* chunk_offsets,
                         const int32_t* chunk_src_pos0, const int32_t* chunk_dst_pos0, int32_t dst_base,
@@ -316,7 +326,8 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
     }
     hipError_t e;
     if (attn_mfma_supported(s))
-        e = launch_attn_mfma(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, ctx->ws, hs);
+        e = launch_attn_mfma(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, ctx->ws,
+                             ctx->attn_softmax_mode, hs);
     else
         e = launch_attn_simt(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, hs);
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);

@@ -39,10 +39,8 @@ struct Workspace {
     float* scores = nullptr;        // [max_tokens]
     int32_t* inv_index = nullptr;   // [max_tokens] position -> row of k_new / -1
     uint32_t* select_tmp = nullptr; // small counters for the selection kernels
-    float* attn_part_o = nullptr;   // split-key partial outputs
-    float* attn_part_ml = nullptr;  // their running max / sum
-    size_t attn_part_o_elems = 0;
-    size_t attn_part_ml_elems = 0;
+    int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
+    size_t attn_flags_elems = 0;
 };
 
 }  // namespace fr
@@ -55,6 +53,7 @@ struct fr_ctx {
     bool has_device = false;
     int device = -1;
     fr::Workspace ws;
+    int attn_softmax_mode = FR_ATTN_SOFTMAX_AUTO;
     std::string err;
 };
 
@@ -86,7 +85,7 @@ bool attn_mfma_supported(const Shape& s);
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R,
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
                             const void* v_new, const int32_t* inv, void* out, float* lse,
-                            const Workspace& ws, hipStream_t st);
+                            const Workspace& ws, int softmax_mode, hipStream_t st);
 
 // ---- element helpers (device) ------------------------------------------------------------
 template <typename T>

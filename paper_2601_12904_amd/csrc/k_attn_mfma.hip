@@ -17,6 +17,13 @@
 // The key order inside every block of 16 keys is permuted identically in P^T and V^T
 // ([0-3, 8-11, 4-7, 12-15]); a contraction does not care about the order of its terms.
 //
+// Softmax.  exp(s - m) / sum exp(s - m) does not depend on m, and fp32 / bf16 leave about 2^127 of
+// headroom, so the fast kernel fixes each query column's reference m once (the maximum over the
+// column's first 32 visible keys) and never rescales: the tile loop holds no maximum, no
+// comparison and no branch.  If a later logit exceeds the reference by more than that headroom
+// the sums overflow to inf; the workgroup then raises a flag, and the safe kernel (classic online
+// softmax with a running maximum) recomputes exactly the flagged workgroups.
+//
 // Stale entries.  Key j is read from k_new/v_new when inv[j] >= 0 (its token is in the Q index)
 // and from the cache otherwise: the cache is never written and stale rows are never read.
 #include "fr_internal.hpp"
@@ -34,13 +41,21 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int D = 128;           // head_dim
 constexpr int KT = 64;           // keys per tile
 constexpr int K_PITCH = D + 8;   // bf16 elements per K row in LDS (272 B: 16-byte reads hit distinct banks)
-constexpr int V_PITCH = KT + 8;  // bf16 elements per V^T row in LDS (144 B)
+constexpr int O_PITCH = D + 8;   // bf16 elements per output row in the epilogue's LDS staging
 constexpr float NEG_BIG = -1.0e30f;
 
-struct __attribute__((aligned(16))) Smem {
-    __bf16 k[KT * K_PITCH];   // [key][d]
-    __bf16 vt[D * V_PITCH];   // [d][key slot]
+struct __attribute__((aligned(16))) Stage {
+    __bf16 k[KT * K_PITCH];   // [key][d], rows padded to 272 B
+    __bf16 vt[D * KT];        // [d][key slot], 128-byte rows, 16-byte chunks XOR-swizzled (see vt_chunk)
 };
+constexpr int N_STAGE = 2;   // tile kt+1 is written (after the barrier that ends tile kt-1) while tile kt is consumed
+constexpr size_t EPILOGUE_LDS = 4 * 64 * O_PITCH * sizeof(__bf16);   // four waves x [64 columns][d] bf16
+
+// V^T rows are exactly 128 bytes (all 32 LDS banks), so both the transposing writes (one lane per 8-dim
+// group, rows 8 apart) and the operand reads (one lane per row, 32 consecutive rows) would pile onto the
+// same banks.  The 16-byte chunk index is therefore XORed with a key that differs between rows 1 apart
+// and between rows 8 apart.
+__device__ __forceinline__ int vt_chunk(int dd, int chunk) { return chunk ^ ((dd ^ (dd >> 3)) & 7); }
 
 __device__ __forceinline__ uint32_t perm_lo(uint32_t a, uint32_t b) {  // (a.lo16, b.lo16) -> a in low half
     return __builtin_amdgcn_perm(b, a, 0x05040100u);
@@ -49,102 +64,83 @@ __device__ __forceinline__ uint32_t perm_hi(uint32_t a, uint32_t b) {  // (a.hi1
     return __builtin_amdgcn_perm(b, a, 0x07060302u);
 }
 
-// G = query heads per KV head.  grid.x = n_row_tiles * Hkv.
+// ---- what a lane knows about its workgroup, wave and two query columns ---------------------------
 template <int G>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const __bf16* __restrict__ q_rows,
-                                                        const int32_t* __restrict__ q_index, int R,
-                                                        const __bf16* __restrict__ k_cache,
-                                                        const __bf16* __restrict__ v_cache, int L,
-                                                        const __bf16* __restrict__ k_new,
-                                                        const __bf16* __restrict__ v_new,
-                                                        const int32_t* __restrict__ inv, __bf16* __restrict__ out,
-                                                        float* __restrict__ lse_out, int Hq, int Hkv, int n_row_tiles,
-                                                        float scale_log2e) {
-    constexpr int TRW = 64 / G;   // token rows per wave
-    constexpr int TR = 4 * TRW;   // token rows per workgroup
-    __shared__ Smem sm;
-
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int x = lane & 31, h = lane >> 5;
-    const int g = blockIdx.x % Hkv;                             // consecutive blocks land on different XCDs
-    const int tile = n_row_tiles - 1 - (int)(blockIdx.x / Hkv);  // longest tiles first
-    const int row0 = tile * TR;
-
-    // ---- this lane's two query columns (one per 32-wide N block) ---------------------------------
+struct Geometry {
+    static constexpr int TRW = 64 / G;   // token rows per wave
+    static constexpr int TR = 4 * TRW;   // token rows per workgroup
+    int g, tile, row0;
+    int x, h, wave;
     int col_row[2], col_head[2], col_pos[2];
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const int col = 32 * nb + x;
-        const int r = row0 + wave * TRW + (col % TRW);
-        col_row[nb] = r;
-        col_head[nb] = g * G + col / TRW;
-        col_pos[nb] = (r < R) ? q_index[r] : -1;
-    }
-    const int last_row = min(R, row0 + TR) - 1;
-    const int p_max = q_index[last_row];                        // rows ascend: the tile's furthest key
-    const int w_first = row0 + wave * TRW, w_last = min(R, w_first + TRW) - 1;
-    const int wp_min = (w_first < R) ? q_index[w_first] : -1;   // every key <= wp_min is visible to the whole wave
-    const int wp_max = (w_first < R) ? q_index[w_last] : -1;    // no key > wp_max is visible to any of its rows
-    const int n_kt = p_max / KT + 1;
+    int wp_max;    // no key beyond it is visible to any row of this wave
+    int n_kt;      // key tiles the workgroup walks
+    int n_plain;   // leading tiles whose keys are visible to every row of the workgroup
 
-    // ---- Q fragments: B operand of S^T = K Q^T, kept in registers for the whole loop -------------
-    bf16x8 qf[2][8];
+    __device__ __forceinline__ void init(const int32_t* __restrict__ q_index, int R, int Hkv, int n_row_tiles) {
+        const int tid = threadIdx.x, lane = tid & 63;
+        wave = tid >> 6;
+        x = lane & 31;
+        h = lane >> 5;
+        g = blockIdx.x % Hkv;                               // consecutive blocks land on different XCDs
+        tile = n_row_tiles - 1 - (int)(blockIdx.x / Hkv);   // longest tiles first
+        row0 = tile * TR;
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const __bf16* qp = q_rows + ((size_t)col_row[nb] * Hq + col_head[nb]) * D + 8 * h;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            if (col_row[nb] < R) {
-                qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) qf[nb][ks][e] = (__bf16)0.0f;
-            }
+        for (int nb = 0; nb < 2; ++nb) {
+            const int col = 32 * nb + x;
+            const int r = row0 + wave * TRW + (col % TRW);
+            col_row[nb] = r;                                 // rows past the end compute a copy of the last
+            col_head[nb] = g * G + col / TRW;                // row and are never stored
+            col_pos[nb] = q_index[min(r, R - 1)];
         }
+        const int p_first = q_index[row0];                   // rows ascend: every key <= p_first is visible to all
+        const int p_max = q_index[min(R, row0 + TR) - 1];    // the workgroup's furthest key
+        wp_max = q_index[min(row0 + wave * TRW + TRW, R) - 1];   // a wave past the end copies the last row
+        n_kt = p_max / KT + 1;
+        n_plain = min((p_first + 1) / KT, n_kt - 1);
     }
+};
 
-    f32x16 o[4][2];
-#pragma unroll
-    for (int md = 0; md < 4; ++md)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
-    float m2[2] = {NEG_BIG, NEG_BIG};   // running max of the scaled (log2 domain) logits, per column
-    float lsum[2] = {0.f, 0.f};         // this lane's share of the running denominator
+// ---- staging: global -> registers -> LDS ------------------------------------------------------------
+// Loads never branch: a key past the end of the cache is clamped to the last row (it lies beyond every
+// row's position, so the causal mask removes it), and the cache / fresh-row choice is a pointer select.
+template <bool HAS_NEW>
+struct Stager {
+    const __bf16 *k_cache, *v_cache, *k_new, *v_new;
+    const int32_t* inv;
+    int L, Hkv, g;
+    int st_vec, st_key, kslot;
+    u32x4 kreg[4], vreg[4];
 
-    // staging assignments
-    const int st_vec = tid & 15;            // 16-byte vector within a 256-byte head row
-    const int st_key = tid >> 4;            // K: keys st_key + 16 i;  V: key group st_key (4 keys)
-    const int kslot = 16 * (st_key >> 2) + 4 * ((0x3120 >> (4 * (st_key & 3))) & 3);  // permuted slot of key 4*st_key
-
-    for (int kt = 0; kt < n_kt; ++kt) {
+    __device__ __forceinline__ void init(const __bf16* kc, const __bf16* vc, const __bf16* kn, const __bf16* vn,
+                                         const int32_t* iv, int L_, int Hkv_, int g_) {
+        k_cache = kc; v_cache = vc; k_new = kn; v_new = vn; inv = iv; L = L_; Hkv = Hkv_; g = g_;
+        st_vec = threadIdx.x & 15;   // 16-byte vector within a 256-byte head row
+        st_key = threadIdx.x >> 4;   // K: keys st_key + 16 i;  V: key group st_key (4 consecutive keys)
+        kslot = 16 * (st_key >> 2) + 4 * ((0x3120 >> (4 * (st_key & 3))) & 3);   // permuted slot of key 4*st_key
+    }
+    __device__ __forceinline__ void load(int kt) {
         const int key0 = kt * KT;
-        // ---- stage K [key][d] and V^T [d][slot] ------------------------------------------------
-        u32x4 kreg[4], vreg[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int jk = key0 + st_key + 16 * i;
-            const int jv = key0 + 4 * st_key + i;
-            u32x4 zk = {0u, 0u, 0u, 0u};
-            kreg[i] = zk;
-            vreg[i] = zk;
-            if (jk < L) {
-                const int rr = inv ? inv[jk] : -1;
-                const __bf16* p = (rr >= 0) ? k_new + ((size_t)rr * Hkv + g) * D : k_cache + ((size_t)jk * Hkv + g) * D;
-                kreg[i] = *reinterpret_cast<const u32x4*>(p + 8 * st_vec);
+            const int jk = min(key0 + st_key + 16 * i, L - 1);
+            const int jv = min(key0 + 4 * st_key + i, L - 1);
+            const __bf16* pk = k_cache + ((size_t)jk * Hkv + g) * D;
+            const __bf16* pv = v_cache + ((size_t)jv * Hkv + g) * D;
+            if (HAS_NEW) {
+                const int rk = inv[jk], rv = inv[jv];
+                const __bf16* nk = k_new + ((size_t)max(rk, 0) * Hkv + g) * D;
+                const __bf16* nv = v_new + ((size_t)max(rv, 0) * Hkv + g) * D;
+                pk = (rk >= 0) ? nk : pk;
+                pv = (rv >= 0) ? nv : pv;
             }
-            if (jv < L) {
-                const int rr = inv ? inv[jv] : -1;
-                const __bf16* p = (rr >= 0) ? v_new + ((size_t)rr * Hkv + g) * D : v_cache + ((size_t)jv * Hkv + g) * D;
-                vreg[i] = *reinterpret_cast<const u32x4*>(p + 8 * st_vec);
-            }
+            kreg[i] = *reinterpret_cast<const u32x4*>(pk + 8 * st_vec);
+            vreg[i] = *reinterpret_cast<const u32x4*>(pv + 8 * st_vec);
         }
-        __syncthreads();   // previous tile fully consumed
+    }
+    __device__ __forceinline__ void write(Stage& st) const {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<u32x4*>(&sm.k[(st_key + 16 * i) * K_PITCH + 8 * st_vec]) = kreg[i];
+            *reinterpret_cast<u32x4*>(&st.k[(st_key + 16 * i) * K_PITCH + 8 * st_vec]) = kreg[i];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {   // dims 8*st_vec + 2c, +2c+1: gather the 4 keys of each
             u32x2 lo, hi;
@@ -152,108 +148,329 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const __bf16* __restrict
             lo[1] = perm_lo(vreg[2][c], vreg[3][c]);
             hi[0] = perm_hi(vreg[0][c], vreg[1][c]);
             hi[1] = perm_hi(vreg[2][c], vreg[3][c]);
-            *reinterpret_cast<u32x2*>(&sm.vt[(8 * st_vec + 2 * c) * V_PITCH + kslot]) = lo;
-            *reinterpret_cast<u32x2*>(&sm.vt[(8 * st_vec + 2 * c + 1) * V_PITCH + kslot]) = hi;
+            const int d0 = 8 * st_vec + 2 * c, d1 = d0 + 1;
+            *reinterpret_cast<u32x2*>(&st.vt[d0 * KT + 8 * vt_chunk(d0, kslot >> 3) + (kslot & 4)]) = lo;
+            *reinterpret_cast<u32x2*>(&st.vt[d1 * KT + 8 * vt_chunk(d1, kslot >> 3) + (kslot & 4)]) = hi;
         }
-        __syncthreads();
+    }
+};
 
-        if (key0 <= wp_max) {   // otherwise nothing in this tile is visible to this wave
-            // ---- S^T = K Q^T -------------------------------------------------------------------
-            f32x16 s[2][2];
+// S^T for 32 keys (half mb of a staged tile) against this wave's 64 query columns.
+__device__ __forceinline__ void qk_half(const Stage& st, int mb, const bf16x8 (&qf)[2][8], int x, int h, f32x16 (&s)[2]) {
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+    for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
+        for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) s[mb][nb][v] = 0.f;
+    for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&st.k[(32 * mb + x) * K_PITCH + 16 * ks + 8 * h]);
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+        for (int nb = 0; nb < 2; ++nb) s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s[nb], 0, 0, 0);
+    }
+}
+
+template <bool MASK>
+__device__ __forceinline__ void mask_half(f32x16 (&s)[2], const int (&col_pos)[2], int key_base, int h) {
+    if (!MASK) return;
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sm.k[(32 * mb + x) * K_PITCH + 16 * ks + 8 * h]);
+    for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                    for (int nb = 0; nb < 2; ++nb)
-                        s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s[mb][nb], 0, 0, 0);
-                }
+        for (int v = 0; v < 16; ++v) {
+            const int key = key_base + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (key > col_pos[nb]) s[nb][v] = -INFINITY;
+        }
+}
+
+// O^T += V^T P^T for the 32 keys of half mb.
+__device__ __forceinline__ void pv_half(const Stage& st, int mb, const bf16x8 (&pf)[2][2], int x, int h, f32x16 (&o)[4][2]) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const int kb = 2 * mb + kk;
+#pragma unroll
+        for (int md = 0; md < 4; ++md) {
+            const int dd = 32 * md + x;
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&st.vt[dd * KT + 8 * vt_chunk(dd, 2 * kb + h)]);
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) o[md][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nb][kk], o[md][nb], 0, 0, 0);
+        }
+    }
+}
+
+// One staged tile with a fixed exponent reference per column: no maximum, no rescale.
+template <bool MASK>
+__device__ __forceinline__ void tile_fixed_ref(const Stage& st, const bf16x8 (&qf)[2][8], f32x16 (&o)[4][2],
+                                               float (&lsum)[2], const float (&mref)[2], const int (&col_pos)[2],
+                                               int key0, int x, int h, float scale_log2e) {
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+        f32x16 s[2];
+        qk_half(st, mb, qf, x, h, s);
+        mask_half<MASK>(s, col_pos, key0 + 32 * mb, h);
+        bf16x8 pf[2][2];   // P^T as B operand: [nb][16-key block of this half]
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            float psum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nb][v], scale_log2e, -mref[nb]));
+                psum += p;
+                pf[nb][v >> 3][v & 7] = (__bf16)p;
             }
-            // ---- causal mask by position (only tiles that reach past the wave's first row) ------
-            if (key0 + KT - 1 > wp_min) {
+            lsum[nb] += psum;
+        }
+        pv_half(st, mb, pf, x, h, o);
+    }
+}
+
+// Normalise, transpose through LDS and store 16 bytes per lane; lse = (m + log2 l) ln 2.
+template <int G>
+__device__ __forceinline__ void store_output(const Geometry<G>& ge, f32x16 (&o)[4][2], const float (&l)[2],
+                                             const float (&mref)[2], int R, int Hq, unsigned char* smem,
+                                             __bf16* __restrict__ out, float* __restrict__ lse_out) {
+    constexpr int TRW = Geometry<G>::TRW;
+    __bf16* ob = reinterpret_cast<__bf16*>(smem) + ge.wave * 64 * O_PITCH;   // this wave's [64 columns][d]
+    const int lane = threadIdx.x & 63;
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
+    for (int nb = 0; nb < 2; ++nb) {
+        const float inv_l = 1.0f / l[nb];
 #pragma unroll
-                    for (int nb = 0; nb < 2; ++nb)
+        for (int md = 0; md < 4; ++md)
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int key = key0 + 32 * mb + 8 * (v >> 2) + 4 * h + (v & 3);
-                            if (key > col_pos[nb]) s[mb][nb][v] = -INFINITY;
-                        }
+            for (int q4 = 0; q4 < 4; ++q4) {
+                bf16x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[md][nb][4 * q4 + e] * inv_l);
+                *reinterpret_cast<bf16x4*>(&ob[(32 * nb + ge.x) * O_PITCH + 32 * md + 8 * q4 + 4 * ge.h]) = w;
             }
-            // ---- online softmax per query column -------------------------------------------------
-            bf16x8 pf[2][4];   // P^T as B operand: [nb][16-key block]
+        if (lse_out != nullptr && ge.h == 0 && ge.col_row[nb] < R)
+            lse_out[(size_t)ge.col_row[nb] * Hq + ge.col_head[nb]] =
+                (mref[nb] + __builtin_amdgcn_logf(l[nb])) * 0.6931471805599453f;
+    }
+    __syncthreads();   // (each wave reads back only its own region; the barrier orders its LDS writes and reads)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int col = 4 * i + (lane >> 4), vec = lane & 15;
+        const int r = ge.row0 + ge.wave * TRW + (col % TRW);
+        if (r < R) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(&ob[col * O_PITCH + 8 * vec]);
+            *reinterpret_cast<u32x4*>(out + ((size_t)r * Hq + ge.g * G + col / TRW) * D + 8 * vec) = w;
+        }
+    }
+}
+
+// ---- fast kernel ---------------------------------------------------------------------------------
+// grid.x = n_row_tiles * Hkv.  Dynamic LDS: the larger of N_STAGE stages and the epilogue's staging.
+template <int G, bool HAS_NEW>
+__global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __restrict__ q_rows,
+                                                             const int32_t* __restrict__ q_index, int R,
+                                                             const __bf16* __restrict__ k_cache,
+                                                             const __bf16* __restrict__ v_cache, int L,
+                                                             const __bf16* __restrict__ k_new,
+                                                             const __bf16* __restrict__ v_new,
+                                                             const int32_t* __restrict__ inv, __bf16* __restrict__ out,
+                                                             float* __restrict__ lse_out, int32_t* __restrict__ redo_flags,
+                                                             int Hq, int Hkv, int n_row_tiles, float scale_log2e) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    Stage* stages = reinterpret_cast<Stage*>(smem_raw);
+    Geometry<G> ge;
+    ge.init(q_index, R, Hkv, n_row_tiles);
+    const int x = ge.x, h = ge.h;
+
+    // Q fragments: B operand of S^T = K Q^T, kept in registers for the whole loop
+    bf16x8 qf[2][8];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const __bf16* qp = q_rows + ((size_t)min(ge.col_row[nb], R - 1) * Hq + ge.col_head[nb]) * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    }
+    f32x16 o[4][2];
+#pragma unroll
+    for (int md = 0; md < 4; ++md)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
+    float lsum[2] = {0.f, 0.f};
+
+    Stager<HAS_NEW> sg;
+    sg.init(k_cache, v_cache, k_new, v_new, inv, L, Hkv, ge.g);
+    sg.load(0);
+    sg.write(stages[0]);
+    if (ge.n_kt > 1) sg.load(1);
+    __syncthreads();
+
+    // exponent reference of each column: the maximum over its visible keys among the first 32
+    float mref[2];
+    {
+        f32x16 s[2];
+        qk_half(stages[0], 0, qf, x, h, s);
+        mask_half<true>(s, ge.col_pos, 0, h);
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            float t = s[nb][0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) t = fmaxf(t, s[nb][v]);
+            t = fmaxf(t, __shfl_xor(t, 32));
+            mref[nb] = t * scale_log2e;
+        }
+    }
+
+    // Tile loop: after the barrier that ends tile kt-1, tile kt+1 moves from registers to the free LDS stage,
+    // the loads of tile kt+2 are issued, and tile kt is consumed: one barrier per tile, two stages.
+    int kt = 0, buf = 0;   // buf = kt % N_STAGE
+    for (; kt < ge.n_plain; ++kt) {   // plain tiles: every key visible to every row, a next tile always exists
+        const int nbuf = (buf + 1 == N_STAGE) ? 0 : buf + 1;
+        if (kt > 0) __syncthreads();
+        sg.write(stages[nbuf]);
+        if (kt + 2 < ge.n_kt) sg.load(kt + 2);
+        tile_fixed_ref<false>(stages[buf], qf, o, lsum, mref, ge.col_pos, kt * KT, x, h, scale_log2e);
+        buf = nbuf;
+    }
+    for (; kt < ge.n_kt; ++kt) {      // tiles that cross some row's own position
+        const int nbuf = (buf + 1 == N_STAGE) ? 0 : buf + 1;
+        if (kt > 0) __syncthreads();
+        if (kt + 1 < ge.n_kt) {
+            sg.write(stages[nbuf]);
+            if (kt + 2 < ge.n_kt) sg.load(kt + 2);
+        }
+        if (kt * KT <= ge.wp_max)
+            tile_fixed_ref<true>(stages[buf], qf, o, lsum, mref, ge.col_pos, kt * KT, x, h, scale_log2e);
+        buf = nbuf;
+    }
+
+    // overflow check: with a fixed reference a runaway logit shows up as inf / nan in the sums
+    float l[2];
+    bool bad = false;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        l[nb] = lsum[nb] + __shfl_xor(lsum[nb], 32);
+        float chk = l[nb];
+#pragma unroll
+        for (int md = 0; md < 4; ++md)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) chk += fabsf(o[md][nb][v]);
+        bad = bad || !(chk < INFINITY) || !(l[nb] > 0.f);
+    }
+    const int any_bad = __syncthreads_or(bad ? 1 : 0);   // also: every wave is done with the stages
+    if (threadIdx.x == 0) redo_flags[blockIdx.x] = any_bad;
+    if (any_bad) return;
+    store_output<G>(ge, o, l, mref, R, Hq, smem_raw, out, lse_out);
+}
+
+// ---- safe kernel: classic online softmax, runs only where the fast kernel raised its flag ----------
+template <int G, bool HAS_NEW>
+__global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __restrict__ q_rows,
+                                                               const int32_t* __restrict__ q_index, int R,
+                                                               const __bf16* __restrict__ k_cache,
+                                                               const __bf16* __restrict__ v_cache, int L,
+                                                               const __bf16* __restrict__ k_new,
+                                                               const __bf16* __restrict__ v_new,
+                                                               const int32_t* __restrict__ inv, __bf16* __restrict__ out,
+                                                               float* __restrict__ lse_out,
+                                                               const int32_t* __restrict__ redo_flags, int Hq, int Hkv,
+                                                               int n_row_tiles, float scale_log2e) {
+    if (redo_flags != nullptr && redo_flags[blockIdx.x] == 0) return;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    Stage* stages = reinterpret_cast<Stage*>(smem_raw);
+    Geometry<G> ge;
+    ge.init(q_index, R, Hkv, n_row_tiles);
+    const int x = ge.x, h = ge.h;
+    bf16x8 qf[2][8];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const __bf16* qp = q_rows + ((size_t)min(ge.col_row[nb], R - 1) * Hq + ge.col_head[nb]) * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    }
+    f32x16 o[4][2];
+#pragma unroll
+    for (int md = 0; md < 4; ++md)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
+    float lsum[2] = {0.f, 0.f};
+    float m2[2] = {NEG_BIG, NEG_BIG};
+    Stager<HAS_NEW> sg;
+    sg.init(k_cache, v_cache, k_new, v_new, inv, L, Hkv, ge.g);
+    for (int kt = 0; kt < ge.n_kt; ++kt) {
+        sg.load(kt);
+        __syncthreads();
+        sg.write(stages[0]);
+        __syncthreads();
+        if (kt * KT > ge.wp_max) continue;   // wave-uniform; the barriers stay outside
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            f32x16 s[2];
+            qk_half(stages[0], mb, qf, x, h, s);
+            mask_half<true>(s, ge.col_pos, kt * KT + 32 * mb, h);
+            bf16x8 pf[2][2];
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
-                float mx = NEG_BIG;
+                float t = s[nb][0];
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[mb][nb][v]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m2[nb], mx * scale_log2e);
+                for (int v = 1; v < 16; ++v) t = fmaxf(t, s[nb][v]);
+                t = fmaxf(t, __shfl_xor(t, 32));
+                const float m_new = fmaxf(m2[nb], t * scale_log2e);
                 const float alpha = __builtin_amdgcn_exp2f(m2[nb] - m_new);
                 m2[nb] = m_new;
                 float psum = 0.f;
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][nb][v], scale_log2e, -m_new));
-                        s[mb][nb][v] = p;
-                        psum += p;
-                    }
+                for (int v = 0; v < 16; ++v) {
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nb][v], scale_log2e, -m_new));
+                    psum += p;
+                    pf[nb][v >> 3][v & 7] = (__bf16)p;
+                }
                 lsum[nb] = lsum[nb] * alpha + psum;
 #pragma unroll
                 for (int md = 0; md < 4; ++md)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[md][nb][v] *= alpha;
-#pragma unroll
-                for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[nb][kb][e] = (__bf16)s[kb >> 1][nb][8 * (kb & 1) + e];
             }
-            // ---- O^T += V^T P^T ------------------------------------------------------------------
-#pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
-#pragma unroll
-                for (int md = 0; md < 4; ++md) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sm.vt[(32 * md + x) * V_PITCH + 16 * kb + 8 * h]);
-#pragma unroll
-                    for (int nb = 0; nb < 2; ++nb)
-                        o[md][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nb][kb], o[md][nb], 0, 0, 0);
-                }
-            }
+            pv_half(stages[0], mb, pf, x, h, o);
         }
     }
+    float l[2];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) l[nb] = lsum[nb] + __shfl_xor(lsum[nb], 32);
+    __syncthreads();
+    store_output<G>(ge, o, l, m2, R, Hq, smem_raw, out, lse_out);
+}
 
-    // ---- epilogue: normalise and store ---------------------------------------------------------
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const float l = lsum[nb] + __shfl_xor(lsum[nb], 32);
-        if (col_row[nb] < R) {
-            const float inv_l = 1.0f / l;
-            __bf16* op = out + ((size_t)col_row[nb] * Hq + col_head[nb]) * D;
-#pragma unroll
-            for (int md = 0; md < 4; ++md)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    bf16x4 w;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[md][nb][4 * q4 + e] * inv_l);
-                    *reinterpret_cast<bf16x4*>(op + 32 * md + 8 * q4 + 4 * h) = w;
-                }
-            if (lse_out != nullptr && h == 0)
-                lse_out[(size_t)col_row[nb] * Hq + col_head[nb]] = (m2[nb] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
-        }
+template <int G, bool HAS_NEW>
+hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
+                  const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
+                  float* lse, const Workspace& ws, int mode, hipStream_t st) {
+    const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
+    constexpr int TR = Geometry<G>::TR;
+    const int n_row_tiles = (R + TR - 1) / TR;
+    const size_t lds_fast = N_STAGE * sizeof(Stage) > EPILOGUE_LDS ? N_STAGE * sizeof(Stage) : EPILOGUE_LDS;
+    const size_t lds_safe = sizeof(Stage) > EPILOGUE_LDS ? sizeof(Stage) : EPILOGUE_LDS;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, HAS_NEW>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_running_max_kernel<G, HAS_NEW>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_safe);
+        if (e != hipSuccess) return e;
+        attr_set = true;
     }
+    dim3 grid(n_row_tiles * s.Hkv), block(256);
+    if ((size_t)grid.x > ws.attn_flags_elems) return hipErrorInvalidValue;
+    const int32_t* flags = ws.attn_flags;
+    if (mode != FR_ATTN_SOFTMAX_RUNNING_MAX)
+        attn_fixed_ref_kernel<G, HAS_NEW><<<grid, block, lds_fast, st>>>(
+            (const __bf16*)q_rows, q_index, R, (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L,
+            (const __bf16*)k_new, (const __bf16*)v_new, inv, (__bf16*)out, lse, ws.attn_flags, s.Hq, s.Hkv, n_row_tiles,
+            scale_log2e);
+    else
+        flags = nullptr;   // recompute every workgroup with the running maximum
+    attn_running_max_kernel<G, HAS_NEW><<<grid, block, lds_safe, st>>>(
+        (const __bf16*)q_rows, q_index, R, (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new,
+        (const __bf16*)v_new, inv, (__bf16*)out, lse, flags, s.Hq, s.Hkv, n_row_tiles, scale_log2e);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -264,26 +481,19 @@ bool attn_mfma_supported(const Shape& s) {
 
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                             const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv,
-                            void* out, float* lse, const Workspace& ws, hipStream_t st) {
-    (void)ws;
+                            void* out, float* lse, const Workspace& ws, int mode, hipStream_t st) {
     if (R == 0) return hipSuccess;
-    const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
-    const int TR = 4 * (64 / s.G);
-    const int n_row_tiles = (R + TR - 1) / TR;
-    dim3 grid(n_row_tiles * s.Hkv), block(256);
-#define FR_LAUNCH(GG)                                                                                             \
-    attn_mfma_kernel<GG><<<grid, block, 0, st>>>((const __bf16*)q_rows, q_index, R, (const __bf16*)k_cache,      \
-                                                 (const __bf16*)v_cache, (int)L, (const __bf16*)k_new,           \
-                                                 (const __bf16*)v_new, inv, (__bf16*)out, lse, s.Hq, s.Hkv,      \
-                                                 n_row_tiles, scale_log2e)
+#define FR_GO(GG)                                                                                                    \
+    return (k_new != nullptr)                                                                                        \
+               ? launch<GG, true>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st) \
+               : launch<GG, false>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st)
     switch (s.G) {
-        case 1: FR_LAUNCH(1); break;
-        case 2: FR_LAUNCH(2); break;
-        case 4: FR_LAUNCH(4); break;
-        default: FR_LAUNCH(8); break;
+        case 1: FR_GO(1);
+        case 2: FR_GO(2);
+        case 4: FR_GO(4);
+        default: FR_GO(8);
     }
-#undef FR_LAUNCH
-    return hipGetLastError();
+#undef FR_GO
 }
 
 }  // namespace fr
