@@ -48,7 +48,11 @@ struct __attribute__((aligned(16))) Stage {
     __bf16 k[KT * K_PITCH];   // [key][d], rows padded to 272 B
     __bf16 vt[D * KT];        // [d][key slot], 128-byte rows, 16-byte chunks XOR-swizzled (see vt_chunk)
 };
-constexpr int N_STAGE = 2;   // tile kt+1 is written (after the barrier that ends tile kt-1) while tile kt is consumed
+// The fast kernel keeps separate rings of three K tiles and three V^T tiles (see its tile loop).
+struct __attribute__((aligned(16))) Rings {
+    __bf16 k[3][KT * K_PITCH];
+    __bf16 vt[3][D * KT];
+};
 constexpr size_t EPILOGUE_LDS = 4 * 64 * O_PITCH * sizeof(__bf16);   // four waves x [64 columns][d] bf16
 
 // V^T rows are exactly 128 bytes (all 32 LDS banks), so both the transposing writes (one lane per 8-dim
@@ -118,29 +122,54 @@ struct Stager {
         st_key = threadIdx.x >> 4;   // K: keys st_key + 16 i;  V: key group st_key (4 consecutive keys)
         kslot = 16 * (st_key >> 2) + 4 * ((0x3120 >> (4 * (st_key & 3))) & 3);   // permuted slot of key 4*st_key
     }
-    __device__ __forceinline__ void load(int kt) {
+    // The position -> fresh-row map is read one step ahead of the rows themselves (fetch_inv_* for tile kt+1
+    // right after load_* of tile kt), so that a row load never waits on the lookup that addresses it.
+    int inv_k[4], inv_v[4];
+    __device__ __forceinline__ void fetch_inv_k(int kt) {
+        if (!HAS_NEW) return;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) inv_k[i] = inv[min(kt * KT + st_key + 16 * i, L - 1)];
+    }
+    __device__ __forceinline__ void fetch_inv_v(int kt) {
+        if (!HAS_NEW) return;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) inv_v[i] = inv[min(kt * KT + 4 * st_key + i, L - 1)];
+    }
+    __device__ __forceinline__ void load_k(int kt) {   // needs fetch_inv_k(kt) before
         const int key0 = kt * KT;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int jk = min(key0 + st_key + 16 * i, L - 1);
-            const int jv = min(key0 + 4 * st_key + i, L - 1);
             const __bf16* pk = k_cache + ((size_t)jk * Hkv + g) * D;
-            const __bf16* pv = v_cache + ((size_t)jv * Hkv + g) * D;
             if (HAS_NEW) {
-                const int rk = inv[jk], rv = inv[jv];
+                const int rk = inv_k[i];
                 const __bf16* nk = k_new + ((size_t)max(rk, 0) * Hkv + g) * D;
-                const __bf16* nv = v_new + ((size_t)max(rv, 0) * Hkv + g) * D;
                 pk = (rk >= 0) ? nk : pk;
-                pv = (rv >= 0) ? nv : pv;
             }
             kreg[i] = *reinterpret_cast<const u32x4*>(pk + 8 * st_vec);
+        }
+    }
+    __device__ __forceinline__ void load_v(int kt) {   // needs fetch_inv_v(kt) before
+        const int key0 = kt * KT;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int jv = min(key0 + 4 * st_key + i, L - 1);
+            const __bf16* pv = v_cache + ((size_t)jv * Hkv + g) * D;
+            if (HAS_NEW) {
+                const int rv = inv_v[i];
+                const __bf16* nv = v_new + ((size_t)max(rv, 0) * Hkv + g) * D;
+                pv = (rv >= 0) ? nv : pv;
+            }
             vreg[i] = *reinterpret_cast<const u32x4*>(pv + 8 * st_vec);
         }
     }
-    __device__ __forceinline__ void write(Stage& st) const {
+    __device__ __forceinline__ void load(int kt) { fetch_inv_k(kt); fetch_inv_v(kt); load_k(kt); load_v(kt); }
+    __device__ __forceinline__ void write_k(__bf16* k) const {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<u32x4*>(&st.k[(st_key + 16 * i) * K_PITCH + 8 * st_vec]) = kreg[i];
+            *reinterpret_cast<u32x4*>(&k[(st_key + 16 * i) * K_PITCH + 8 * st_vec]) = kreg[i];
+    }
+    __device__ __forceinline__ void write_v(__bf16* vt) const {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {   // dims 8*st_vec + 2c, +2c+1: gather the 4 keys of each
             u32x2 lo, hi;
@@ -149,21 +178,22 @@ struct Stager {
             hi[0] = perm_hi(vreg[0][c], vreg[1][c]);
             hi[1] = perm_hi(vreg[2][c], vreg[3][c]);
             const int d0 = 8 * st_vec + 2 * c, d1 = d0 + 1;
-            *reinterpret_cast<u32x2*>(&st.vt[d0 * KT + 8 * vt_chunk(d0, kslot >> 3) + (kslot & 4)]) = lo;
-            *reinterpret_cast<u32x2*>(&st.vt[d1 * KT + 8 * vt_chunk(d1, kslot >> 3) + (kslot & 4)]) = hi;
+            *reinterpret_cast<u32x2*>(&vt[d0 * KT + 8 * vt_chunk(d0, kslot >> 3) + (kslot & 4)]) = lo;
+            *reinterpret_cast<u32x2*>(&vt[d1 * KT + 8 * vt_chunk(d1, kslot >> 3) + (kslot & 4)]) = hi;
         }
     }
+    __device__ __forceinline__ void write(Stage& st) const { write_k(st.k); write_v(st.vt); }
 };
 
 // S^T for 32 keys (half mb of a staged tile) against this wave's 64 query columns.
-__device__ __forceinline__ void qk_half(const Stage& st, int mb, const bf16x8 (&qf)[2][8], int x, int h, f32x16 (&s)[2]) {
+__device__ __forceinline__ void qk_half(const __bf16* k, int mb, const bf16x8 (&qf)[2][8], int x, int h, f32x16 (&s)[2]) {
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&st.k[(32 * mb + x) * K_PITCH + 16 * ks + 8 * h]);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&k[(32 * mb + x) * K_PITCH + 16 * ks + 8 * h]);
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s[nb], 0, 0, 0);
     }
@@ -182,44 +212,78 @@ __device__ __forceinline__ void mask_half(f32x16 (&s)[2], const int (&col_pos)[2
 }
 
 // O^T += V^T P^T for the 32 keys of half mb.
-__device__ __forceinline__ void pv_half(const Stage& st, int mb, const bf16x8 (&pf)[2][2], int x, int h, f32x16 (&o)[4][2]) {
+__device__ __forceinline__ void pv_half(const __bf16* vt, int mb, const bf16x8 (&pf)[2][2], int x, int h, f32x16 (&o)[4][2]) {
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
         const int kb = 2 * mb + kk;
 #pragma unroll
         for (int md = 0; md < 4; ++md) {
             const int dd = 32 * md + x;
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&st.vt[dd * KT + 8 * vt_chunk(dd, 2 * kb + h)]);
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vt[dd * KT + 8 * vt_chunk(dd, 2 * kb + h)]);
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) o[md][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nb][kk], o[md][nb], 0, 0, 0);
         }
     }
 }
 
-// One staged tile with a fixed exponent reference per column: no maximum, no rescale.
-template <bool MASK>
-__device__ __forceinline__ void tile_fixed_ref(const Stage& st, const bf16x8 (&qf)[2][8], f32x16 (&o)[4][2],
-                                               float (&lsum)[2], const float (&mref)[2], const int (&col_pos)[2],
-                                               int key0, int x, int h, float scale_log2e) {
+// One step of the fast kernel's software pipeline, at the granularity of 32 keys ("a half").  It turns the
+// logits of half j (s_cur) into bf16 weights (pf_cur), while the matrix cores form the logits of half j+1
+// (s_nxt = K Q^T, 16 instructions) and add half j-1 to the output (O^T += V^T P^T with pf_prev, 16
+// instructions).  The three strands are independent, so the vector ALU's exp work runs in the shadow of the
+// matrix instructions.  The exponent reference is fixed per column: no maximum, no rescale, no branch.
+template <bool MASK, bool DO_QK>
+__device__ __forceinline__ void pipeline_step(const __bf16* k_next, int mb_next, const __bf16* vt_prev, int mb_prev,
+                                              const bf16x8 (&qf)[2][8], f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2],
+                                              const bf16x8 (&pf_prev)[2][2], bf16x8 (&pf_cur)[2][2], f32x16 (&o)[4][2],
+                                              float (&lsum)[2], const float (&mref)[2], const int (&col_pos)[2],
+                                              int key_base, int x, int h, float scale_log2e) {
+    mask_half<MASK>(s_cur, col_pos, key_base, h);
+    if (DO_QK) {
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-        f32x16 s[2];
-        qk_half(st, mb, qf, x, h, s);
-        mask_half<MASK>(s, col_pos, key0 + 32 * mb, h);
-        bf16x8 pf[2][2];   // P^T as B operand: [nb][16-key block of this half]
+        for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            float psum = 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nb][v], scale_log2e, -mref[nb]));
-                psum += p;
-                pf[nb][v >> 3][v & 7] = (__bf16)p;
-            }
-            lsum[nb] += psum;
-        }
-        pv_half(st, mb, pf, x, h, o);
+            for (int v = 0; v < 16; ++v) s_nxt[nb][v] = 0.f;
     }
+    // strand 1 + first half of the weights (query column block 0)
+    float psum0 = 0.f, psum1 = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        if (DO_QK) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&k_next[(32 * mb_next + x) * K_PITCH + 16 * ks + 8 * h]);
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+                s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s_nxt[nb], 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int v = 2 * ks + e;
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[0][v], scale_log2e, -mref[0]));
+            psum0 += p;
+            pf_cur[0][v >> 3][v & 7] = (__bf16)p;
+        }
+    }
+    // strand 2 + second half of the weights (query column block 1)
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const int kb = 2 * mb_prev + kk;
+#pragma unroll
+        for (int md = 0; md < 4; ++md) {
+            const int dd = 32 * md + x;
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vt_prev[dd * KT + 8 * vt_chunk(dd, 2 * kb + h)]);
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+                o[md][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf_prev[nb][kk], o[md][nb], 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int v = 8 * kk + 2 * md + e;
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[1][v], scale_log2e, -mref[1]));
+                psum1 += p;
+                pf_cur[1][v >> 3][v & 7] = (__bf16)p;
+            }
+        }
+    }
+    lsum[0] += psum0;
+    lsum[1] += psum1;
 }
 
 // Normalise, transpose through LDS and store 16 bytes per lane; lse = (m + log2 l) ln 2.
@@ -259,7 +323,7 @@ __device__ __forceinline__ void store_output(const Geometry<G>& ge, f32x16 (&o)[
 }
 
 // ---- fast kernel ---------------------------------------------------------------------------------
-// grid.x = n_row_tiles * Hkv.  Dynamic LDS: the larger of N_STAGE stages and the epilogue's staging.
+// grid.x = n_row_tiles * Hkv.  Dynamic LDS: the larger of the K/V rings and the epilogue's staging.
 template <int G, bool HAS_NEW>
 __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __restrict__ q_rows,
                                                              const int32_t* __restrict__ q_index, int R,
@@ -271,7 +335,7 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
                                                              float* __restrict__ lse_out, int32_t* __restrict__ redo_flags,
                                                              int Hq, int Hkv, int n_row_tiles, float scale_log2e) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    Stage* stages = reinterpret_cast<Stage*>(smem_raw);
+    Rings& rg = *reinterpret_cast<Rings*>(smem_raw);
     Geometry<G> ge;
     ge.init(q_index, R, Hkv, n_row_tiles);
     const int x = ge.x, h = ge.h;
@@ -293,51 +357,99 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
             for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
     float lsum[2] = {0.f, 0.f};
 
+    // ---- prologue: K tiles 0 and 1 and V tile 0 in LDS, K tile 2 and V tile 1 in flight -----------------
     Stager<HAS_NEW> sg;
     sg.init(k_cache, v_cache, k_new, v_new, inv, L, Hkv, ge.g);
-    sg.load(0);
-    sg.write(stages[0]);
-    if (ge.n_kt > 1) sg.load(1);
+    const int n_kt = ge.n_kt;
+    sg.fetch_inv_k(0);
+    sg.fetch_inv_v(0);
+    sg.load_k(0);
+    sg.load_v(0);
+    sg.fetch_inv_k(1);
+    sg.fetch_inv_v(1);
+    {   // V ring slot 2 is read (against all-zero weights) by the very first step: it must hold finite numbers
+        const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) reinterpret_cast<u32x4*>(rg.vt[2])[threadIdx.x + 256 * i] = z;
+    }
+    sg.write_k(rg.k[0]);
+    sg.write_v(rg.vt[0]);
+    if (n_kt > 1) {
+        sg.load_k(1);
+        sg.fetch_inv_k(2);
+        sg.write_k(rg.k[1]);
+        sg.load_v(1);
+        sg.fetch_inv_v(2);
+    }
+    if (n_kt > 2) {
+        sg.load_k(2);
+        sg.fetch_inv_k(3);
+    }
     __syncthreads();
 
-    // exponent reference of each column: the maximum over its visible keys among the first 32
+    // logits of the first 32 keys; exponent reference of each column = their maximum over the visible ones
+    f32x16 s_a[2], s_b[2];
+    qk_half(rg.k[0], 0, qf, x, h, s_a);
     float mref[2];
-    {
-        f32x16 s[2];
-        qk_half(stages[0], 0, qf, x, h, s);
-        mask_half<true>(s, ge.col_pos, 0, h);
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            float t = s[nb][0];
+    for (int nb = 0; nb < 2; ++nb) {
+        float t = s_a[nb][0];   // key 0 (h = 0) or key 4 (h = 1); key 0 is visible to every row
 #pragma unroll
-            for (int v = 1; v < 16; ++v) t = fmaxf(t, s[nb][v]);
-            t = fmaxf(t, __shfl_xor(t, 32));
-            mref[nb] = t * scale_log2e;
+        for (int v = 0; v < 16; ++v) {
+            const int key = 8 * (v >> 2) + 4 * h + (v & 3);
+            t = fmaxf(t, key <= ge.col_pos[nb] ? s_a[nb][v] : NEG_BIG);
         }
+        if (h == 1 && ge.col_pos[nb] < 4) t = NEG_BIG;
+        t = fmaxf(t, __shfl_xor(t, 32));
+        mref[nb] = t * scale_log2e;
     }
+    bf16x8 pf_a[2][2], pf_b[2][2];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf_b[nb][kk][e] = (__bf16)0.0f;
 
-    // Tile loop: after the barrier that ends tile kt-1, tile kt+1 moves from registers to the free LDS stage,
-    // the loads of tile kt+2 are issued, and tile kt is consumed: one barrier per tile, two stages.
-    int kt = 0, buf = 0;   // buf = kt % N_STAGE
-    for (; kt < ge.n_plain; ++kt) {   // plain tiles: every key visible to every row, a next tile always exists
-        const int nbuf = (buf + 1 == N_STAGE) ? 0 : buf + 1;
+    // ---- tile loop ------------------------------------------------------------------------------------
+    // Iteration kt, after its barrier: K tile kt+2 and V tile kt+1 move from registers into their rings, the
+    // loads of K tile kt+3 and V tile kt+2 are issued, and two pipeline steps run:
+    //   step (kt, 0): weights of keys [64kt, 64kt+32)    | logits of (kt, 1) from K[kt]     | O += half (kt-1, 1), V[kt-1]
+    //   step (kt, 1): weights of keys [64kt+32, 64kt+64) | logits of (kt+1, 0) from K[kt+1] | O += half (kt, 0),   V[kt]
+    // A ring slot is rewritten two iterations after its last reader, so one barrier per tile suffices.
+    int k0 = 0, k1 = 1, k2 = 2;   // ring slots of tiles kt, kt+1, kt+2 (K);  V tile kt-1 sits in slot k2, kt in k0, kt+1 in k1
+    int kt = 0;
+    for (; kt < ge.n_plain; ++kt) {   // plain tiles: every key visible to every row; a next tile always exists
         if (kt > 0) __syncthreads();
-        sg.write(stages[nbuf]);
-        if (kt + 2 < ge.n_kt) sg.load(kt + 2);
-        tile_fixed_ref<false>(stages[buf], qf, o, lsum, mref, ge.col_pos, kt * KT, x, h, scale_log2e);
-        buf = nbuf;
+        if (kt + 2 < n_kt) sg.write_k(rg.k[k2]);
+        sg.write_v(rg.vt[k1]);
+        if (kt + 3 < n_kt) { sg.load_k(kt + 3); sg.fetch_inv_k(kt + 4); }
+        if (kt + 2 < n_kt) { sg.load_v(kt + 2); sg.fetch_inv_v(kt + 3); }
+        pipeline_step<false, true>(rg.k[k0], 1, rg.vt[k2], 1, qf, s_a, s_b, pf_b, pf_a, o, lsum, mref, ge.col_pos,
+                                   kt * KT, x, h, scale_log2e);
+        // (V tile kt+1 was just written to slot k1; slot k2 is free for K tile kt+2 -- written above -- because the
+        //  K and V rings are separate arrays)
+        pipeline_step<false, true>(rg.k[k1], 0, rg.vt[k0], 0, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref, ge.col_pos,
+                                   kt * KT + 32, x, h, scale_log2e);
+        const int t = k0; k0 = k1; k1 = k2; k2 = t;
     }
-    for (; kt < ge.n_kt; ++kt) {      // tiles that cross some row's own position
-        const int nbuf = (buf + 1 == N_STAGE) ? 0 : buf + 1;
+    for (; kt < n_kt; ++kt) {         // tiles that cross some row's own position
         if (kt > 0) __syncthreads();
-        if (kt + 1 < ge.n_kt) {
-            sg.write(stages[nbuf]);
-            if (kt + 2 < ge.n_kt) sg.load(kt + 2);
-        }
-        if (kt * KT <= ge.wp_max)
-            tile_fixed_ref<true>(stages[buf], qf, o, lsum, mref, ge.col_pos, kt * KT, x, h, scale_log2e);
-        buf = nbuf;
+        if (kt + 2 < n_kt) sg.write_k(rg.k[k2]);
+        if (kt + 1 < n_kt) sg.write_v(rg.vt[k1]);
+        if (kt + 3 < n_kt) { sg.load_k(kt + 3); sg.fetch_inv_k(kt + 4); }
+        if (kt + 2 < n_kt) { sg.load_v(kt + 2); sg.fetch_inv_v(kt + 3); }
+        pipeline_step<true, true>(rg.k[k0], 1, rg.vt[k2], 1, qf, s_a, s_b, pf_b, pf_a, o, lsum, mref, ge.col_pos,
+                                  kt * KT, x, h, scale_log2e);
+        if (kt + 1 < n_kt)
+            pipeline_step<true, true>(rg.k[k1], 0, rg.vt[k0], 0, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref, ge.col_pos,
+                                      kt * KT + 32, x, h, scale_log2e);
+        else
+            pipeline_step<true, false>(rg.k[k1], 0, rg.vt[k0], 0, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref, ge.col_pos,
+                                       kt * KT + 32, x, h, scale_log2e);
+        const int t = k0; k0 = k1; k1 = k2; k2 = t;
     }
+    pv_half(rg.vt[k2], 1, pf_b, x, h, o);   // the last half: tile n_kt-1 now sits in slot k2
 
     // overflow check: with a fixed reference a runaway logit shows up as inf / nan in the sums
     float l[2];
@@ -403,7 +515,7 @@ __global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __r
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
             f32x16 s[2];
-            qk_half(stages[0], mb, qf, x, h, s);
+            qk_half(stages[0].k, mb, qf, x, h, s);
             mask_half<true>(s, ge.col_pos, kt * KT + 32 * mb, h);
             bf16x8 pf[2][2];
 #pragma unroll
@@ -428,7 +540,7 @@ __global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __r
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[md][nb][v] *= alpha;
             }
-            pv_half(stages[0], mb, pf, x, h, o);
+            pv_half(stages[0].vt, mb, pf, x, h, o);
         }
     }
     float l[2];
@@ -445,7 +557,7 @@ hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, in
     const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
     constexpr int TR = Geometry<G>::TR;
     const int n_row_tiles = (R + TR - 1) / TR;
-    const size_t lds_fast = N_STAGE * sizeof(Stage) > EPILOGUE_LDS ? N_STAGE * sizeof(Stage) : EPILOGUE_LDS;
+    const size_t lds_fast = sizeof(Rings) > EPILOGUE_LDS ? sizeof(Rings) : EPILOGUE_LDS;
     const size_t lds_safe = sizeof(Stage) > EPILOGUE_LDS ? sizeof(Stage) : EPILOGUE_LDS;
     static bool attr_set = false;
     if (!attr_set) {
