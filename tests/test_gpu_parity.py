@@ -264,3 +264,50 @@ def test_chained_layer(name, seed):
     H.assert_close(H.host(k_cache), want_k, dt, "chained K cache")
     assert np.array_equal(H.host(v_cache), want_v)
     ctx.close()
+
+
+def test_attention_softmax_modes_agree():
+    """The running-maximum kernel alone (forced through fr_set_option) gives the oracle's result too."""
+    w = workloads()["small_bf16"](5)
+    k_ctx, _, k, qi = staged(w)
+    k_cache, v_cache = assembled_cache(w, k_ctx)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    want, want_lse = orc.sparse_prefill_attn(w.q_full[qi], qi, k_cache, v_cache, w.k_full[qi], w.v_full[qi])
+    ctx.fr_set_option(B.FR_OPT_ATTN_SOFTMAX, B.FR_ATTN_SOFTMAX_RUNNING_MAX)
+    got, lse = run_attention(ctx, w, qi, k_cache, v_cache)
+    H.assert_close(got, want, "bf16", "running-max attention")
+    assert np.max(np.abs(lse - want_lse)) <= 2e-3
+    ctx.fr_set_option(B.FR_OPT_ATTN_SOFTMAX, B.FR_ATTN_SOFTMAX_AUTO)
+    got2, _ = run_attention(ctx, w, qi, k_cache, v_cache)
+    H.assert_close(got2, want, "bf16", "default attention")
+    with pytest.raises(B.FusionRAGError):
+        ctx.fr_set_option(B.FR_OPT_ATTN_SOFTMAX, 7)
+    ctx.close()
+
+
+def test_attention_logits_far_above_the_first_keys():
+    """Degenerate case of the fixed exponent reference: logits that grow along the sequence until exp2 would
+    overflow against the maximum of the first 32 keys.  The default path must still match the oracle (the
+    overflowing workgroups are recomputed with a running maximum)."""
+    shape = synth.LLAMA3_8B_BF16
+    rng = np.random.default_rng(11)
+    L_ctx, nq, d = 600, 24, shape.head_dim
+    L = L_ctx + nq
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    ramp = np.linspace(0.0, 1.0, L)[:, None, None]                       # key j gains ramp_j * 180 * u
+    k_all = rng.standard_normal((L, shape.n_kv_heads, d)) * 0.05 + ramp * 180.0 * u
+    q_all = rng.standard_normal((L, shape.n_q_heads, d)) * 0.05 + 12.0 * u   # logit ~ 12*180*ramp/sqrt(128) ~ 190*ramp
+    v_all = rng.standard_normal((L, shape.n_kv_heads, d))
+    r = lambda a: synth.round_to_storage(a.astype(np.float32), "bf16")
+    k_all, q_all, v_all = r(k_all), r(q_all), r(v_all)
+    sel = np.sort(rng.choice(L_ctx, size=90, replace=False))
+    qi = np.concatenate([sel, L_ctx + np.arange(nq)])
+    w = synth.Workload("ramp", shape, 0, np.array([0, L_ctx], np.int32), np.zeros(1, np.int32), nq, 0.15,
+                       k_all[:L_ctx], v_all[:L_ctx], q_all, k_all, v_all, np.zeros(0, np.int64))
+    ctx = H.make_ctx(shape, L, 1, nq)
+    got, lse = run_attention(ctx, w, qi, k_all, v_all)
+    want, want_lse = orc.sparse_prefill_attn(q_all[qi], qi, k_all, v_all, k_all[qi], v_all[qi])
+    H.assert_close(got, want, "bf16", "attention with runaway logits")
+    assert np.max(np.abs(lse - want_lse) / np.abs(want_lse)) <= 1e-3
+    ctx.close()
