@@ -134,6 +134,8 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_sel = take(4096);
     w.attn_flags_elems = (size_t)(max_tokens / 32 + 1) * s.Hkv;   // one per (row tile of >= 32 rows, KV head)
     const size_t o_flags = take(w.attn_flags_elems * 4);
+    w.kv_images_bytes = (s.dtype == FR_BF16 && s.d == 128) ? (size_t)((max_tokens + 63) / 64) * s.Hkv * 36864 : 0;
+    const size_t o_img = take(w.kv_images_bytes);
     w.bytes = off;
     hipError_t e = hipMalloc((void**)&w.base, w.bytes);
     if (e != hipSuccess) {
@@ -147,6 +149,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.inv_index = (int32_t*)(w.base + o_inv);
     w.select_tmp = (uint32_t*)(w.base + o_sel);
     w.attn_flags = (int32_t*)(w.base + o_flags);
+    w.kv_images = (unsigned char*)(w.base + o_img);
     ctx->has_device = true;
     *out = ctx;
     return FR_OK;

@@ -41,6 +41,8 @@ struct Workspace {
     uint32_t* select_tmp = nullptr; // small counters for the selection kernels
     int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
     size_t attn_flags_elems = 0;
+    unsigned char* kv_images = nullptr;  // [Hkv][ceil(max_tokens / 64)] LDS-ready K / V^T tile images, 32 KB each
+    size_t kv_images_bytes = 0;
 };
 
 }  // namespace fr

@@ -12,7 +12,7 @@
 //     softmax statistics of a query column live in one lane (plus its partner lane + 32);
 //   * the fp32 accumulator layout of S^T is, after conversion to bf16, exactly the B-operand
 //     layout of the second product (contraction over keys), so P never leaves registers;
-//   * V is transposed once per tile while it is staged into LDS (4 keys x 8 dims per lane,
+//   * V is transposed once per (KV head, key tile) by the packing pre-pass (4 keys x 8 dims per lane,
 //     repacked with byte permutes), so the A operand of the second product is a 16-byte LDS read.
 // The key order inside every block of 16 keys is permuted identically in P^T and V^T
 // ([0-3, 8-11, 4-7, 12-15]); a contraction does not care about the order of its terms.
@@ -24,8 +24,13 @@
 // the sums overflow to inf; the workgroup then raises a flag, and the safe kernel (classic online
 // softmax with a running maximum) recomputes exactly the flagged workgroups.
 //
-// Stale entries.  Key j is read from k_new/v_new when inv[j] >= 0 (its token is in the Q index)
-// and from the cache otherwise: the cache is never written and stale rows are never read.
+// K/V tile images.  Every row tile of a KV head walks the same K/V stream (47 row tiles per head at 17k
+// tokens / 15 %), so the work that does not depend on the rows is done once, by a packing pre-pass: for each
+// (KV head, 64-key tile) it resolves stale / fresh rows (key j comes from k_new/v_new when inv[j] >= 0, i.e.
+// its token is in the Q index, and from the cache otherwise: the cache is never written and stale rows are
+// never read), transposes V, applies the LDS bank swizzle and writes a 32 KB image that is byte for byte what
+// the attention kernels want in LDS.  The fast kernel's tile loop then stages a tile with direct-to-LDS
+// copies: no lookups, no pointer selects, no permutes, no address arithmetic, no staging registers.
 #include "fr_internal.hpp"
 
 namespace fr {
@@ -40,26 +45,28 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int D = 128;           // head_dim
 constexpr int KT = 64;           // keys per tile
-constexpr int K_PITCH = D + 8;   // bf16 elements per K row in LDS (272 B: 16-byte reads hit distinct banks)
 constexpr int O_PITCH = D + 8;   // bf16 elements per output row in the epilogue's LDS staging
 constexpr float NEG_BIG = -1.0e30f;
 
-struct __attribute__((aligned(16))) Stage {
-    __bf16 k[KT * K_PITCH];   // [key][d], rows padded to 272 B
-    __bf16 vt[D * KT];        // [d][key slot], 128-byte rows, 16-byte chunks XOR-swizzled (see vt_chunk)
-};
-// The fast kernel keeps separate rings of three K tiles and three V^T tiles (see its tile loop).
+// Tile image = [K image 18 KB][V^T image 18 KB], padded so that 16-byte operand reads (one lane per row, 16
+// lanes per LDS pass) fall into 16 distinct bank groups and every fragment address is base + constant:
+//   K image:   64 rows (keys) of 272 B (256 B of data + 16 B pad), then 1 KB of tail pad;
+//   V^T image: 128 rows (dims) of 144 B (64 key slots = 128 B of data + 16 B pad), slot order see key_slot.
+constexpr int K_ROW = 272, V_ROW = 144;
+constexpr int K_IMG_BYTES = 18432;
+constexpr int V_IMG_BYTES = D * V_ROW;   // 18432
+constexpr int IMG_BYTES = K_IMG_BYTES + V_IMG_BYTES;
+static_assert(KT * K_ROW <= K_IMG_BYTES && K_IMG_BYTES % 1024 == 0 && V_IMG_BYTES % 1024 == 0, "image layout");
+// Inside every block of 16 keys the order is [0-3, 8-11, 4-7, 12-15]: the order in which the accumulator
+// layout of S^T hands the keys to the second product.  Slot of key t (0..63) of a tile:
+__device__ __forceinline__ int key_slot(int t) { return 16 * (t >> 4) + 4 * ((0x3120 >> (4 * ((t >> 2) & 3))) & 3) + (t & 3); }
+
+// The fast kernel keeps separate rings of three K images and three V^T images (see its tile loop).
 struct __attribute__((aligned(16))) Rings {
-    __bf16 k[3][KT * K_PITCH];
-    __bf16 vt[3][D * KT];
+    unsigned char k[3][K_IMG_BYTES];
+    unsigned char vt[3][V_IMG_BYTES];
 };
 constexpr size_t EPILOGUE_LDS = 4 * 64 * O_PITCH * sizeof(__bf16);   // four waves x [64 columns][d] bf16
-
-// V^T rows are exactly 128 bytes (all 32 LDS banks), so both the transposing writes (one lane per 8-dim
-// group, rows 8 apart) and the operand reads (one lane per row, 32 consecutive rows) would pile onto the
-// same banks.  The 16-byte chunk index is therefore XORed with a key that differs between rows 1 apart
-// and between rows 8 apart.
-__device__ __forceinline__ int vt_chunk(int dd, int chunk) { return chunk ^ ((dd ^ (dd >> 3)) & 7); }
 
 __device__ __forceinline__ uint32_t perm_lo(uint32_t a, uint32_t b) {  // (a.lo16, b.lo16) -> a in low half
     return __builtin_amdgcn_perm(b, a, 0x05040100u);
@@ -104,96 +111,113 @@ struct Geometry {
     }
 };
 
-// ---- staging: global -> registers -> LDS ------------------------------------------------------------
-// Loads never branch: a key past the end of the cache is clamped to the last row (it lies beyond every
-// row's position, so the causal mask removes it), and the cache / fresh-row choice is a pointer select.
-template <bool HAS_NEW>
-struct Stager {
-    const __bf16 *k_cache, *v_cache, *k_new, *v_new;
-    const int32_t* inv;
-    int L, Hkv, g;
-    int st_vec, st_key, kslot;
+// ---- packing pre-pass: grid (key tiles, KV heads) ---------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_kv_images_kernel(const __bf16* __restrict__ k_cache,
+                                                             const __bf16* __restrict__ v_cache, int L,
+                                                             const __bf16* __restrict__ k_new,
+                                                             const __bf16* __restrict__ v_new,
+                                                             const int32_t* __restrict__ inv, int Hkv, int n_img_tiles,
+                                                             unsigned char* __restrict__ images) {
+    __shared__ __attribute__((aligned(16))) unsigned char img[IMG_BYTES];
+    const int tid = threadIdx.x, kt = blockIdx.x, g = blockIdx.y;
+    const int st_vec = tid & 15;   // 16-byte vector (8 dims) within a 256-byte head row
+    const int st_key = tid >> 4;   // K: keys st_key + 16 i;  V: keys 4 st_key + i
     u32x4 kreg[4], vreg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {   // a key past the end is clamped: it lies beyond every row's position
+        const int jk = min(kt * KT + st_key + 16 * i, L - 1);
+        const int jv = min(kt * KT + 4 * st_key + i, L - 1);
+        const __bf16* pk = k_cache + ((size_t)jk * Hkv + g) * D;
+        const __bf16* pv = v_cache + ((size_t)jv * Hkv + g) * D;
+        if (inv != nullptr) {
+            const int rk = inv[jk], rv = inv[jv];
+            if (rk >= 0) pk = k_new + ((size_t)rk * Hkv + g) * D;
+            if (rv >= 0) pv = v_new + ((size_t)rv * Hkv + g) * D;
+        }
+        kreg[i] = *reinterpret_cast<const u32x4*>(pk + 8 * st_vec);
+        vreg[i] = *reinterpret_cast<const u32x4*>(pv + 8 * st_vec);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&img[(st_key + 16 * i) * K_ROW + 16 * st_vec]) = kreg[i];
+    {   // pads: K row tails, K image tail, V^T row tails (never read by the matrix operands; kept zero)
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        if (tid < KT) *reinterpret_cast<u32x4*>(&img[tid * K_ROW + 256]) = z;
+        if (tid < (K_IMG_BYTES - KT * K_ROW) / 16) *reinterpret_cast<u32x4*>(&img[KT * K_ROW + 16 * tid]) = z;
+        if (tid < D) *reinterpret_cast<u32x4*>(&img[K_IMG_BYTES + tid * V_ROW + 128]) = z;
+    }
+    const int slot = key_slot(4 * st_key);   // the 4 keys of this lane occupy slots slot .. slot + 3
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {   // dims 8 st_vec + 2c and + 2c + 1: gather the 4 keys of each
+        u32x2 lo, hi;
+        lo[0] = perm_lo(vreg[0][c], vreg[1][c]);
+        lo[1] = perm_lo(vreg[2][c], vreg[3][c]);
+        hi[0] = perm_hi(vreg[0][c], vreg[1][c]);
+        hi[1] = perm_hi(vreg[2][c], vreg[3][c]);
+        const int d0 = 8 * st_vec + 2 * c, d1 = d0 + 1;
+        *reinterpret_cast<u32x2*>(&img[K_IMG_BYTES + d0 * V_ROW + 2 * slot]) = lo;
+        *reinterpret_cast<u32x2*>(&img[K_IMG_BYTES + d1 * V_ROW + 2 * slot]) = hi;
+    }
+    __syncthreads();
+    unsigned char* dst = images + ((size_t)g * n_img_tiles + kt) * IMG_BYTES;
+#pragma unroll
+    for (int i = 0; i < IMG_BYTES / 4096; ++i)
+        *reinterpret_cast<u32x4*>(dst + i * 4096 + tid * 16) = *reinterpret_cast<const u32x4*>(&img[i * 4096 + tid * 16]);
+}
 
-    __device__ __forceinline__ void init(const __bf16* kc, const __bf16* vc, const __bf16* kn, const __bf16* vn,
-                                         const int32_t* iv, int L_, int Hkv_, int g_) {
-        k_cache = kc; v_cache = vc; k_new = kn; v_new = vn; inv = iv; L = L_; Hkv = Hkv_; g = g_;
-        st_vec = threadIdx.x & 15;   // 16-byte vector within a 256-byte head row
-        st_key = threadIdx.x >> 4;   // K: keys st_key + 16 i;  V: key group st_key (4 consecutive keys)
-        kslot = 16 * (st_key >> 2) + 4 * ((0x3120 >> (4 * (st_key & 3))) & 3);   // permuted slot of key 4*st_key
-    }
-    // The position -> fresh-row map is read one step ahead of the rows themselves (fetch_inv_* for tile kt+1
-    // right after load_* of tile kt), so that a row load never waits on the lookup that addresses it.
-    int inv_k[4], inv_v[4];
-    __device__ __forceinline__ void fetch_inv_k(int kt) {
-        if (!HAS_NEW) return;
+// ---- staging in the fast kernel: image -> LDS directly (global_load_lds_dwordx4: lane i of a wave deposits its
+//      16 bytes at the wave's LDS base + 16 i), no registers involved.  An image is 18 chunks of 1 KB; wave w
+//      moves chunks w, w + 4, ...  Completion: the issuing wave's vmcnt, then a workgroup barrier. ----------
+__device__ __forceinline__ void dma_image(const unsigned char* src, unsigned char* lds_dst, int wave, int lane) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) inv_k[i] = inv[min(kt * KT + st_key + 16 * i, L - 1)];
+    for (int c = 0; c < 5; ++c) {
+        const int chunk = wave + 4 * c;
+        if (chunk < K_IMG_BYTES / 1024)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + chunk * 1024 + lane * 16),
+                                             (__attribute__((address_space(3))) void*)(lds_dst + chunk * 1024), 16, 0, 0);
     }
-    __device__ __forceinline__ void fetch_inv_v(int kt) {
-        if (!HAS_NEW) return;
+}
+__device__ __forceinline__ void wait_dma() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
+
+// ---- staging in the safe kernel: image -> registers -> LDS, 9 copies of 16 bytes per lane ----------------
+struct ImageStager {
+    const unsigned char* head_images;   // images of this KV head
+    int lane_off;                       // threadIdx.x * 16
+    u32x4 reg[IMG_BYTES / 4096];
+    __device__ __forceinline__ void init(const unsigned char* images, int g, int n_img_tiles) {
+        head_images = images + (size_t)g * n_img_tiles * IMG_BYTES;
+        lane_off = threadIdx.x * 16;
+    }
+    __device__ __forceinline__ void load(int kt) {
+        const unsigned char* p = head_images + (size_t)kt * IMG_BYTES + lane_off;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) inv_v[i] = inv[min(kt * KT + 4 * st_key + i, L - 1)];
+        for (int i = 0; i < IMG_BYTES / 4096; ++i) reg[i] = *reinterpret_cast<const u32x4*>(p + i * 4096);
     }
-    __device__ __forceinline__ void load_k(int kt) {   // needs fetch_inv_k(kt) before
-        const int key0 = kt * KT;
+    __device__ __forceinline__ void write(unsigned char* img) const {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int jk = min(key0 + st_key + 16 * i, L - 1);
-            const __bf16* pk = k_cache + ((size_t)jk * Hkv + g) * D;
-            if (HAS_NEW) {
-                const int rk = inv_k[i];
-                const __bf16* nk = k_new + ((size_t)max(rk, 0) * Hkv + g) * D;
-                pk = (rk >= 0) ? nk : pk;
-            }
-            kreg[i] = *reinterpret_cast<const u32x4*>(pk + 8 * st_vec);
-        }
+        for (int i = 0; i < IMG_BYTES / 4096; ++i) *reinterpret_cast<u32x4*>(img + i * 4096 + lane_off) = reg[i];
     }
-    __device__ __forceinline__ void load_v(int kt) {   // needs fetch_inv_v(kt) before
-        const int key0 = kt * KT;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int jv = min(key0 + 4 * st_key + i, L - 1);
-            const __bf16* pv = v_cache + ((size_t)jv * Hkv + g) * D;
-            if (HAS_NEW) {
-                const int rv = inv_v[i];
-                const __bf16* nv = v_new + ((size_t)max(rv, 0) * Hkv + g) * D;
-                pv = (rv >= 0) ? nv : pv;
-            }
-            vreg[i] = *reinterpret_cast<const u32x4*>(pv + 8 * st_vec);
-        }
+};
+
+// Per-lane byte offsets of the operand fragments inside an image: row x, 16-byte half h.
+struct FragOffsets {
+    int k;   // K fragment: + 32 ks (16 dims per step) + 32 * K_ROW for the second half of the tile
+    int v;   // V^T fragment: + 32 kb (16 key slots per block) + 32 * V_ROW * md for dim block md
+    __device__ __forceinline__ void init(int x, int h) {
+        k = x * K_ROW + 16 * h;
+        v = x * V_ROW + 16 * h;
     }
-    __device__ __forceinline__ void load(int kt) { fetch_inv_k(kt); fetch_inv_v(kt); load_k(kt); load_v(kt); }
-    __device__ __forceinline__ void write_k(__bf16* k) const {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<u32x4*>(&k[(st_key + 16 * i) * K_PITCH + 8 * st_vec]) = kreg[i];
-    }
-    __device__ __forceinline__ void write_v(__bf16* vt) const {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {   // dims 8*st_vec + 2c, +2c+1: gather the 4 keys of each
-            u32x2 lo, hi;
-            lo[0] = perm_lo(vreg[0][c], vreg[1][c]);
-            lo[1] = perm_lo(vreg[2][c], vreg[3][c]);
-            hi[0] = perm_hi(vreg[0][c], vreg[1][c]);
-            hi[1] = perm_hi(vreg[2][c], vreg[3][c]);
-            const int d0 = 8 * st_vec + 2 * c, d1 = d0 + 1;
-            *reinterpret_cast<u32x2*>(&vt[d0 * KT + 8 * vt_chunk(d0, kslot >> 3) + (kslot & 4)]) = lo;
-            *reinterpret_cast<u32x2*>(&vt[d1 * KT + 8 * vt_chunk(d1, kslot >> 3) + (kslot & 4)]) = hi;
-        }
-    }
-    __device__ __forceinline__ void write(Stage& st) const { write_k(st.k); write_v(st.vt); }
 };
 
 // S^T for 32 keys (half mb of a staged tile) against this wave's 64 query columns.
-__device__ __forceinline__ void qk_half(const __bf16* k, int mb, const bf16x8 (&qf)[2][8], int x, int h, f32x16 (&s)[2]) {
+__device__ __forceinline__ void qk_half(const unsigned char* k, int mb, const bf16x8 (&qf)[2][8], const FragOffsets& fo,
+                                        f32x16 (&s)[2]) {
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[nb][v] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&k[(32 * mb + x) * K_PITCH + 16 * ks + 8 * h]);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(k + fo.k + 32 * ks + mb * (32 * K_ROW));
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s[nb], 0, 0, 0);
     }
@@ -212,14 +236,14 @@ __device__ __forceinline__ void mask_half(f32x16 (&s)[2], const int (&col_pos)[2
 }
 
 // O^T += V^T P^T for the 32 keys of half mb.
-__device__ __forceinline__ void pv_half(const __bf16* vt, int mb, const bf16x8 (&pf)[2][2], int x, int h, f32x16 (&o)[4][2]) {
+__device__ __forceinline__ void pv_half(const unsigned char* vt, int mb, const bf16x8 (&pf)[2][2], const FragOffsets& fo,
+                                        f32x16 (&o)[4][2]) {
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
         const int kb = 2 * mb + kk;
 #pragma unroll
         for (int md = 0; md < 4; ++md) {
-            const int dd = 32 * md + x;
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vt[dd * KT + 8 * vt_chunk(dd, 2 * kb + h)]);
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(vt + fo.v + 32 * kb + md * (32 * V_ROW));
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) o[md][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nb][kk], o[md][nb], 0, 0, 0);
         }
@@ -232,11 +256,12 @@ __device__ __forceinline__ void pv_half(const __bf16* vt, int mb, const bf16x8 (
 // instructions).  The three strands are independent, so the vector ALU's exp work runs in the shadow of the
 // matrix instructions.  The exponent reference is fixed per column: no maximum, no rescale, no branch.
 template <bool MASK, bool DO_QK>
-__device__ __forceinline__ void pipeline_step(const __bf16* k_next, int mb_next, const __bf16* vt_prev, int mb_prev,
-                                              const bf16x8 (&qf)[2][8], f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2],
+__device__ __forceinline__ void pipeline_step(const unsigned char* k_next, int mb_next, const unsigned char* vt_prev,
+                                              int mb_prev, const FragOffsets& fo, const bf16x8 (&qf)[2][8],
+                                              f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2],
                                               const bf16x8 (&pf_prev)[2][2], bf16x8 (&pf_cur)[2][2], f32x16 (&o)[4][2],
                                               float (&lsum)[2], const float (&mref)[2], const int (&col_pos)[2],
-                                              int key_base, int x, int h, float scale_log2e) {
+                                              int key_base, int h, float scale_log2e) {
     mask_half<MASK>(s_cur, col_pos, key_base, h);
     if (DO_QK) {
 #pragma unroll
@@ -249,7 +274,7 @@ __device__ __forceinline__ void pipeline_step(const __bf16* k_next, int mb_next,
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
         if (DO_QK) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&k_next[(32 * mb_next + x) * K_PITCH + 16 * ks + 8 * h]);
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(k_next + fo.k + 32 * ks + mb_next * (32 * K_ROW));
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
                 s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s_nxt[nb], 0, 0, 0);
@@ -268,8 +293,7 @@ __device__ __forceinline__ void pipeline_step(const __bf16* k_next, int mb_next,
         const int kb = 2 * mb_prev + kk;
 #pragma unroll
         for (int md = 0; md < 4; ++md) {
-            const int dd = 32 * md + x;
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(&vt_prev[dd * KT + 8 * vt_chunk(dd, 2 * kb + h)]);
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(vt_prev + fo.v + 32 * kb + md * (32 * V_ROW));
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
                 o[md][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf_prev[nb][kk], o[md][nb], 0, 0, 0);
@@ -324,21 +348,20 @@ __device__ __forceinline__ void store_output(const Geometry<G>& ge, f32x16 (&o)[
 
 // ---- fast kernel ---------------------------------------------------------------------------------
 // grid.x = n_row_tiles * Hkv.  Dynamic LDS: the larger of the K/V rings and the epilogue's staging.
-template <int G, bool HAS_NEW>
+template <int G>
 __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __restrict__ q_rows,
                                                              const int32_t* __restrict__ q_index, int R,
-                                                             const __bf16* __restrict__ k_cache,
-                                                             const __bf16* __restrict__ v_cache, int L,
-                                                             const __bf16* __restrict__ k_new,
-                                                             const __bf16* __restrict__ v_new,
-                                                             const int32_t* __restrict__ inv, __bf16* __restrict__ out,
-                                                             float* __restrict__ lse_out, int32_t* __restrict__ redo_flags,
-                                                             int Hq, int Hkv, int n_row_tiles, float scale_log2e) {
+                                                             const unsigned char* __restrict__ images, int n_img_tiles,
+                                                             __bf16* __restrict__ out, float* __restrict__ lse_out,
+                                                             int32_t* __restrict__ redo_flags, int Hq, int Hkv,
+                                                             int n_row_tiles, float scale_log2e) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Rings& rg = *reinterpret_cast<Rings*>(smem_raw);
     Geometry<G> ge;
     ge.init(q_index, R, Hkv, n_row_tiles);
     const int x = ge.x, h = ge.h;
+    FragOffsets fo;
+    fo.init(x, h);
 
     // Q fragments: B operand of S^T = K Q^T, kept in registers for the whole loop
     bf16x8 qf[2][8];
@@ -357,50 +380,33 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
             for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
     float lsum[2] = {0.f, 0.f};
 
-    // ---- prologue: K tiles 0 and 1 and V tile 0 in LDS, K tile 2 and V tile 1 in flight -----------------
-    Stager<HAS_NEW> sg;
-    sg.init(k_cache, v_cache, k_new, v_new, inv, L, Hkv, ge.g);
+    // ---- prologue: K images 0 and 1 and V image 0 land in LDS ---------------------------------------------
+    const unsigned char* head_images = images + (size_t)ge.g * n_img_tiles * IMG_BYTES;
+    const int wave = ge.wave, lane = threadIdx.x & 63;
     const int n_kt = ge.n_kt;
-    sg.fetch_inv_k(0);
-    sg.fetch_inv_v(0);
-    sg.load_k(0);
-    sg.load_v(0);
-    sg.fetch_inv_k(1);
-    sg.fetch_inv_v(1);
+    dma_image(head_images, rg.k[0], wave, lane);
+    dma_image(head_images + K_IMG_BYTES, rg.vt[0], wave, lane);
+    if (n_kt > 1) dma_image(head_images + IMG_BYTES, rg.k[1], wave, lane);
     {   // V ring slot 2 is read (against all-zero weights) by the very first step: it must hold finite numbers
         const u32x4 z = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) reinterpret_cast<u32x4*>(rg.vt[2])[threadIdx.x + 256 * i] = z;
+        for (int i = threadIdx.x; i < V_IMG_BYTES / 16; i += 256) *reinterpret_cast<u32x4*>(&rg.vt[2][16 * i]) = z;
     }
-    sg.write_k(rg.k[0]);
-    sg.write_v(rg.vt[0]);
-    if (n_kt > 1) {
-        sg.load_k(1);
-        sg.fetch_inv_k(2);
-        sg.write_k(rg.k[1]);
-        sg.load_v(1);
-        sg.fetch_inv_v(2);
-    }
-    if (n_kt > 2) {
-        sg.load_k(2);
-        sg.fetch_inv_k(3);
-    }
+    wait_dma();
     __syncthreads();
 
     // logits of the first 32 keys; exponent reference of each column = their maximum over the visible ones
     f32x16 s_a[2], s_b[2];
-    qk_half(rg.k[0], 0, qf, x, h, s_a);
+    qk_half(rg.k[0], 0, qf, fo, s_a);
     float mref[2];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-        float t = s_a[nb][0];   // key 0 (h = 0) or key 4 (h = 1); key 0 is visible to every row
+        float t = NEG_BIG;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int key = 8 * (v >> 2) + 4 * h + (v & 3);
             t = fmaxf(t, key <= ge.col_pos[nb] ? s_a[nb][v] : NEG_BIG);
         }
-        if (h == 1 && ge.col_pos[nb] < 4) t = NEG_BIG;
-        t = fmaxf(t, __shfl_xor(t, 32));
+        t = fmaxf(t, __shfl_xor(t, 32));   // key 0 (held by the h = 0 lane) is visible to every row
         mref[nb] = t * scale_log2e;
     }
     bf16x8 pf_a[2][2], pf_b[2][2];
@@ -412,44 +418,46 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
             for (int e = 0; e < 8; ++e) pf_b[nb][kk][e] = (__bf16)0.0f;
 
     // ---- tile loop ------------------------------------------------------------------------------------
-    // Iteration kt, after its barrier: K tile kt+2 and V tile kt+1 move from registers into their rings, the
-    // loads of K tile kt+3 and V tile kt+2 are issued, and two pipeline steps run:
+    // Iteration kt: wait for the own direct-to-LDS copies issued one iteration ago, barrier (now K image kt+1
+    // and V image kt are complete and visible, and nobody reads the slots of K image kt-1 / V image kt-2 any
+    // more), issue the copies of K image kt+2 and V image kt+1 into those slots, and run two pipeline steps:
     //   step (kt, 0): weights of keys [64kt, 64kt+32)    | logits of (kt, 1) from K[kt]     | O += half (kt-1, 1), V[kt-1]
     //   step (kt, 1): weights of keys [64kt+32, 64kt+64) | logits of (kt+1, 0) from K[kt+1] | O += half (kt, 0),   V[kt]
-    // A ring slot is rewritten two iterations after its last reader, so one barrier per tile suffices.
-    int k0 = 0, k1 = 1, k2 = 2;   // ring slots of tiles kt, kt+1, kt+2 (K);  V tile kt-1 sits in slot k2, kt in k0, kt+1 in k1
+    int k0 = 0, k1 = 1, k2 = 2;   // ring slots of K images kt, kt+1, kt+2; V images kt-1, kt, kt+1 sit in k2, k0, k1
     int kt = 0;
     for (; kt < ge.n_plain; ++kt) {   // plain tiles: every key visible to every row; a next tile always exists
-        if (kt > 0) __syncthreads();
-        if (kt + 2 < n_kt) sg.write_k(rg.k[k2]);
-        sg.write_v(rg.vt[k1]);
-        if (kt + 3 < n_kt) { sg.load_k(kt + 3); sg.fetch_inv_k(kt + 4); }
-        if (kt + 2 < n_kt) { sg.load_v(kt + 2); sg.fetch_inv_v(kt + 3); }
-        pipeline_step<false, true>(rg.k[k0], 1, rg.vt[k2], 1, qf, s_a, s_b, pf_b, pf_a, o, lsum, mref, ge.col_pos,
-                                   kt * KT, x, h, scale_log2e);
-        // (V tile kt+1 was just written to slot k1; slot k2 is free for K tile kt+2 -- written above -- because the
-        //  K and V rings are separate arrays)
-        pipeline_step<false, true>(rg.k[k1], 0, rg.vt[k0], 0, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref, ge.col_pos,
-                                   kt * KT + 32, x, h, scale_log2e);
+        if (kt > 0) {
+            wait_dma();
+            __syncthreads();
+        }
+        const unsigned char* nxt = head_images + (size_t)(kt + 1) * IMG_BYTES;
+        if (kt + 2 < n_kt) dma_image(nxt + IMG_BYTES, rg.k[k2], wave, lane);
+        dma_image(nxt + K_IMG_BYTES, rg.vt[k1], wave, lane);
+        pipeline_step<false, true>(rg.k[k0], 1, rg.vt[k2], 1, fo, qf, s_a, s_b, pf_b, pf_a, o, lsum, mref, ge.col_pos,
+                                   kt * KT, h, scale_log2e);
+        pipeline_step<false, true>(rg.k[k1], 0, rg.vt[k0], 0, fo, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref, ge.col_pos,
+                                   kt * KT + 32, h, scale_log2e);
         const int t = k0; k0 = k1; k1 = k2; k2 = t;
     }
     for (; kt < n_kt; ++kt) {         // tiles that cross some row's own position
-        if (kt > 0) __syncthreads();
-        if (kt + 2 < n_kt) sg.write_k(rg.k[k2]);
-        if (kt + 1 < n_kt) sg.write_v(rg.vt[k1]);
-        if (kt + 3 < n_kt) { sg.load_k(kt + 3); sg.fetch_inv_k(kt + 4); }
-        if (kt + 2 < n_kt) { sg.load_v(kt + 2); sg.fetch_inv_v(kt + 3); }
-        pipeline_step<true, true>(rg.k[k0], 1, rg.vt[k2], 1, qf, s_a, s_b, pf_b, pf_a, o, lsum, mref, ge.col_pos,
-                                  kt * KT, x, h, scale_log2e);
+        if (kt > 0) {
+            wait_dma();
+            __syncthreads();
+        }
+        const unsigned char* nxt = head_images + (size_t)(kt + 1) * IMG_BYTES;
+        if (kt + 2 < n_kt) dma_image(nxt + IMG_BYTES, rg.k[k2], wave, lane);
+        if (kt + 1 < n_kt) dma_image(nxt + K_IMG_BYTES, rg.vt[k1], wave, lane);
+        pipeline_step<true, true>(rg.k[k0], 1, rg.vt[k2], 1, fo, qf, s_a, s_b, pf_b, pf_a, o, lsum, mref, ge.col_pos,
+                                  kt * KT, h, scale_log2e);
         if (kt + 1 < n_kt)
-            pipeline_step<true, true>(rg.k[k1], 0, rg.vt[k0], 0, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref, ge.col_pos,
-                                      kt * KT + 32, x, h, scale_log2e);
+            pipeline_step<true, true>(rg.k[k1], 0, rg.vt[k0], 0, fo, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref,
+                                      ge.col_pos, kt * KT + 32, h, scale_log2e);
         else
-            pipeline_step<true, false>(rg.k[k1], 0, rg.vt[k0], 0, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref, ge.col_pos,
-                                       kt * KT + 32, x, h, scale_log2e);
+            pipeline_step<true, false>(rg.k[k1], 0, rg.vt[k0], 0, fo, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref,
+                                       ge.col_pos, kt * KT + 32, h, scale_log2e);
         const int t = k0; k0 = k1; k1 = k2; k2 = t;
     }
-    pv_half(rg.vt[k2], 1, pf_b, x, h, o);   // the last half: tile n_kt-1 now sits in slot k2
+    pv_half(rg.vt[k2], 1, pf_b, fo, o);   // the last half: V image n_kt-1 now sits in slot k2
 
     // overflow check: with a fixed reference a runaway logit shows up as inf / nan in the sums
     float l[2];
@@ -464,30 +472,30 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
             for (int v = 0; v < 16; ++v) chk += fabsf(o[md][nb][v]);
         bad = bad || !(chk < INFINITY) || !(l[nb] > 0.f);
     }
-    const int any_bad = __syncthreads_or(bad ? 1 : 0);   // also: every wave is done with the stages
+    const int any_bad = __syncthreads_or(bad ? 1 : 0);   // also: every wave is done with the rings
     if (threadIdx.x == 0) redo_flags[blockIdx.x] = any_bad;
     if (any_bad) return;
     store_output<G>(ge, o, l, mref, R, Hq, smem_raw, out, lse_out);
 }
 
 // ---- safe kernel: classic online softmax, runs only where the fast kernel raised its flag ----------
-template <int G, bool HAS_NEW>
+template <int G>
 __global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __restrict__ q_rows,
                                                                const int32_t* __restrict__ q_index, int R,
-                                                               const __bf16* __restrict__ k_cache,
-                                                               const __bf16* __restrict__ v_cache, int L,
-                                                               const __bf16* __restrict__ k_new,
-                                                               const __bf16* __restrict__ v_new,
-                                                               const int32_t* __restrict__ inv, __bf16* __restrict__ out,
+                                                               const unsigned char* __restrict__ images,
+                                                               int n_img_tiles, __bf16* __restrict__ out,
                                                                float* __restrict__ lse_out,
                                                                const int32_t* __restrict__ redo_flags, int Hq, int Hkv,
                                                                int n_row_tiles, float scale_log2e) {
     if (redo_flags != nullptr && redo_flags[blockIdx.x] == 0) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    Stage* stages = reinterpret_cast<Stage*>(smem_raw);
+    unsigned char* k_img = smem_raw;
+    unsigned char* v_img = smem_raw + K_IMG_BYTES;
     Geometry<G> ge;
     ge.init(q_index, R, Hkv, n_row_tiles);
     const int x = ge.x, h = ge.h;
+    FragOffsets fo;
+    fo.init(x, h);
     bf16x8 qf[2][8];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
@@ -504,18 +512,18 @@ __global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __r
             for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
     float lsum[2] = {0.f, 0.f};
     float m2[2] = {NEG_BIG, NEG_BIG};
-    Stager<HAS_NEW> sg;
-    sg.init(k_cache, v_cache, k_new, v_new, inv, L, Hkv, ge.g);
+    ImageStager sg;
+    sg.init(images, ge.g, n_img_tiles);
     for (int kt = 0; kt < ge.n_kt; ++kt) {
         sg.load(kt);
         __syncthreads();
-        sg.write(stages[0]);
+        sg.write(k_img);
         __syncthreads();
         if (kt * KT > ge.wp_max) continue;   // wave-uniform; the barriers stay outside
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
             f32x16 s[2];
-            qk_half(stages[0].k, mb, qf, x, h, s);
+            qk_half(k_img, mb, qf, fo, s);
             mask_half<true>(s, ge.col_pos, kt * KT + 32 * mb, h);
             bf16x8 pf[2][2];
 #pragma unroll
@@ -540,7 +548,7 @@ __global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __r
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[md][nb][v] *= alpha;
             }
-            pv_half(stages[0].vt, mb, pf, x, h, o);
+            pv_half(v_img, mb, pf, fo, o);
         }
     }
     float l[2];
@@ -550,38 +558,42 @@ __global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __r
     store_output<G>(ge, o, l, m2, R, Hq, smem_raw, out, lse_out);
 }
 
-template <int G, bool HAS_NEW>
+template <int G>
 hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                   const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
                   float* lse, const Workspace& ws, int mode, hipStream_t st) {
     const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
     constexpr int TR = Geometry<G>::TR;
     const int n_row_tiles = (R + TR - 1) / TR;
+    const int n_img_tiles = (int)((L + KT - 1) / KT);
     const size_t lds_fast = sizeof(Rings) > EPILOGUE_LDS ? sizeof(Rings) : EPILOGUE_LDS;
-    const size_t lds_safe = sizeof(Stage) > EPILOGUE_LDS ? sizeof(Stage) : EPILOGUE_LDS;
+    const size_t lds_safe = (size_t)IMG_BYTES > EPILOGUE_LDS ? (size_t)IMG_BYTES : EPILOGUE_LDS;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, HAS_NEW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_running_max_kernel<G, HAS_NEW>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_running_max_kernel<G>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_safe);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(n_row_tiles * s.Hkv), block(256);
     if ((size_t)grid.x > ws.attn_flags_elems) return hipErrorInvalidValue;
+    if ((size_t)n_img_tiles * s.Hkv * IMG_BYTES > ws.kv_images_bytes) return hipErrorInvalidValue;
+    pack_kv_images_kernel<<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
+        (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
+        k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, ws.kv_images);
     const int32_t* flags = ws.attn_flags;
     if (mode != FR_ATTN_SOFTMAX_RUNNING_MAX)
-        attn_fixed_ref_kernel<G, HAS_NEW><<<grid, block, lds_fast, st>>>(
-            (const __bf16*)q_rows, q_index, R, (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L,
-            (const __bf16*)k_new, (const __bf16*)v_new, inv, (__bf16*)out, lse, ws.attn_flags, s.Hq, s.Hkv, n_row_tiles,
-            scale_log2e);
+        attn_fixed_ref_kernel<G><<<grid, block, lds_fast, st>>>((const __bf16*)q_rows, q_index, R, ws.kv_images,
+                                                                n_img_tiles, (__bf16*)out, lse, ws.attn_flags, s.Hq,
+                                                                s.Hkv, n_row_tiles, scale_log2e);
     else
         flags = nullptr;   // recompute every workgroup with the running maximum
-    attn_running_max_kernel<G, HAS_NEW><<<grid, block, lds_safe, st>>>(
-        (const __bf16*)q_rows, q_index, R, (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new,
-        (const __bf16*)v_new, inv, (__bf16*)out, lse, flags, s.Hq, s.Hkv, n_row_tiles, scale_log2e);
+    attn_running_max_kernel<G><<<grid, block, lds_safe, st>>>((const __bf16*)q_rows, q_index, R, ws.kv_images,
+                                                              n_img_tiles, (__bf16*)out, lse, flags, s.Hq, s.Hkv,
+                                                              n_row_tiles, scale_log2e);
     return hipGetLastError();
 }
 
@@ -595,17 +607,12 @@ hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q
                             const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv,
                             void* out, float* lse, const Workspace& ws, int mode, hipStream_t st) {
     if (R == 0) return hipSuccess;
-#define FR_GO(GG)                                                                                                    \
-    return (k_new != nullptr)                                                                                        \
-               ? launch<GG, true>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st) \
-               : launch<GG, false>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st)
     switch (s.G) {
-        case 1: FR_GO(1);
-        case 2: FR_GO(2);
-        case 4: FR_GO(4);
-        default: FR_GO(8);
+        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st);
+        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st);
+        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st);
+        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st);
     }
-#undef FR_GO
 }
 
 }  // namespace fr
