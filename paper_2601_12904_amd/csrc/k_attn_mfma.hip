@@ -33,6 +33,10 @@
 // copies: no lookups, no pointer selects, no permutes, no address arithmetic, no staging registers.
 #include "fr_internal.hpp"
 
+#ifndef FR_SCHED_HINTS
+#define FR_SCHED_HINTS 1
+#endif
+
 namespace fr {
 
 namespace {
@@ -308,6 +312,15 @@ __device__ __forceinline__ void pipeline_step(const unsigned char* k_next, int m
     }
     lsum[0] += psum0;
     lsum[1] += psum1;
+#if FR_SCHED_HINTS
+    // Ask the scheduler to alternate matrix and transcendental instructions (the two long-latency strands);
+    // measured: a few per cent over its own order, while fuller patterns (LDS reads, other vector work) lose.
+#pragma unroll
+    for (int i = 0; i < (DO_QK ? 32 : 16); ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // matrix
+        __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);   // transcendental
+    }
+#endif
 }
 
 // Normalise, transpose through LDS and store 16 bytes per lane; lse = (m + log2 l) ln 2.
