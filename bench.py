@@ -25,9 +25,10 @@ import torch
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E peak
 
-# HBM traffic of one sparse-attention launch (bytes), from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`
-# runs of this script scaled by a copy kernel of known size; see profiles/.  None until measured.
-MEASURED_ATTN_TRAFFIC = {}
+# HBM traffic of one sparse-attention launch (bytes), from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of
+# this script scaled by a plain copy of known size (profiles/bench_config2_hbm_traffic.md): 146.0 MB fetched
+# + 27.0 MB written.  Workloads that were not measured report null.
+MEASURED_ATTN_TRAFFIC = {"llama3_8b_layer_16x1024+512": 173.0e6}
 
 
 def attention_pairs(q_index: np.ndarray) -> int:
@@ -89,6 +90,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rope-layers", type=int, default=32, help="layers in the batched rope-shift bandwidth run")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); the path has no multi-GPU part")
@@ -185,6 +188,14 @@ def main():
     rope_all_ms = a.elapsed_time(b) / reps
     rope_all_gbps = nl * bytes_rope / (rope_all_ms * 1e-3) / 1e9
     del big_src, big_dst
+
+    if args.calibrate_copy:   # 2^28 fp32 = 1 GiB read + 1 GiB written by one elementwise copy kernel
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     result = {
         "metric": "selective-prefill layer latency (ms) + attn TFLOP/s + HBM GB/s, 17k ctx 15% recompute",
