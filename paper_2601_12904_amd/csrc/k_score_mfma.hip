@@ -36,17 +36,21 @@ __device__ __forceinline__ bf16x8 zero8() {
 }
 
 // ---- pass A -------------------------------------------------------------------------------------
-// grid (query-column tiles of 256, chunk, KV head), 256 threads.
+// One workgroup = (KV head, chunk, 256 query columns).  1-D grid with the KV head as the fastest index:
+// consecutive workgroups land on different XCDs, so all query-column tiles of one (head, chunk) share one L2.
+// Key tiles are double-buffered in LDS; the next tile waits in registers while the current one is consumed.
 template <int G>
 __global__ __launch_bounds__(256) void score_lse_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                                                             ChunkTable ct, int nq, int Hq, int Hkv,
+                                                             ChunkTable ct, int nq, int Hq, int Hkv, int n_qtiles,
                                                              float scale_log2e, float* __restrict__ lse2) {
-    __shared__ __attribute__((aligned(16))) __bf16 ks_lds[64 * PITCH];
+    __shared__ __attribute__((aligned(16))) __bf16 ks_lds[2][64 * PITCH];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
-    const int c = blockIdx.y, g = blockIdx.z;
+    const int g = blockIdx.x % Hkv;
+    const int qtile = (blockIdx.x / Hkv) % n_qtiles;
+    const int c = blockIdx.x / (Hkv * n_qtiles);
     const int c0 = ct.off[c], c1 = ct.off[c + 1];
     const int NQG = nq * G;
-    const int n_base = (blockIdx.x * 4 + wave) * 64;
+    const int n_base = (qtile * 4 + wave) * 64;
 
     bf16x8 qf[2][8];
     int col_n[2];
@@ -54,26 +58,37 @@ __global__ __launch_bounds__(256) void score_lse_mfma_kernel(const __bf16* __res
     for (int nb = 0; nb < 2; ++nb) {
         const int n = n_base + 32 * nb + x;
         col_n[nb] = n;
-        const __bf16* qp = q + ((size_t)(n / G) * Hq + g * G + (n % G)) * D + 8 * h;
+        const int nc = min(n, NQG - 1);   // columns past the end copy the last one and are never stored
+        const __bf16* qp = q + ((size_t)(nc / G) * Hq + g * G + (nc % G)) * D + 8 * h;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = (n < NQG) ? *reinterpret_cast<const bf16x8*>(qp + 16 * ks) : zero8();
+        for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
     }
     float m2[2] = {NEG_BIG, NEG_BIG}, lsum[2] = {0.f, 0.f};
     const int st_vec = tid & 15, st_key = tid >> 4;
     const int n_kt = (c1 - c0 + 63) / 64;
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const int key0 = c0 + kt * 64;
-        u32x4 kreg[4];
+    u32x4 kreg[4];
+    auto load_tile = [&](int kt) {   // keys past the chunk's end are clamped (finite data) and masked below
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int j = key0 + st_key + 16 * i;
-            u32x4 z = {0u, 0u, 0u, 0u};
-            kreg[i] = (j < c1) ? *reinterpret_cast<const u32x4*>(k + ((size_t)j * Hkv + g) * D + 8 * st_vec) : z;
+            const int j = min(c0 + kt * 64 + st_key + 16 * i, c1 - 1);
+            kreg[i] = *reinterpret_cast<const u32x4*>(k + ((size_t)j * Hkv + g) * D + 8 * st_vec);
         }
-        __syncthreads();
+    };
+    auto write_tile = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&ks_lds[(st_key + 16 * i) * PITCH + 8 * st_vec]) = kreg[i];
-        __syncthreads();
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&ks_lds[buf][(st_key + 16 * i) * PITCH + 8 * st_vec]) = kreg[i];
+    };
+    if (n_kt > 0) {
+        load_tile(0);
+        write_tile(0);
+        if (n_kt > 1) load_tile(1);
+    }
+    for (int kt = 0; kt < n_kt; ++kt) {
+        const int key0 = c0 + kt * 64;
+        const int buf = kt & 1;
+        __syncthreads();   // tile kt is visible; everyone is done with tile kt-1 (the other buffer)
+        if (kt + 1 < n_kt) write_tile(buf ^ 1);
+        if (kt + 2 < n_kt) load_tile(kt + 2);
 
         f32x16 s[2][2];
 #pragma unroll
@@ -86,7 +101,7 @@ __global__ __launch_bounds__(256) void score_lse_mfma_kernel(const __bf16* __res
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ks_lds[(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ks_lds[buf][(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
                     s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s[mb][nb], 0, 0, 0);
@@ -143,19 +158,22 @@ __global__ void score_lse2_global_kernel(int n_chunks, int NQG, float* __restric
 }
 
 // ---- pass B -------------------------------------------------------------------------------------
-// grid (key tiles of 256 inside a chunk, chunk, KV head), 256 threads.  scope_global: use lse2[g][C].
+// One workgroup = (KV head, chunk, 256 keys of the chunk), KV head fastest in the 1-D grid (see pass A).
+// scope_global: use lse2[g][C].  Query-column tiles are double-buffered in LDS like the key tiles of pass A.
 template <int G>
 __global__ __launch_bounds__(256) void score_colsum_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                                                                ChunkTable ct, int nq, int Hq, int Hkv,
+                                                                ChunkTable ct, int nq, int Hq, int Hkv, int n_ktiles,
                                                                 float scale_log2e, int scope_global,
                                                                 const float* __restrict__ lse2,
                                                                 float* __restrict__ col_partial) {
-    __shared__ __attribute__((aligned(16))) __bf16 q_lds[64 * PITCH];
-    __shared__ __attribute__((aligned(16))) float lse_lds[64];
+    __shared__ __attribute__((aligned(16))) __bf16 q_lds[2][64 * PITCH];
+    __shared__ __attribute__((aligned(16))) float lse_lds[2][64];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
-    const int c = blockIdx.y, g = blockIdx.z;
+    const int g = blockIdx.x % Hkv;
+    const int ktile = (blockIdx.x / Hkv) % n_ktiles;
+    const int c = blockIdx.x / (Hkv * n_ktiles);
     const int c0 = ct.off[c], c1 = ct.off[c + 1];
-    const int kbase = c0 + blockIdx.x * 256;
+    const int kbase = c0 + ktile * 256;
     if (kbase >= c1) return;
     const int NQG = nq * G;
     const int L_ctx = ct.off[ct.n];
@@ -167,29 +185,37 @@ __global__ __launch_bounds__(256) void score_colsum_mfma_kernel(const __bf16* __
     for (int nb = 0; nb < 2; ++nb) {
         const int j = kbase + 64 * wave + 32 * nb + x;
         col_key[nb] = j;
-        const __bf16* kp = k + ((size_t)j * Hkv + g) * D + 8 * h;
+        const __bf16* kp = k + ((size_t)min(j, c1 - 1) * Hkv + g) * D + 8 * h;   // keys past the end: copy, never stored
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kf[nb][ks] = (j < c1) ? *reinterpret_cast<const bf16x8*>(kp + 16 * ks) : zero8();
+        for (int ks = 0; ks < 8; ++ks) kf[nb][ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
     }
     float csum[2] = {0.f, 0.f};
     const int st_vec = tid & 15, st_row = tid >> 4;
     const int n_qt = (NQG + 63) / 64;
-    for (int qt = 0; qt < n_qt; ++qt) {
+    u32x4 qreg[4];
+    float lv = 0.f;
+    auto load_tile = [&](int qt) {
         const int n0 = qt * 64;
-        u32x4 qreg[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int n = n0 + st_row + 16 * i;
-            u32x4 z = {0u, 0u, 0u, 0u};
-            qreg[i] = (n < NQG) ? *reinterpret_cast<const u32x4*>(q + ((size_t)(n / G) * Hq + g * G + (n % G)) * D + 8 * st_vec) : z;
+            const int n = min(n0 + st_row + 16 * i, NQG - 1);
+            qreg[i] = *reinterpret_cast<const u32x4*>(q + ((size_t)(n / G) * Hq + g * G + (n % G)) * D + 8 * st_vec);
         }
-        float lv = 0.f;
         if (tid < 64) lv = (n0 + tid < NQG) ? lrow[n0 + tid] : INFINITY;   // rows past the end contribute exp2(-inf) = 0
-        __syncthreads();
+    };
+    auto write_tile = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&q_lds[(st_row + 16 * i) * PITCH + 8 * st_vec]) = qreg[i];
-        if (tid < 64) lse_lds[tid] = lv;
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&q_lds[buf][(st_row + 16 * i) * PITCH + 8 * st_vec]) = qreg[i];
+        if (tid < 64) lse_lds[buf][tid] = lv;
+    };
+    load_tile(0);
+    write_tile(0);
+    if (n_qt > 1) load_tile(1);
+    for (int qt = 0; qt < n_qt; ++qt) {
+        const int buf = qt & 1;
         __syncthreads();
+        if (qt + 1 < n_qt) write_tile(buf ^ 1);
+        if (qt + 2 < n_qt) load_tile(qt + 2);
 
         f32x16 s[2][2];
 #pragma unroll
@@ -202,7 +228,7 @@ __global__ __launch_bounds__(256) void score_colsum_mfma_kernel(const __bf16* __
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&q_lds[(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&q_lds[buf][(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
                     s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[nb][ks], s[mb][nb], 0, 0, 0);
@@ -211,7 +237,7 @@ __global__ __launch_bounds__(256) void score_colsum_mfma_kernel(const __bf16* __
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4 lz = *reinterpret_cast<const f32x4*>(&lse_lds[32 * mb + 8 * q4 + 4 * h]);
+                const f32x4 lz = *reinterpret_cast<const f32x4*>(&lse_lds[buf][32 * mb + 8 * q4 + 4 * h]);
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -243,13 +269,14 @@ hipError_t run(const Shape& s, const void* q, int nq, const void* k_ctx, const C
     const int NQG = nq * G;
     int max_len = 0;
     for (int i = 0; i < ct.n; ++i) max_len = ct.off[i + 1] - ct.off[i] > max_len ? ct.off[i + 1] - ct.off[i] : max_len;
-    score_lse_mfma_kernel<G><<<dim3((NQG + 255) / 256, ct.n, s.Hkv), dim3(256), 0, st>>>(
-        (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, c, ws.lse);
+    const int n_qtiles = (NQG + 255) / 256, n_ktiles = (max_len + 255) / 256;
+    score_lse_mfma_kernel<G><<<dim3(n_qtiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
+        (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, n_qtiles, c, ws.lse);
     if (norm == FR_NORM_GLOBAL)
         score_lse2_global_kernel<<<dim3((NQG + 255) / 256, s.Hkv), dim3(256), 0, st>>>(ct.n, NQG, ws.lse);
-    score_colsum_mfma_kernel<G><<<dim3((max_len + 255) / 256, ct.n, s.Hkv), dim3(256), 0, st>>>(
-        (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, c, norm == FR_NORM_GLOBAL ? 1 : 0, ws.lse,
-        ws.col_partial);
+    score_colsum_mfma_kernel<G><<<dim3(n_ktiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
+        (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, n_ktiles, c, norm == FR_NORM_GLOBAL ? 1 : 0,
+        ws.lse, ws.col_partial);
     score_reduce_heads_kernel<<<dim3((L_ctx + 255) / 256), dim3(256), 0, st>>>(ws.col_partial, L_ctx, s.Hkv, scores);
     return hipGetLastError();
 }

@@ -311,3 +311,49 @@ def test_attention_logits_far_above_the_first_keys():
     H.assert_close(got, want, "bf16", "attention with runaway logits")
     assert np.max(np.abs(lse - want_lse) / np.abs(want_lse)) <= 1e-3
     ctx.close()
+
+
+@pytest.mark.parametrize("config_id,n_sample", [(2, 96), (4, 64)])
+def test_full_size_chain_sampled(config_id, n_sample):
+    """The benchmark's configurations at full size, in the launch configuration bench.py times: the whole chain
+    on the GPU; the oracle checks the Q index (all of it), the shifted keys and the attention output on a
+    sample of rows it can compute one by one, and the scattered cache on the sampled rows."""
+    w = synth.CONFIGS[config_id](seed=0)
+    dt, tdt = w.shape.dtype, H.TORCH_DTYPE[w.shape.dtype]
+    Hq, Hkv, d = w.shape.n_q_heads, w.shape.n_kv_heads, w.shape.head_dim
+    k = B.fr_topk_count(w.L_ctx, w.ratio)
+    R = k + w.nq
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    k_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_cache[: w.L_ctx] = H.dev(w.v_cached, dt)
+    qi = torch.empty(R, dtype=torch.int32, device="cuda")
+    scores = torch.empty(w.L_ctx, dtype=torch.float32, device="cuda")
+    ctx.fr_rope_shift(H.dev(w.k_cached, dt), k_cache, w.chunk_offsets, w.src_pos0)
+    k_ctx_gpu = H.host(k_cache[: w.L_ctx])
+    ctx.fr_score_select(H.dev(w.q_question, dt), w.nq, k_cache, w.chunk_offsets, k, B.FR_NORM_PER_CHUNK, scores, qi)
+    idx = qi.long()
+    q_rows = H.dev(w.q_full, dt)[idx].contiguous()
+    k_new, v_new = H.dev(w.k_full, dt)[idx].contiguous(), H.dev(w.v_full, dt)[idx].contiguous()
+    out = torch.empty((R, Hq, d), dtype=tdt, device="cuda")
+    ctx.fr_sparse_prefill_attn(q_rows, qi, R, k_cache, v_cache, w.L, k_new, v_new, out)
+    ctx.fr_kv_scatter(k_new, v_new, qi, R, k_cache, v_cache, w.L)
+    torch.cuda.synchronize()
+
+    k_ctx_o = orc.rope_shift(w.k_cached, w.chunk_offsets, w.src_pos0, None, w.shape.rope_base)
+    H.assert_close(k_ctx_gpu, k_ctx_o, dt, "shifted keys")
+    k_ctx_r = synth.round_to_storage(k_ctx_o, dt)
+    scores_o = orc.critical_scores(w.q_question, k_ctx_r, w.chunk_offsets)
+    assert H.max_rel_err(scores.cpu().numpy().astype(np.float64), scores_o) <= 2e-3   # the GPU scored its own shifted keys
+    qi_g = qi.cpu().numpy().astype(np.int64)
+    H.assert_index_set(qi_g, scores_o, k, w.nq)
+    kc = np.zeros((w.L, Hkv, d), np.float32)
+    vc = np.zeros((w.L, Hkv, d), np.float32)
+    kc[: w.L_ctx], vc[: w.L_ctx] = k_ctx_r, w.v_cached
+    rows = np.unique(np.linspace(0, R - 1, n_sample).round().astype(np.int64))
+    want, _ = orc.sparse_prefill_attn(w.q_full[qi_g], qi_g, kc, vc, w.k_full[qi_g], w.v_full[qi_g], rows=rows)
+    H.assert_close(H.host(out[torch.from_numpy(rows).cuda()]), want, dt, "sampled attention rows")
+    pos = qi_g[rows]
+    assert np.array_equal(H.host(k_cache[torch.from_numpy(pos).cuda()]), w.k_full[pos].astype(np.float64))
+    assert np.array_equal(H.host(v_cache[torch.from_numpy(pos).cuda()]), w.v_full[pos].astype(np.float64))
+    ctx.close()
