@@ -159,6 +159,33 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
 fr_status fr_kv_scatter(fr_ctx* ctx, const void* k_new, const void* v_new, const int32_t* q_index,
                         int32_t R, void* k_cache, void* v_cache, int64_t L, void* stream);
 
+/* ---- The model steps around the path, for the recomputed rows only (eq. 9: the sparse prefill feeds the
+ * rows cat(X[C_idx], Q) through every layer).  bf16 contexts only.  All matrices are row-major with the
+ * contraction dimension contiguous; M = number of rows (any), N and F multiples of 128, K a multiple of 64.
+ * Products accumulate in fp32 and are rounded once to bf16 after the fused epilogue. ---------------------- */
+
+/* out[r, :] = x[r, :] * rsqrt(mean(x[r, :]^2) + eps) * gain.   x, out dev [R, hidden]; gain dev [hidden];
+ * hidden a multiple of 8. */
+fr_status fr_rmsnorm(fr_ctx* ctx, const void* x, const void* gain, int32_t R, int32_t hidden, float eps, void* out,
+                     void* stream);
+
+/* out = a . w^T (+ residual).   a dev [M, K]; w dev [N, K]; residual dev [M, N] or NULL; out dev [M, N]
+ * (out may equal residual). */
+fr_status fr_linear(fr_ctx* ctx, const void* a, const void* w, int32_t M, int32_t N, int32_t K, const void* residual,
+                    void* out, void* stream);
+
+/* out[:, j] = silu(a . w_gate_up[2j]) * (a . w_gate_up[2j + 1]): gate and up projections with their rows
+ * interleaved in one weight matrix.   a dev [M, K]; w_gate_up dev [2 F, K]; out dev [M, F]. */
+fr_status fr_linear_swiglu(fr_ctx* ctx, const void* a, const void* w_gate_up, int32_t M, int32_t F, int32_t K,
+                           void* out, void* stream);
+
+/* Q/K/V projection of the recomputed rows with the rotary embedding of each row's own position (the position
+ * list of eq. 9, i.e. the Q index) applied to q and k; rope parameters from the context's layer description.
+ *   a dev [M, K]; w_qkv dev [(Hq + 2 Hkv) d, K]: query heads, then key heads, then value heads;
+ *   positions dev [M] int32;  q_out dev [M, Hq, d];  k_out, v_out dev [M, Hkv, d]. */
+fr_status fr_qkv_rope(fr_ctx* ctx, const void* a, const void* w_qkv, int32_t M, int32_t K, const int32_t* positions,
+                      void* q_out, void* k_out, void* v_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -255,3 +255,40 @@ def kv_deviation(kv_fa: np.ndarray, kv_fr: np.ndarray) -> np.ndarray:
     a = np.asarray(kv_fa, dtype=F64)
     b = np.asarray(kv_fr, dtype=F64)
     return ((a - b) ** 2).reshape(a.shape[0], -1).sum(axis=1)
+
+
+# --------------------------------------------------------------------------------------
+# The model steps around the path (Sec. 2.1: each layer multiplies its input by the query, key and
+# value weight matrices and adds positional embeddings by position index; eq. 9: only the rows
+# cat(X[C_idx], Q) are fed).  RMSNorm and the SwiGLU feed-forward are those of the Llama-3-8B
+# shaped layer that the full-stack configuration names; they are ordinary textbook definitions.
+# --------------------------------------------------------------------------------------
+def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """y = x / sqrt(mean(x^2) + eps) * gain, row by row."""
+    x = np.asarray(x, dtype=F64)
+    return x / np.sqrt((x * x).mean(axis=-1, keepdims=True) + eps) * np.asarray(gain, dtype=F64)
+
+
+def linear(a: np.ndarray, w: np.ndarray, residual: Optional[np.ndarray] = None) -> np.ndarray:
+    """out = a . w^T (+ residual); a [M, K], w [N, K]."""
+    out = np.asarray(a, dtype=F64) @ np.asarray(w, dtype=F64).T
+    return out if residual is None else out + np.asarray(residual, dtype=F64)
+
+
+def linear_swiglu(a: np.ndarray, w_gate_up: np.ndarray) -> np.ndarray:
+    """out[:, j] = silu(a . w[2j]) * (a . w[2j+1]), silu(t) = t / (1 + exp(-t)); gate and up rows interleaved."""
+    y = linear(a, w_gate_up)
+    gate, up = y[:, 0::2], y[:, 1::2]
+    return gate / (1.0 + np.exp(-gate)) * up
+
+
+def qkv_rope(a: np.ndarray, w_qkv: np.ndarray, positions: np.ndarray, Hq: int, Hkv: int, d: int, base: float,
+             layout: str = "interleaved", index_base: int = 0):
+    """Q/K/V projection of the fed rows, rotary embedding at each row's own position on q and k (eq. 9 feeds
+    the positions cat(C_idx, question positions)).  Weight rows: query heads, key heads, value heads."""
+    y = linear(a, w_qkv)
+    M = y.shape[0]
+    q = y[:, : Hq * d].reshape(M, Hq, d)
+    k = y[:, Hq * d: (Hq + Hkv) * d].reshape(M, Hkv, d)
+    v = y[:, (Hq + Hkv) * d:].reshape(M, Hkv, d)
+    return rope_rotate(q, positions, base, layout, index_base), rope_rotate(k, positions, base, layout, index_base), v

@@ -22,7 +22,8 @@ STATUS_NAMES = {0: "FR_OK", 1: "FR_ERR_INVALID_ARG", 2: "FR_ERR_UNSUPPORTED", 3:
 FR_OPT_ATTN_SOFTMAX = 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_topk_count", "fr_rope_shift",
-           "fr_score_select", "fr_select_topk", "fr_sparse_prefill_attn", "fr_kv_scatter")
+           "fr_score_select", "fr_select_topk", "fr_sparse_prefill_attn", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
+           "fr_linear_swiglu", "fr_qkv_rope")
 
 
 class fr_layer_desc(ctypes.Structure):
@@ -73,6 +74,14 @@ def load() -> ctypes.CDLL:
     lib.fr_sparse_prefill_attn.restype = i32
     lib.fr_kv_scatter.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, vp]
     lib.fr_kv_scatter.restype = i32
+    lib.fr_rmsnorm.argtypes = [vp, vp, vp, i32, i32, ctypes.c_float, vp, vp]
+    lib.fr_rmsnorm.restype = i32
+    lib.fr_linear.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.fr_linear.restype = i32
+    lib.fr_linear_swiglu.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.fr_linear_swiglu.restype = i32
+    lib.fr_qkv_rope.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.fr_qkv_rope.restype = i32
     _lib = lib
     return lib
 
@@ -172,3 +181,19 @@ class Context:
     def fr_kv_scatter(self, k_new, v_new, q_index, R: int, k_cache, v_cache, L: int, stream=None):
         self._check(self._lib.fr_kv_scatter(self._h, _ptr(k_new), _ptr(v_new), _ptr(q_index), int(R), _ptr(k_cache),
                                             _ptr(v_cache), int(L), _stream(stream)))
+
+    def fr_rmsnorm(self, x, gain, R: int, hidden: int, eps: float, out, stream=None):
+        self._check(self._lib.fr_rmsnorm(self._h, _ptr(x), _ptr(gain), int(R), int(hidden), float(eps), _ptr(out),
+                                         _stream(stream)))
+
+    def fr_linear(self, a, w, M: int, N: int, K: int, residual, out, stream=None):
+        self._check(self._lib.fr_linear(self._h, _ptr(a), _ptr(w), int(M), int(N), int(K), _ptr(residual), _ptr(out),
+                                        _stream(stream)))
+
+    def fr_linear_swiglu(self, a, w_gate_up, M: int, F: int, K: int, out, stream=None):
+        self._check(self._lib.fr_linear_swiglu(self._h, _ptr(a), _ptr(w_gate_up), int(M), int(F), int(K), _ptr(out),
+                                               _stream(stream)))
+
+    def fr_qkv_rope(self, a, w_qkv, M: int, K: int, positions, q_out, k_out, v_out, stream=None):
+        self._check(self._lib.fr_qkv_rope(self._h, _ptr(a), _ptr(w_qkv), int(M), int(K), _ptr(positions), _ptr(q_out),
+                                          _ptr(k_out), _ptr(v_out), _stream(stream)))

@@ -136,6 +136,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_flags = take(w.attn_flags_elems * 4);
     w.kv_images_bytes = (s.dtype == FR_BF16 && s.d == 128) ? (size_t)((max_tokens + 63) / 64) * s.Hkv * 36864 : 0;
     const size_t o_img = take(w.kv_images_bytes);
+    const size_t o_rr = take((size_t)max_tokens * (s.d / 2) * sizeof(float2));
     w.bytes = off;
     hipError_t e = hipMalloc((void**)&w.base, w.bytes);
     if (e != hipSuccess) {
@@ -150,6 +151,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.select_tmp = (uint32_t*)(w.base + o_sel);
     w.attn_flags = (int32_t*)(w.base + o_flags);
     w.kv_images = (unsigned char*)(w.base + o_img);
+    w.rope_rows = (float2*)(w.base + o_rr);
     ctx->has_device = true;
     *out = ctx;
     return FR_OK;
@@ -352,6 +354,91 @@ fr_status fr_kv_scatter(fr_ctx* ctx, const void* k_new, const void* v_new, const
     if ((st = need_device(ctx)) != FR_OK) return st;
     hipError_t e = launch_kv_scatter(ctx->shape, k_new, v_new, q_index, R, k_cache, v_cache, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "scatter launch", e);
+    return FR_OK;
+}
+
+// ---- model steps around the path -------------------------------------------------------------------
+
+static fr_status check_stack(fr_ctx* ctx, const char* what) {
+    if (ctx->shape.dtype != FR_BF16) return fail(ctx, FR_ERR_UNSUPPORTED, "%s: bf16 contexts only", what);
+    return FR_OK;
+}
+
+fr_status fr_rmsnorm(fr_ctx* ctx, const void* x, const void* gain, int32_t R, int32_t hidden, float eps, void* out,
+                     void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    fr_status st = check_stack(ctx, "fr_rmsnorm");
+    if (st != FR_OK) return st;
+    if (R < 0 || hidden <= 0 || hidden % 8 != 0) return fail(ctx, FR_ERR_INVALID_ARG, "bad R = %d / hidden = %d", R, hidden);
+    if (!(eps >= 0.f)) return fail(ctx, FR_ERR_INVALID_ARG, "eps must be non-negative");
+    if (R == 0) return FR_OK;
+    if (!x || !gain || !out || !aligned16(x) || !aligned16(gain) || !aligned16(out))
+        return fail(ctx, FR_ERR_INVALID_ARG, "x / gain / out is NULL or not 16-byte aligned");
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipError_t e = launch_rmsnorm(x, gain, R, hidden, eps, out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, "rmsnorm launch", e);
+    return FR_OK;
+}
+
+static fr_status check_gemm(fr_ctx* ctx, const char* what, const void* a, const void* w, int32_t M, int32_t N, int32_t K) {
+    fr_status st = check_stack(ctx, what);
+    if (st != FR_OK) return st;
+    if (M < 0 || N <= 0 || K <= 0) return fail(ctx, FR_ERR_INVALID_ARG, "%s: bad M = %d, N = %d, K = %d", what, M, N, K);
+    if (N % 128 != 0 || K % 64 != 0)
+        return fail(ctx, FR_ERR_UNSUPPORTED, "%s: N = %d must be a multiple of 128 and K = %d of 64", what, N, K);
+    if (M > 0 && (!a || !w || !aligned16(a) || !aligned16(w)))
+        return fail(ctx, FR_ERR_INVALID_ARG, "%s: a / w is NULL or not 16-byte aligned", what);
+    return FR_OK;
+}
+
+fr_status fr_linear(fr_ctx* ctx, const void* a, const void* w, int32_t M, int32_t N, int32_t K, const void* residual,
+                    void* out, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    fr_status st = check_gemm(ctx, "fr_linear", a, w, M, N, K);
+    if (st != FR_OK) return st;
+    if (M == 0) return FR_OK;
+    if (!out || !aligned16(out) || !aligned16(residual))
+        return fail(ctx, FR_ERR_INVALID_ARG, "fr_linear: out is NULL or out / residual not 16-byte aligned");
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipError_t e = launch_linear(a, w, M, N, K, residual, out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, "linear launch", e);
+    return FR_OK;
+}
+
+fr_status fr_linear_swiglu(fr_ctx* ctx, const void* a, const void* w_gate_up, int32_t M, int32_t F, int32_t K,
+                           void* out, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    if (F <= 0 || F > INT32_MAX / 2) return fail(ctx, FR_ERR_INVALID_ARG, "fr_linear_swiglu: bad F = %d", F);
+    fr_status st = check_gemm(ctx, "fr_linear_swiglu", a, w_gate_up, M, 2 * F, K);
+    if (st != FR_OK) return st;
+    if (M == 0) return FR_OK;
+    if (!out || !aligned16(out)) return fail(ctx, FR_ERR_INVALID_ARG, "fr_linear_swiglu: out is NULL or misaligned");
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipError_t e = launch_linear_swiglu(a, w_gate_up, M, F, K, out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, "swiglu launch", e);
+    return FR_OK;
+}
+
+fr_status fr_qkv_rope(fr_ctx* ctx, const void* a, const void* w_qkv, int32_t M, int32_t K, const int32_t* positions,
+                      void* q_out, void* k_out, void* v_out, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    const Shape& s = ctx->shape;
+    if (s.d != 128 || s.rope_layout != FR_ROPE_INTERLEAVED)
+        return fail(ctx, FR_ERR_UNSUPPORTED, "fr_qkv_rope: head_dim 128 with interleaved rotary pairs only");
+    fr_status st = check_gemm(ctx, "fr_qkv_rope", a, w_qkv, M, (s.Hq + 2 * s.Hkv) * s.d, K);
+    if (st != FR_OK) return st;
+    if (M > ctx->max_tokens) return fail(ctx, FR_ERR_WORKSPACE, "fr_qkv_rope: M = %d exceeds max_tokens", M);
+    if (M == 0) return FR_OK;
+    if (!positions || !q_out || !k_out || !v_out || !aligned16(q_out) || !aligned16(k_out) || !aligned16(v_out) ||
+        (reinterpret_cast<uintptr_t>(positions) & 3u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "fr_qkv_rope: positions / q_out / k_out / v_out is NULL or misaligned");
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipError_t e = launch_qkv_rope(s, a, w_qkv, M, K, positions, ctx->ws.rope_rows, q_out, k_out, v_out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, "qkv launch", e);
     return FR_OK;
 }
 

@@ -41,6 +41,7 @@ struct Workspace {
     uint32_t* select_tmp = nullptr; // small counters for the selection kernels
     int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
     size_t attn_flags_elems = 0;
+    float2* rope_rows = nullptr;    // [max_tokens][d/2] (cos, sin) of the recomputed rows' positions
     unsigned char* kv_images = nullptr;  // [Hkv][ceil(max_tokens / 64)] LDS-ready K / V^T tile images, 32 KB each
     size_t kv_images_bytes = 0;
 };
@@ -88,6 +89,13 @@ hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
                             const void* v_new, const int32_t* inv, void* out, float* lse,
                             const Workspace& ws, int softmax_mode, hipStream_t st);
+
+hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
+                         hipStream_t st);
+hipError_t launch_linear_swiglu(const void* a, const void* w_gate_up, int M, int F, int K, void* out, hipStream_t st);
+hipError_t launch_qkv_rope(const Shape& s, const void* a, const void* w_qkv, int M, int K, const int32_t* positions,
+                           float2* rope_rows, void* q_out, void* k_out, void* v_out, hipStream_t st);
+hipError_t launch_rmsnorm(const void* x, const void* gain, int R, int hidden, float eps, void* out, hipStream_t st);
 
 // ---- element helpers (device) ------------------------------------------------------------
 template <typename T>

@@ -1,0 +1,283 @@
+// The model steps around the selective-prefill path for the recomputed rows (the per-layer work of the
+// full-stack configuration): y = x W^T on the gfx950 matrix cores with fused epilogues, RMSNorm, and the
+// rotary table of the rows' positions.
+//
+// GEMM.  out[M, N] = a[M, K] . w[N, K]^T, bf16 in, fp32 accumulate.  Both operands are K-contiguous, so the
+// kernel computes the transposed tile C^T = W A^T with v_mfma_f32_32x32x16_bf16: output features run along the
+// accumulator's register dimension and activation rows along lanes, which puts four consecutive features of one
+// row into one lane -- rotary pairs and (gate, up) pairs are then combined without any lane exchange.
+// One workgroup (4 waves, 2 x 2) computes 128 features x 128 rows; each wave 64 x 64.  K is walked in tiles of
+// 64: both operand tiles (128 rows of 128 bytes) are copied straight into an LDS ring with direct-to-LDS loads
+// (no staging registers); each lane chooses which 16-byte chunk of its row it fetches so that chunk c of row r
+// lands at chunk position c ^ swz(r), swz(r) = (r ^ (r >> 3)) & 7: the 16-byte fragment reads (one lane per row)
+// of any 16 consecutive rows then fall into 16 distinct bank groups.
+#include "fr_internal.hpp"
+
+namespace fr {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int BF = 128;   // output features per workgroup (MFMA M side)
+constexpr int BR = 128;   // activation rows per workgroup (MFMA N side)
+constexpr int BK = 64;    // K elements per tile: 128 bytes per row
+constexpr int TILE_BYTES = 128 * BK * 2;            // one operand tile: 16 KB
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;         // W tile then A tile
+constexpr int N_STAGE = 4;
+constexpr int EPI_PITCH = 64 + 4;                   // fp32 elements per row of a wave's epilogue staging
+
+__device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
+
+// Copy one 128-row x 128-byte operand tile into LDS.  Chunk u (16 bytes) of the tile sits at byte 16 u; the
+// four waves move 4 KB each.  `rows` bounds the operand (rows past the end are clamped and never stored).
+__device__ __forceinline__ void dma_tile(const __bf16* __restrict__ base, int64_t ld, int row0, int rows, int k0,
+                                         unsigned char* lds_tile, int wave, int lane) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int u = (wave * 4 + j) * 64 + lane;
+        const int r = u >> 3, cpos = u & 7;
+        const int c = cpos ^ swz(r);
+        const __bf16* src = base + (int64_t)min(row0 + r, rows - 1) * ld + k0 + 8 * c;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(lds_tile + (wave * 4 + j) * 1024), 16, 0, 0);
+    }
+}
+
+enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_QKV_ROPE = 2, EPI_SWIGLU = 3 };
+
+struct GemmArgs {
+    const __bf16* a;        // [M, K]
+    const __bf16* w;        // [N, K]
+    int M, N, K;
+    __bf16* out;            // EPI_STORE / EPI_RESIDUAL: [M, N];  EPI_SWIGLU: [M, N / 2]
+    const __bf16* residual; // EPI_RESIDUAL: [M, N]
+    // EPI_QKV_ROPE: features [0, Hq d) -> q_out[M, Hq, d] rotated, [Hq d, (Hq + Hkv) d) -> k_out rotated, rest -> v_out
+    __bf16 *q_out, *k_out, *v_out;
+    const float2* rope;     // [M][d / 2] (cos, sin) of each row's position
+    int Hq, Hkv, d;
+};
+
+// grid.x = feature tiles (fastest), grid.y = row tiles: workgroups that share an activation tile are neighbours.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int wf = wave & 1, wr = wave >> 1;           // wave position: features x rows
+    const int f0 = blockIdx.x * BF, r0 = blockIdx.y * BR;
+    const int n_kt = g.K / BK;
+
+    // fragment byte offsets inside a tile: row (32 blk + x) of this wave's half, k step ks -> chunk (2 ks + h)
+    int frag[4][2];   // [ks][blk & 1]
+    {
+        const int keyx = (x ^ (x >> 3)) & 7;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int par = 0; par < 2; ++par) frag[ks][par] = x * 128 + (((2 * ks + h) ^ keyx ^ (4 * par)) << 4);
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+
+    auto issue = [&](int kt) {
+        unsigned char* st = smem + (kt % N_STAGE) * STAGE_BYTES;
+        dma_tile(g.w, g.K, f0, g.N, kt * BK, st, wave, lane);
+        dma_tile(g.a, g.K, r0, g.M, kt * BK, st + TILE_BYTES, wave, lane);
+    };
+#pragma unroll
+    for (int p = 0; p < N_STAGE - 1; ++p)
+        if (p < n_kt) issue(p);
+
+    for (int kt = 0; kt < n_kt; ++kt) {
+        // own copies of tile kt are the oldest outstanding: wait until at most the (N_STAGE - 2) newer tiles remain
+        if (kt + N_STAGE - 2 < n_kt) {
+            __builtin_amdgcn_s_waitcnt(0x0f70 | (8 * (N_STAGE - 2) & 15) | (((8 * (N_STAGE - 2)) >> 4) << 14));
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0f70);
+        }
+        __syncthreads();   // tile kt complete and visible; everyone is done with tile kt-1, whose stage is refilled next
+        if (kt + N_STAGE - 1 < n_kt) issue(kt + N_STAGE - 1);
+        const unsigned char* wt = smem + (kt % N_STAGE) * STAGE_BYTES + (64 * wf) * 128;
+        const unsigned char* at = smem + (kt % N_STAGE) * STAGE_BYTES + TILE_BYTES + (64 * wr) * 128;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 wfrag[2], afrag[2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                wfrag[b] = *reinterpret_cast<const bf16x8*>(wt + b * (32 * 128) + frag[ks][b]);
+                afrag[b] = *reinterpret_cast<const bf16x8*>(at + b * (32 * 128) + frag[ks][b]);
+            }
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[mb], afrag[nb], acc[mb][nb], 0, 0, 0);
+        }
+    }
+
+    // ---- epilogue: fp32 tile through LDS ([row][feature] per wave), then 8 consecutive features per lane ----
+    __syncthreads();
+    float* ep = reinterpret_cast<float*>(smem) + wave * 64 * EPI_PITCH;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                f32x4 t;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) t[e] = acc[mb][nb][4 * q4 + e];
+                *reinterpret_cast<f32x4*>(&ep[(32 * nb + x) * EPI_PITCH + 32 * mb + 8 * q4 + 4 * h]) = t;
+            }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int rl = 8 * i + (lane >> 3), seg = lane & 7;     // local row, group of 8 features
+        const int r = r0 + 64 * wr + rl;
+        const int f = f0 + 64 * wf + 8 * seg;
+        if (r >= g.M) continue;
+        float v[8];
+        {
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(&ep[rl * EPI_PITCH + 8 * seg]);
+            const f32x4 hi = *reinterpret_cast<const f32x4*>(&ep[rl * EPI_PITCH + 8 * seg + 4]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
+        }
+        if (EPI == EPI_STORE || EPI == EPI_RESIDUAL) {
+            if (EPI == EPI_RESIDUAL) {
+                const bf16x8 res = *reinterpret_cast<const bf16x8*>(g.residual + (int64_t)r * g.N + f);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += (float)res[e];
+            }
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
+            *reinterpret_cast<bf16x8*>(g.out + (int64_t)r * g.N + f) = o;
+        } else if (EPI == EPI_SWIGLU) {   // features interleaved (gate_j, up_j): out_j = silu(gate_j) * up_j
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float gt = v[2 * e], up = v[2 * e + 1];
+                o[e] = (__bf16)(gt / (1.0f + __expf(-gt)) * up);
+            }
+            *reinterpret_cast<bf16x4*>(g.out + (int64_t)r * (g.N / 2) + f / 2) = o;
+        } else {                          // EPI_QKV_ROPE
+            const int qf_end = g.Hq * g.d, kf_end = qf_end + g.Hkv * g.d;
+            __bf16* dst;
+            bool rotate = true;
+            if (f < qf_end) dst = g.q_out + (int64_t)r * qf_end + f;
+            else if (f < kf_end) dst = g.k_out + (int64_t)r * (g.Hkv * g.d) + (f - qf_end);
+            else { dst = g.v_out + (int64_t)r * (g.Hkv * g.d) + (f - kf_end); rotate = false; }
+            if (rotate) {
+                const int p0 = (f % g.d) >> 1;   // first rotary pair of this group (interleaved pairs)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float2 cs = g.rope[(int64_t)r * (g.d / 2) + p0 + e];
+                    const float a = v[2 * e], b = v[2 * e + 1];
+                    v[2 * e] = a * cs.x - b * cs.y;
+                    v[2 * e + 1] = b * cs.x + a * cs.y;
+                }
+            }
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
+            *reinterpret_cast<bf16x8*>(dst) = o;
+        }
+    }
+}
+
+// y = x * rsqrt(mean(x^2) + eps) * gain, one wave per row, fp32 statistics.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__ x, const __bf16* __restrict__ gain, int R,
+                                                      int hidden, float eps, __bf16* __restrict__ out) {
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= R) return;
+    const __bf16* xr = x + (int64_t)row * hidden;
+    float ss = 0.f;
+    for (int c = lane * 8; c < hidden; c += 512) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(xr + c);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += (float)v[e] * (float)v[e];
+    }
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    const float inv = 1.0f / sqrtf(ss / (float)hidden + eps);
+    __bf16* orow = out + (int64_t)row * hidden;
+    for (int c = lane * 8; c < hidden; c += 512) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>(xr + c);
+        const bf16x8 gn = *reinterpret_cast<const bf16x8*>(gain + c);
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (__bf16)((float)v[e] * inv * (float)gn[e]);
+        *reinterpret_cast<bf16x8*>(orow + c) = o;
+    }
+}
+
+// rope[r][p] = (cos, sin)(positions[r] * theta_p) in fp64, rounded once.
+__global__ void rope_rows_table_kernel(const int32_t* __restrict__ positions, int R, int half_d, int d, double base,
+                                       int index_base, float2* __restrict__ table) {
+    const int r = blockIdx.x, p = threadIdx.x;
+    if (r >= R || p >= half_d) return;
+    const double theta = pow(base, -2.0 * (double)(p + index_base) / (double)d);
+    double sn, cs;
+    sincos((double)positions[r] * theta, &sn, &cs);
+    table[(size_t)r * half_d + p] = make_float2((float)cs, (float)sn);
+}
+
+template <int EPI>
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
+    const size_t lds = (size_t)N_STAGE * STAGE_BYTES;   // 128 KB; the epilogue staging (4 x 64 x 68 x 4 B) fits inside
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((g.N + BF - 1) / BF, (g.M + BR - 1) / BR);
+    gemm_bf16_kernel<EPI><<<grid, dim3(256), lds, st>>>(g);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
+                         hipStream_t st) {
+    GemmArgs g{};
+    g.a = (const __bf16*)a; g.w = (const __bf16*)w; g.M = M; g.N = N; g.K = K;
+    g.out = (__bf16*)out; g.residual = (const __bf16*)residual;
+    return residual ? launch_gemm<EPI_RESIDUAL>(g, st) : launch_gemm<EPI_STORE>(g, st);
+}
+
+hipError_t launch_linear_swiglu(const void* a, const void* w_gate_up, int M, int F, int K, void* out, hipStream_t st) {
+    GemmArgs g{};
+    g.a = (const __bf16*)a; g.w = (const __bf16*)w_gate_up; g.M = M; g.N = 2 * F; g.K = K; g.out = (__bf16*)out;
+    return launch_gemm<EPI_SWIGLU>(g, st);
+}
+
+hipError_t launch_qkv_rope(const Shape& s, const void* a, const void* w_qkv, int M, int K, const int32_t* positions,
+                           float2* rope_rows, void* q_out, void* k_out, void* v_out, hipStream_t st) {
+    rope_rows_table_kernel<<<dim3(M), dim3(64), 0, st>>>(positions, M, s.d / 2, s.d, s.rope_base, s.rope_index_base,
+                                                          rope_rows);
+    GemmArgs g{};
+    g.a = (const __bf16*)a; g.w = (const __bf16*)w_qkv; g.M = M; g.N = (s.Hq + 2 * s.Hkv) * s.d; g.K = K;
+    g.q_out = (__bf16*)q_out; g.k_out = (__bf16*)k_out; g.v_out = (__bf16*)v_out; g.rope = rope_rows;
+    g.Hq = s.Hq; g.Hkv = s.Hkv; g.d = s.d;
+    return launch_gemm<EPI_QKV_ROPE>(g, st);
+}
+
+hipError_t launch_rmsnorm(const void* x, const void* gain, int R, int hidden, float eps, void* out, hipStream_t st) {
+    if (R == 0) return hipSuccess;
+    rmsnorm_kernel<<<dim3((R + 3) / 4), dim3(256), 0, st>>>((const __bf16*)x, (const __bf16*)gain, R, hidden, eps,
+                                                           (__bf16*)out);
+    return hipGetLastError();
+}
+
+}  // namespace fr

@@ -1,0 +1,74 @@
+"""GPU parity of the model steps around the path (RMSNorm, projections with fused epilogues) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fusionrag_oracle as orc
+from paper_2601_12904_amd import binding as B
+from paper_2601_12904_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+SHAPE = synth.LLAMA3_8B_BF16
+
+
+def bf(x):
+    return synth.round_to_storage(np.asarray(x, dtype=np.float32), "bf16")
+
+
+@pytest.fixture()
+def ctx():
+    c = H.make_ctx(SHAPE, 4096, 4, 64)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (130, 256, 192), (300, 384, 1024), (257, 128, 4096)])
+def test_linear(ctx, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    a, w, r = bf(rng.standard_normal((M, K))), bf(rng.standard_normal((N, K)) * 0.05), bf(rng.standard_normal((M, N)))
+    out = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    ctx.fr_linear(H.dev(a, "bf16"), H.dev(w, "bf16"), M, N, K, None, out)
+    torch.cuda.synchronize()
+    H.assert_close(H.host(out), orc.linear(a, w), "bf16", "linear")
+    res = H.dev(r, "bf16")
+    ctx.fr_linear(H.dev(a, "bf16"), H.dev(w, "bf16"), M, N, K, res, res)       # in place on the residual
+    torch.cuda.synchronize()
+    H.assert_close(H.host(res), orc.linear(a, w, r), "bf16", "linear + residual")
+
+
+@pytest.mark.parametrize("M,F,K", [(70, 64, 128), (300, 192, 320)])
+def test_linear_swiglu(ctx, M, F, K):
+    rng = np.random.default_rng(M + F)
+    a, w = bf(rng.standard_normal((M, K))), bf(rng.standard_normal((2 * F, K)) * 0.1)
+    out = torch.zeros((M, F), dtype=torch.bfloat16, device="cuda")
+    ctx.fr_linear_swiglu(H.dev(a, "bf16"), H.dev(w, "bf16"), M, F, K, out)
+    torch.cuda.synchronize()
+    H.assert_close(H.host(out), orc.linear_swiglu(a, w), "bf16", "swiglu")
+
+
+@pytest.mark.parametrize("M,K", [(5, 64), (333, 256)])
+def test_qkv_rope(ctx, M, K):
+    rng = np.random.default_rng(M)
+    Hq, Hkv, d = SHAPE.n_q_heads, SHAPE.n_kv_heads, SHAPE.head_dim
+    a, w = bf(rng.standard_normal((M, K))), bf(rng.standard_normal(((Hq + 2 * Hkv) * d, K)) * 0.1)
+    pos = np.sort(rng.choice(4000, size=M, replace=False)).astype(np.int32)
+    q = torch.zeros((M, Hq, d), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((M, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    v = torch.zeros((M, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    ctx.fr_qkv_rope(H.dev(a, "bf16"), H.dev(w, "bf16"), M, K, torch.from_numpy(pos).cuda(), q, k, v)
+    torch.cuda.synchronize()
+    qo, ko, vo = orc.qkv_rope(a, w, pos, Hq, Hkv, d, SHAPE.rope_base)
+    H.assert_close(H.host(q), qo, "bf16", "q")
+    H.assert_close(H.host(k), ko, "bf16", "k")
+    H.assert_close(H.host(v), vo, "bf16", "v")
+
+
+@pytest.mark.parametrize("R,hidden", [(1, 64), (37, 4096), (130, 520)])
+def test_rmsnorm(ctx, R, hidden):
+    rng = np.random.default_rng(R)
+    x, g = bf(rng.standard_normal((R, hidden)) * 3), bf(1 + 0.1 * rng.standard_normal(hidden))
+    out = torch.zeros((R, hidden), dtype=torch.bfloat16, device="cuda")
+    ctx.fr_rmsnorm(H.dev(x, "bf16"), H.dev(g, "bf16"), R, hidden, 1e-5, out)
+    torch.cuda.synchronize()
+    H.assert_close(H.host(out), orc.rmsnorm(x, g, 1e-5), "bf16", "rmsnorm")
