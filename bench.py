@@ -80,12 +80,80 @@ def cpu_baseline(w, k, sample_rows: int = 384):
     }, qi, scores
 
 
+def bench_stack(args):
+    """TTFT-equivalent of the full stack: 32 Llama-3-8B-shaped layers (hidden 4096, FFN 14336, random weights) of
+    selective prefill over config 2's prompt, rows chosen once by Query-Guided Selection."""
+    from paper_2601_12904_amd import binding as B
+    from paper_2601_12904_amd import stack as S
+    from paper_2601_12904_amd import synth
+    from tests import harness as H
+
+    hidden, ffn, n_layers = 4096, 14336, args.layers
+    w = synth.config_17k(seed=args.seed) if args.ratio is None else synth.config_17k(seed=args.seed, ratio=args.ratio)
+    dt, bf = w.shape.dtype, torch.bfloat16
+    Hq, Hkv, d = w.shape.n_q_heads, w.shape.n_kv_heads, w.shape.head_dim
+    k = B.fr_topk_count(w.L_ctx, w.ratio)
+    R = k + w.nq
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(args.seed)
+    layers = [S.random_layer(hidden, ffn, Hq, Hkv, d, gen) for _ in range(n_layers)]
+    st = S.SelectivePrefillStack(ctx, layers, hidden, ffn)
+    # the row set: one selection on the prompt's (synthetic) final-layer queries and shifted keys, as in config 2
+    k_sel = torch.zeros((w.L_ctx, Hkv, d), dtype=bf, device="cuda")
+    ctx.fr_rope_shift(H.dev(w.k_cached, dt), k_sel, w.chunk_offsets, w.src_pos0)
+    qi = torch.empty(R, dtype=torch.int32, device="cuda")
+    ctx.fr_score_select(H.dev(w.q_question, dt), w.nq, k_sel, w.chunk_offsets, k, B.FR_NORM_PER_CHUNK, None, qi)
+    scratch = torch.empty(R, dtype=torch.int32, device="cuda")
+    # per-layer caches: every layer has its own stale chunk cache (same distribution, different draws)
+    sig = 1.0 / np.sqrt(d)
+    k_cached = [(torch.randn((w.L_ctx, Hkv, d), generator=gen, device="cuda") * sig).to(bf) for _ in range(n_layers)]
+    k_cache = [torch.zeros((w.L, Hkv, d), dtype=bf, device="cuda") for _ in range(n_layers)]
+    v_cache = [torch.zeros((w.L, Hkv, d), dtype=bf, device="cuda") for _ in range(n_layers)]
+    for vc in v_cache:
+        vc[: w.L_ctx] = (torch.randn((w.L_ctx, Hkv, d), generator=gen, device="cuda") * sig).to(bf)
+    h0 = torch.randn((R, hidden), generator=gen, device="cuda").to(bf)
+
+    def run(select_every_layer):
+        h = h0.clone()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        st.forward(h, qi, k_cached, k_cache, v_cache, w.chunk_offsets, w.src_pos0, w.nq, w.L,
+                   select_every_layer=select_every_layer, k_select=k, q_index_scratch=scratch)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(h.float()).all())
+        return (time.perf_counter() - t0) * 1e3
+
+    for _ in range(max(1, args.warmup // 3)):
+        run(True)
+    steps = max(1, args.steps // 10)
+    ms_every = float(np.mean([run(True) for _ in range(steps)]))
+    ms_once = float(np.mean([run(False) for _ in range(steps)]))
+    gemm_flops = 2.0 * R * n_layers * (hidden * (Hq + 2 * Hkv) * d + Hq * d * hidden + 3 * hidden * ffn)
+    attn_flops = 4.0 * d * Hq * attention_pairs(qi.cpu().numpy()) * n_layers
+    print(json.dumps({
+        "metric": "TTFT-equivalent of the selective-prefill stack (ms), 17k ctx",
+        "value": round(ms_every, 3), "unit": "ms/prompt", "n_gpus": 1, "steps": steps, "warmup": max(1, args.warmup // 3),
+        "ms_per_step": round(ms_every, 3), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": dt, "data": "synthetic",
+        "config": {"workload": f"llama3_8b_stack_{n_layers}x(" + w.name + ")", "layers": n_layers, "hidden": hidden,
+                   "ffn": ffn, "recompute_ratio": w.ratio, "rows": R, "seed": args.seed,
+                   "selection": "score_select executed in every layer (result discarded); rows chosen once"},
+        "ms_selection_once": round(ms_once, 3),
+        "gemm_tflop": round(gemm_flops / 1e12, 2), "attn_tflop": round(attn_flops / 1e12, 2),
+        "overall_tflops": round((gemm_flops + attn_flops) / (ms_once * 1e-3) / 1e12, 1),
+    }))
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4])
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4, 5],
+                    help="2 = the headline layer; 5 = the 32-layer Llama-3-8B-shaped stack over config 2's prompt")
+    ap.add_argument("--layers", type=int, default=32, help="decoder layers of the --config 5 stack")
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -103,6 +171,8 @@ def main():
     from tests import harness as H
 
     torch.cuda.set_device(0)
+    if args.config == 5:
+        return bench_stack(args)
     w = synth.CONFIGS[args.config](seed=args.seed) if args.ratio is None else \
         synth.CONFIGS[args.config](seed=args.seed, ratio=args.ratio)
     dt, tdt = w.shape.dtype, H.TORCH_DTYPE[w.shape.dtype]

@@ -292,3 +292,23 @@ def qkv_rope(a: np.ndarray, w_qkv: np.ndarray, positions: np.ndarray, Hq: int, H
     k = y[:, Hq * d: (Hq + Hkv) * d].reshape(M, Hkv, d)
     v = y[:, (Hq + Hkv) * d:].reshape(M, Hkv, d)
     return rope_rotate(q, positions, base, layout, index_base), rope_rotate(k, positions, base, layout, index_base), v
+
+
+def selective_prefill_layer(h: np.ndarray, q_index: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, weights: dict,
+                            Hq: int, Hkv: int, d: int, rope_base: float, eps: float, round_fn=None, rows=None):
+    """One decoder layer of the sparse prefill (eq. 9) for the fed rows h [R, hidden] at positions q_index:
+    RMSNorm -> Q/K/V with RoPE -> sparse attention over the cache with the fresh K/V -> output projection +
+    residual -> RMSNorm -> SwiGLU feed-forward + residual.  Returns (h_out, k_new, v_new).  `round_fn`, if
+    given, is applied wherever a real pipeline stores a tensor (so that a reduced-precision pipeline can be
+    followed store by store); `rows` restricts everything after the K/V projection to a subset of rows."""
+    r = round_fn if round_fn is not None else (lambda t: t)
+    x = r(rmsnorm(h, weights["g1"], eps))
+    q, k_new, v_new = (r(t) for t in qkv_rope(x, weights["w_qkv"], q_index, Hq, Hkv, d, rope_base))
+    sel = np.arange(len(q_index)) if rows is None else np.asarray(rows)
+    attn, _ = sparse_prefill_attn(q, q_index, k_cache, v_cache, k_new, v_new, rows=sel)
+    attn = r(attn).reshape(len(sel), Hq * d)
+    h1 = r(linear(attn, weights["w_o"], np.asarray(h, dtype=F64)[sel]))
+    x2 = r(rmsnorm(h1, weights["g2"], eps))
+    act = r(linear_swiglu(x2, weights["w_gate_up"]))
+    h2 = r(linear(act, weights["w_down"], h1))
+    return h2, k_new, v_new

@@ -72,3 +72,51 @@ def test_rmsnorm(ctx, R, hidden):
     ctx.fr_rmsnorm(H.dev(x, "bf16"), H.dev(g, "bf16"), R, hidden, 1e-5, out)
     torch.cuda.synchronize()
     H.assert_close(H.host(out), orc.rmsnorm(x, g, 1e-5), "bf16", "rmsnorm")
+
+
+def test_two_layer_stack_against_oracle():
+    """A small Llama-shaped stack (real head geometry, reduced widths) end to end: every layer's output rows,
+    fresh K/V and written-back cache against the oracle, which follows the pipeline store by store."""
+    from paper_2601_12904_amd import stack as S
+    rng = np.random.default_rng(3)
+    hidden, ffn, n_layers = 256, 384, 2
+    Hq, Hkv, d = SHAPE.n_q_heads, SHAPE.n_kv_heads, SHAPE.head_dim
+    w = synth.config_small_bf16(seed=7, chunk_lens=(150, 90, 201), nq=24)
+    k = orc.topk_count(w.L_ctx, 0.2)
+    sel = np.sort(rng.choice(w.L_ctx, size=k, replace=False))
+    qi = np.concatenate([sel, w.L_ctx + np.arange(w.nq)]).astype(np.int64)
+    R = len(qi)
+    ctx = H.make_ctx(SHAPE, w.L, w.n_chunks, w.nq)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    layers = [S.random_layer(hidden, ffn, Hq, Hkv, d, gen, std=0.08) for _ in range(n_layers)]
+    st = S.SelectivePrefillStack(ctx, layers, hidden, ffn)
+    h0 = bf(rng.standard_normal((R, hidden)))
+    kc_src = [bf(rng.standard_normal(w.k_cached.shape) * 0.3) for _ in range(n_layers)]
+    vc_src = [bf(rng.standard_normal(w.v_cached.shape)) for _ in range(n_layers)]
+    k_cached = [H.dev(a, "bf16") for a in kc_src]
+    k_cache = [torch.zeros((w.L, Hkv, d), dtype=torch.bfloat16, device="cuda") for _ in range(n_layers)]
+    v_cache = [torch.zeros((w.L, Hkv, d), dtype=torch.bfloat16, device="cuda") for _ in range(n_layers)]
+    for l in range(n_layers):
+        v_cache[l][: w.L_ctx] = H.dev(vc_src[l], "bf16")
+    h = H.dev(h0, "bf16")
+    qi_d = torch.from_numpy(qi.astype(np.int32)).cuda()
+    scratch = torch.empty(R, dtype=torch.int32, device="cuda")
+    st.forward(h, qi_d, k_cached, k_cache, v_cache, w.chunk_offsets, w.src_pos0, w.nq, w.L,
+               select_every_layer=True, k_select=k, q_index_scratch=scratch)
+    torch.cuda.synchronize()
+
+    rnd = lambda t: synth.round_to_storage(np.asarray(t, dtype=np.float32), "bf16").astype(np.float64)
+    ho = h0.astype(np.float64)
+    for l, lw in enumerate(layers):
+        wd = {n: H.host(getattr(lw, n)) for n in ("g1", "w_qkv", "w_o", "g2", "w_gate_up", "w_down")}
+        kc = np.zeros((w.L, Hkv, d))
+        vc = np.zeros((w.L, Hkv, d))
+        kc[: w.L_ctx] = rnd(orc.rope_shift(kc_src[l], w.chunk_offsets, w.src_pos0, None, SHAPE.rope_base))
+        vc[: w.L_ctx] = vc_src[l]
+        ho, k_new, v_new = orc.selective_prefill_layer(ho, qi, kc, vc, wd, Hq, Hkv, d, SHAPE.rope_base, 1e-5, round_fn=rnd)
+        want_k, want_v = orc.kv_scatter(qi, k_new, v_new, kc, vc)
+        H.assert_close(H.host(k_cache[l]), want_k, "bf16", f"layer {l} K cache")
+        H.assert_close(H.host(v_cache[l]), want_v, "bf16", f"layer {l} V cache")
+    H.assert_close(H.host(h), ho, "bf16", "stack output")
+    ctx.close()
