@@ -273,41 +273,49 @@ __device__ __forceinline__ void pipeline_step(const unsigned char* k_next, int m
 #pragma unroll
             for (int v = 0; v < 16; ++v) s_nxt[nb][v] = 0.f;
     }
-    // strand 1 + first half of the weights (query column block 0)
+    // Operand fragments are requested from LDS PF matrix steps before their use (rotating register buffer), so the
+    // LDS latency overlaps the matrix and vector work already in flight.
+    constexpr int PF = 3;
+    bf16x8 fr[PF + 1];
+    auto frag = [&](int i) -> bf16x8 {   // i < 8: K fragment ks = i of the next half;  i >= 8: V fragment (kk, md)
+        if (i < 8) return *reinterpret_cast<const bf16x8*>(k_next + fo.k + 32 * i + mb_next * (32 * K_ROW));
+        const int j = i - 8, kk = j >> 2, md = j & 3;
+        return *reinterpret_cast<const bf16x8*>(vt_prev + fo.v + 32 * (2 * mb_prev + kk) + md * (32 * V_ROW));
+    };
+    constexpr int first = DO_QK ? 0 : 8;
+#pragma unroll
+    for (int i = 0; i < PF; ++i) fr[i] = frag(first + i);
     float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        if (DO_QK) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(k_next + fo.k + 32 * ks + mb_next * (32 * K_ROW));
+    for (int i = first; i < 16; ++i) {
+        if (i + PF < 16) fr[(i - first + PF) % (PF + 1)] = frag(i + PF);
+        const bf16x8 a = fr[(i - first) % (PF + 1)];
+        if (i < 8) {
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-                s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s_nxt[nb], 0, 0, 0);
-        }
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int v = 2 * ks + e;
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[0][v], scale_log2e, -mref[0]));
-            psum0 += p;
-            pf_cur[0][v >> 3][v & 7] = (__bf16)p;
-        }
-    }
-    // strand 2 + second half of the weights (query column block 1)
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-        const int kb = 2 * mb_prev + kk;
-#pragma unroll
-        for (int md = 0; md < 4; ++md) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(vt_prev + fo.v + 32 * kb + md * (32 * V_ROW));
+            for (int nb = 0; nb < 2; ++nb) s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][i], s_nxt[nb], 0, 0, 0);
+        } else {
+            const int j = i - 8, kk = j >> 2, md = j & 3;
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
                 o[md][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf_prev[nb][kk], o[md][nb], 0, 0, 0);
+        }
+        if (DO_QK || i >= 8) {   // two weights per matrix step: column block 0 during the logits, block 1 during the output
+            const int nb = (i < 8) ? 0 : 1;
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const int v = 8 * kk + 2 * md + e;
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[1][v], scale_log2e, -mref[1]));
-                psum1 += p;
-                pf_cur[1][v >> 3][v & 7] = (__bf16)p;
+                const int v = 2 * (i & 7) + e;
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[nb][v], scale_log2e, -mref[nb]));
+                if (nb == 0) psum0 += p; else psum1 += p;
+                pf_cur[nb][v >> 3][v & 7] = (__bf16)p;
             }
+        }
+    }
+    if (!DO_QK) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[0][v], scale_log2e, -mref[0]));
+            psum0 += p;
+            pf_cur[0][v >> 3][v & 7] = (__bf16)p;
         }
     }
     lsum[0] += psum0;
