@@ -2,11 +2,13 @@
 // and the Q index of Sec. 4.3 (ascending critical tokens, then the question tokens).
 //
 // Integer work only.  Scores are mapped to order-preserving 32-bit keys; a most-significant-digit
-// radix select (4 passes of 8 bits, LDS histograms) finds the key of the k-th largest score; an
+// radix select (at most 4 passes of 8 bits, LDS histograms) finds the key of the k-th largest score; an
 // ordered compaction then emits, in index order, every token above that key plus the first
 // (lowest-index) tokens equal to it that are still needed.  The result is unique, so it does not
 // depend on scheduling.  One workgroup: the 64 KB of scores of a 17k-token prompt fit its registers, and the
-// whole selection is latency- rather than bandwidth-sized.
+// whole selection is latency- rather than bandwidth-sized.  Scores of one prompt are clustered (their sign and
+// most exponent bits agree), which would pile a plain histogram onto one or two bins; the digits are therefore
+// taken from key - min(key), starting at the highest bit in which the largest and the smallest key differ.
 #include "fr_internal.hpp"
 
 namespace fr {
@@ -17,33 +19,6 @@ __device__ __forceinline__ uint32_t score_key(float f) {
 }
 
 constexpr int SEL_THREADS = 1024;
-
-// exclusive prefix sum of one value per thread over the block; *total = block sum
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_sums, uint32_t* total) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t inc = v;
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t t = __shfl_up(inc, o);
-        if (lane >= o) inc += t;
-    }
-    if (lane == 63) wave_sums[wave] = inc;
-    __syncthreads();
-    if (wave == 0) {
-        uint32_t w = (lane < SEL_THREADS / 64) ? wave_sums[lane] : 0u;
-        uint32_t winc = w;
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t t = __shfl_up(winc, o);
-            if (lane >= o) winc += t;
-        }
-        if (lane < SEL_THREADS / 64) wave_sums[lane] = winc - w;  // exclusive wave offsets
-        if (lane == SEL_THREADS / 64 - 1) wave_sums[SEL_THREADS / 64] = winc;
-    }
-    __syncthreads();
-    const uint32_t res = wave_sums[wave] + inc - v;
-    *total = wave_sums[SEL_THREADS / 64];
-    __syncthreads();
-    return res;
-}
 
 // Among the candidates of this pass (keys that share the digits fixed so far), the digit of the k-th largest
 // key is the largest d whose suffix count S[d] = sum_{b >= d} hist[b] still reaches `remaining`.  One thread
@@ -74,98 +49,138 @@ __device__ __forceinline__ void pick_digit(const uint32_t* hist, uint32_t* wave_
     __syncthreads();
 }
 
-// PER > 0: every thread keeps its PER consecutive keys in registers (n <= SEL_THREADS * PER);
+__device__ __forceinline__ uint32_t lanes_below(uint64_t ballot) {   // set bits of lanes lower than this one
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+}
+
+// Wave w owns the contiguous index range [w * 64 * per, (w + 1) * 64 * per); its i-th load covers the 64
+// consecutive tokens base + 64 i + lane, so loads and stores are coalesced and (i, lane) order is index order.
+// PER > 0: every thread keeps its PER keys in registers (n <= SEL_THREADS * PER);
 // PER == 0: any n, the scores are re-read from memory in every pass.
 template <int PER>
 __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* __restrict__ scores, int64_t n,
                                                                   int64_t k, int nq, int32_t* __restrict__ out) {
+    constexpr int WAVES = SEL_THREADS / 64;
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t wave_sums[SEL_THREADS / 64 + 1];
+    __shared__ uint32_t wave_a[WAVES], wave_b[WAVES];
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t s_prefix, s_remaining;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     // question tokens: positions n .. n + nq - 1
     for (int i = tid; i < nq; i += SEL_THREADS) out[k + i] = (int32_t)(n + i);
     if (k <= 0 || n <= 0) return;
 
-    // thread t owns the contiguous index range [lo, hi)
-    const int64_t per = (PER > 0) ? PER : (n + SEL_THREADS - 1) / SEL_THREADS;
-    const int64_t lo = min(n, (int64_t)tid * per), hi = min(n, lo + per);
-    const int cnt = (int)(hi - lo);
+    const int per = (PER > 0) ? PER : (int)((n + SEL_THREADS - 1) / SEL_THREADS);
+    const int64_t first = (int64_t)wave * 64 * per + lane;     // this lane's tokens: first + 64 i
+    const int cnt = (int)max((int64_t)0, min((int64_t)per, (n - first + 63) / 64));
     uint32_t keys[PER > 0 ? PER : 1];
     if (PER > 0) {
+        // branch-free: every load is issued (index clamped into the array) before the first one is waited for
+        float raw[PER > 0 ? PER : 1];
 #pragma unroll
-        for (int i = 0; i < PER; ++i) keys[i] = (i < cnt) ? score_key(scores[lo + i]) : 0u;
+        for (int i = 0; i < PER; ++i) raw[i] = scores[min(first + 64 * i, n - 1)];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) keys[i] = (i < cnt) ? score_key(raw[i]) : 0u;
     }
-    auto key_at = [&](int i) -> uint32_t { return (PER > 0) ? keys[i] : score_key(scores[lo + i]); };
+    auto key_at = [&](int i) -> uint32_t { return (PER > 0) ? keys[i] : score_key(scores[first + 64 * (int64_t)i]); };
 
     uint32_t thr_key = 0u;     // key of the k-th largest score
     uint32_t need_eq = 0u;     // how many tokens equal to it are taken
     const bool take_all = (k >= n);
     if (!take_all) {
+        // range of the keys: block-wide minimum and maximum
+        uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+        if (PER > 0) {
+#pragma unroll
+            for (int i = 0; i < PER; ++i)
+                if (i < cnt) { kmin = min(kmin, keys[i]); kmax = max(kmax, keys[i]); }
+        } else {
+            for (int i = 0; i < cnt; ++i) { const uint32_t key = key_at(i); kmin = min(kmin, key); kmax = max(kmax, key); }
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
+        }
+        if (lane == 0) { wave_a[wave] = kmin; wave_b[wave] = kmax; }
         if (tid == 0) { s_prefix = 0u; s_remaining = (uint32_t)k; }
+        __syncthreads();
+        kmin = wave_a[0];
+        kmax = wave_b[0];
+        for (int w2 = 1; w2 < WAVES; ++w2) { kmin = min(kmin, wave_a[w2]); kmax = max(kmax, wave_b[w2]); }
+        // relative keys rk = key - kmin lie in [0, kmax - kmin]; digits of 8 bits (the last one narrower) are taken
+        // from the highest bit in which the two extremes differ downwards
+        const uint32_t span = kmax - kmin;
+        int hi_bit = (span == 0u) ? 1 : 32 - __clz((int)span);   // number of significant bits of the relative keys
         uint32_t mask = 0u;
-        for (int pass = 0; pass < 4; ++pass) {
-            const int shift = 24 - 8 * pass;
+        while (hi_bit > 0) {
+            const int width = min(8, hi_bit), shift = hi_bit - width;
+            const uint32_t digit_mask = (1u << width) - 1u;
             if (tid < 256) hist[tid] = 0u;
             __syncthreads();
             const uint32_t prefix = s_prefix;
             if (PER > 0) {
 #pragma unroll
-                for (int i = 0; i < PER; ++i)
-                    if (i < cnt && (keys[i] & mask) == prefix) atomicAdd(&hist[(keys[i] >> shift) & 255u], 1u);
+                for (int i = 0; i < PER; ++i) {
+                    const uint32_t rk = keys[i] - kmin;
+                    if (i < cnt && (rk & mask) == prefix) atomicAdd(&hist[(rk >> shift) & digit_mask], 1u);
+                }
             } else {
                 for (int i = 0; i < cnt; ++i) {
-                    const uint32_t key = key_at(i);
-                    if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                    const uint32_t rk = key_at(i) - kmin;
+                    if ((rk & mask) == prefix) atomicAdd(&hist[(rk >> shift) & digit_mask], 1u);
                 }
             }
             __syncthreads();
             pick_digit(hist, wave_tot, &s_prefix, &s_remaining, shift);
-            mask |= 0xFFu << shift;
+            mask |= digit_mask << shift;
+            hi_bit = shift;
         }
-        thr_key = s_prefix;
+        thr_key = s_prefix + kmin;
         need_eq = s_remaining;
     }
 
-    // ordered compaction
-    uint32_t cnt_gt = 0u, cnt_eq = 0u;
+    // ordered compaction: per-wave counts by ballots, one exchange of the 16 wave totals, then every wave
+    // writes its tokens in (i, lane) order
+    auto is_gt = [&](int i, uint32_t key) { return i < cnt && (take_all || key > thr_key); };
+    auto is_eq = [&](int i, uint32_t key) { return i < cnt && !take_all && key == thr_key; };
+    uint32_t w_gt = 0u, w_eq = 0u;
     if (PER > 0) {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            cnt_gt += (i < cnt && (take_all || keys[i] > thr_key)) ? 1u : 0u;
-            cnt_eq += (i < cnt && !take_all && keys[i] == thr_key) ? 1u : 0u;
+            w_gt += (uint32_t)__popcll(__ballot(is_gt(i, keys[i])));
+            w_eq += (uint32_t)__popcll(__ballot(is_eq(i, keys[i])));
         }
     } else {
-        for (int i = 0; i < cnt; ++i) {
-            const uint32_t key = key_at(i);
-            cnt_gt += (take_all || key > thr_key) ? 1u : 0u;
-            cnt_eq += (!take_all && key == thr_key) ? 1u : 0u;
+        for (int i = 0; i < per; ++i) {
+            const uint32_t key = (i < cnt) ? key_at(i) : 0u;
+            w_gt += (uint32_t)__popcll(__ballot(is_gt(i, key)));
+            w_eq += (uint32_t)__popcll(__ballot(is_eq(i, key)));
         }
     }
-    uint32_t total;
-    const uint32_t eq_before = block_exclusive_scan(cnt_eq, wave_sums, &total);
-    uint32_t eq_take = 0u;
-    if (need_eq > eq_before) eq_take = min(cnt_eq, need_eq - eq_before);
-    const uint32_t out_before = block_exclusive_scan(cnt_gt + eq_take, wave_sums, &total);
-    uint32_t pos = out_before, eq_left = eq_take;
+    __syncthreads();   // wave_a / wave_b are free again
+    if (lane == 0) { wave_a[wave] = w_gt; wave_b[wave] = w_eq; }
+    __syncthreads();
+    uint32_t eq_seen = 0u, pos = 0u;   // equal keys and outputs of the waves before this one
+    for (int w2 = 0; w2 < wave; ++w2) {
+        const uint32_t e = wave_b[w2];
+        pos += wave_a[w2] + ((need_eq > eq_seen) ? min(e, need_eq - eq_seen) : 0u);
+        eq_seen += e;
+    }
+    auto emit = [&](int i, uint32_t key) {
+        const bool gt = is_gt(i, key), eq = is_eq(i, key);
+        const uint64_t beq = __ballot(eq);
+        const bool sel = gt || (eq && eq_seen + lanes_below(beq) < need_eq);
+        const uint64_t bsel = __ballot(sel);
+        if (sel) out[pos + lanes_below(bsel)] = (int32_t)(first + 64 * (int64_t)i);
+        pos += (uint32_t)__popcll(bsel);
+        eq_seen += (uint32_t)__popcll(beq);
+    };
     if (PER > 0) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            if (i < cnt) {
-                bool sel = take_all || keys[i] > thr_key;
-                if (!take_all && keys[i] == thr_key && eq_left > 0u) { sel = true; --eq_left; }
-                if (sel) out[pos++] = (int32_t)(lo + i);
-            }
-        }
+        for (int i = 0; i < PER; ++i) emit(i, keys[i]);
     } else {
-        for (int i = 0; i < cnt; ++i) {
-            const uint32_t key = key_at(i);
-            bool sel = take_all || key > thr_key;
-            if (!take_all && key == thr_key && eq_left > 0u) { sel = true; --eq_left; }
-            if (sel) out[pos++] = (int32_t)(lo + i);
-        }
+        for (int i = 0; i < per; ++i) emit(i, (i < cnt) ? key_at(i) : 0u);
     }
 }
 
@@ -175,6 +190,8 @@ hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int3
     if (k + nq == 0) return hipSuccess;
     if (n <= (int64_t)SEL_THREADS * 8)
         select_topk_kernel<8><<<dim3(1), dim3(SEL_THREADS), 0, st>>>(scores, n, k, nq, q_index);
+    else if (n <= (int64_t)SEL_THREADS * 16)
+        select_topk_kernel<16><<<dim3(1), dim3(SEL_THREADS), 0, st>>>(scores, n, k, nq, q_index);
     else if (n <= (int64_t)SEL_THREADS * 32)
         select_topk_kernel<32><<<dim3(1), dim3(SEL_THREADS), 0, st>>>(scores, n, k, nq, q_index);
     else

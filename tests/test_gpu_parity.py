@@ -137,17 +137,23 @@ def test_score_select(name, seed, norm):
 
 
 @pytest.mark.parametrize("n,k,nq", [(1, 1, 0), (1, 0, 3), (7, 3, 2), (1000, 150, 5), (1024, 1024, 0), (4097, 1, 1),
-                                    (16384, 2458, 512), (50000, 7500, 17), (16384, 16383, 0)])
+                                    (16384, 2458, 512), (20001, 3000, 0), (50000, 7500, 17), (16384, 16383, 0)])
 def test_select_topk_exact(n, k, nq):
     ctx = H.make_ctx(synth.TINY_F32, 70000, 4, 600)
     rng = np.random.default_rng(n + k)
-    for kind in ("uniform", "ties", "signed", "constant"):
+    for kind in ("uniform", "ties", "signed", "constant", "clustered", "full_range"):
         if kind == "uniform":
             s = rng.random(n).astype(np.float32)
         elif kind == "ties":
             s = rng.integers(0, 8, size=n).astype(np.float32)          # heavy ties: lowest index must win
         elif kind == "signed":
             s = rng.standard_normal(n).astype(np.float32)
+        elif kind == "clustered":                                       # narrow key range, as real score vectors
+            s = (16.0 * np.exp(0.6 * rng.standard_normal(n))).astype(np.float32)
+        elif kind == "full_range":                                      # extremes that span all 32 key bits
+            s = (16.0 * np.exp(0.6 * rng.standard_normal(n))).astype(np.float32)
+            s[n // 2] = -3.0e38
+            s[n // 3] = 3.0e38
         else:
             s = np.full(n, 0.25, dtype=np.float32)
         out = torch.full((k + nq,), -7, dtype=torch.int32, device="cuda")
