@@ -15,6 +15,8 @@
 // All sums run in a fixed order: the scores are reproducible bit for bit.
 #include "fr_internal.hpp"
 
+#include <type_traits>
+
 namespace fr {
 
 namespace {
@@ -35,14 +37,43 @@ __device__ __forceinline__ bf16x8 zero8() {
     return z;
 }
 
+// One 32-row half of a 64-row LDS tile against this wave's 64 register-resident columns: s[nb] (32 x 32 each).
+__device__ __forceinline__ void half_product(const __bf16* tile, int mb, int x, int h, const bf16x8 (&bf)[2][8],
+                                             f32x16 (&s)[2]) {
+    f32x16 zero;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&tile[(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+            s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bf[nb][ks], ks == 0 ? zero : s[nb], 0, 0, 0);
+    }
+}
+
+// Asks the scheduler to alternate matrix and transcendental instructions in the enclosing block, so that the
+// products of one half tile are issued between the exponentials of the half before it.
+__device__ __forceinline__ void interleave_hint() {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // two transcendental
+    }
+}
+
 // ---- pass A -------------------------------------------------------------------------------------
 // One workgroup = (KV head, chunk, 256 query columns).  1-D grid with the KV head as the fastest index:
 // consecutive workgroups land on different XCDs, so all query-column tiles of one (head, chunk) share one L2.
-// Key tiles are double-buffered in LDS; the next tile waits in registers while the current one is consumed.
+// Key tiles are double-buffered in LDS; the tile after the next waits in registers.  The work runs in halves of 32
+// keys, software-pipelined: the products of a half are issued while the exponentials of the half before it
+// run.  Every lane keeps a running maximum and sum over the keys it sees itself (one of the two 4-row groups in
+// every 8 keys); the two lanes of a query column are merged once at the end.
 template <int G>
-__global__ __launch_bounds__(256) void score_lse_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                                                             ChunkTable ct, int nq, int Hq, int Hkv, int n_qtiles,
-                                                             float scale_log2e, float* __restrict__ lse2) {
+__global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __restrict__ q,
+                                                                const __bf16* __restrict__ k, ChunkTable ct, int nq,
+                                                                int Hq, int Hkv, int n_qtiles, float scale_log2e,
+                                                                float* __restrict__ lse2) {
     __shared__ __attribute__((aligned(16))) __bf16 ks_lds[2][64 * PITCH];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int g = blockIdx.x % Hkv;
@@ -67,7 +98,8 @@ __global__ __launch_bounds__(256) void score_lse_mfma_kernel(const __bf16* __res
     const int st_vec = tid & 15, st_key = tid >> 4;
     const int n_kt = (c1 - c0 + 63) / 64;
     u32x4 kreg[4];
-    auto load_tile = [&](int kt) {   // keys past the chunk's end are clamped (finite data) and masked below
+    auto load_tile = [&](int kt) {   // tiles past the last one re-read it; keys past the chunk's end are clamped
+        kt = min(kt, n_kt - 1);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int j = min(c0 + kt * 64 + st_key + 16 * i, c1 - 1);
@@ -78,67 +110,62 @@ __global__ __launch_bounds__(256) void score_lse_mfma_kernel(const __bf16* __res
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&ks_lds[buf][(st_key + 16 * i) * PITCH + 8 * st_vec]) = kreg[i];
     };
-    if (n_kt > 0) {
-        load_tile(0);
-        write_tile(0);
-        if (n_kt > 1) load_tile(1);
-    }
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const int key0 = c0 + kt * 64;
-        const int buf = kt & 1;
-        __syncthreads();   // tile kt is visible; everyone is done with tile kt-1 (the other buffer)
-        if (kt + 1 < n_kt) write_tile(buf ^ 1);
-        if (kt + 2 < n_kt) load_tile(kt + 2);
-
-        f32x16 s[2][2];
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+    // running log-sum-exp of one half: rows (keys) key_lo + 8 (v / 4) + 4 h + v % 4 of the accumulator
+    auto fold_half = [&](auto ragged, f32x16 (&s)[2], int key_lo) {
+        if constexpr (decltype(ragged)::value) {   // last tile of the chunk: keys past its end do not count
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) s[mb][nb][v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ks_lds[buf][(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-                    s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nb][ks], s[mb][nb], 0, 0, 0);
-            }
-        if (key0 + 64 > c1) {   // ragged tail of the chunk
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        if (key0 + 32 * mb + 8 * (v >> 2) + 4 * h + (v & 3) >= c1) s[mb][nb][v] = -INFINITY;
+                for (int v = 0; v < 16; ++v)
+                    if (key_lo + 8 * (v >> 2) + 4 * h + (v & 3) >= c1) s[nb][v] = -INFINITY;
         }
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
             float mx = NEG_BIG;
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[mb][nb][v]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[nb][v]);
             const float m_new = fmaxf(m2[nb], mx * scale_log2e);
             float psum = 0.f;
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    psum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][nb][v], scale_log2e, -m_new));
+            for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(__builtin_fmaf(s[nb][v], scale_log2e, -m_new));
             lsum[nb] = lsum[nb] * __builtin_amdgcn_exp2f(m2[nb] - m_new) + psum;
             m2[nb] = m_new;
         }
+    };
+    // One key tile, branch-free: the products that are issued past the last tile read a stale buffer and are
+    // dropped; the tiles written past the last one are never read.
+    f32x16 s_a[2], s_b[2];
+    auto tile_step = [&](auto ragged, int kt) {
+        const int key0 = c0 + kt * 64;
+        const int buf = kt & 1;
+        half_product(ks_lds[buf], 1, x, h, qf, s_b);
+        fold_half(ragged, s_a, key0);
+        interleave_hint();
+        __syncthreads();   // everyone is done with tile kt; tile kt+1 (written one iteration ago) is visible
+        write_tile(buf);        // tile kt+2
+        load_tile(kt + 3);
+        half_product(ks_lds[buf ^ 1], 0, x, h, qf, s_a);
+        fold_half(ragged, s_b, key0 + 32);
+        interleave_hint();
+    };
+    if (n_kt > 0) {
+        load_tile(0);
+        write_tile(0);
+        load_tile(1);
+        write_tile(1);
+        load_tile(2);
+        __syncthreads();
+        half_product(ks_lds[0], 0, x, h, qf, s_a);
+        for (int kt = 0; kt < n_kt - 1; ++kt) tile_step(std::false_type{}, kt);
+        tile_step(std::true_type{}, n_kt - 1);
     }
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const float l = lsum[nb] + __shfl_xor(lsum[nb], 32);
+    for (int nb = 0; nb < 2; ++nb) {   // merge the two lanes of a query column
+        const float m_o = __shfl_xor(m2[nb], 32), l_o = __shfl_xor(lsum[nb], 32);
+        const float m = fmaxf(m2[nb], m_o);
+        const float l = lsum[nb] * __builtin_amdgcn_exp2f(m2[nb] - m) + l_o * __builtin_amdgcn_exp2f(m_o - m);
         if (h == 0 && col_n[nb] < NQG)
-            lse2[((size_t)g * (ct.n + 1) + c) * NQG + col_n[nb]] = (l > 0.f) ? m2[nb] + __builtin_amdgcn_logf(l) : -INFINITY;
+            lse2[((size_t)g * (ct.n + 1) + c) * NQG + col_n[nb]] = (l > 0.f) ? m + __builtin_amdgcn_logf(l) : -INFINITY;
     }
 }
 
@@ -159,15 +186,16 @@ __global__ void score_lse2_global_kernel(int n_chunks, int NQG, float* __restric
 
 // ---- pass B -------------------------------------------------------------------------------------
 // One workgroup = (KV head, chunk, 256 keys of the chunk), KV head fastest in the 1-D grid (see pass A).
-// scope_global: use lse2[g][C].  Query-column tiles are double-buffered in LDS like the key tiles of pass A.
+// scope_global: use lse2[g][C].  Query-column tiles are double-buffered in LDS and consumed in pipelined halves
+// like the key tiles of pass A.
 template <int G>
-__global__ __launch_bounds__(256) void score_colsum_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+__global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                                                                 ChunkTable ct, int nq, int Hq, int Hkv, int n_ktiles,
                                                                 float scale_log2e, int scope_global,
                                                                 const float* __restrict__ lse2,
                                                                 float* __restrict__ col_partial) {
     __shared__ __attribute__((aligned(16))) __bf16 q_lds[2][64 * PITCH];
-    __shared__ __attribute__((aligned(16))) float lse_lds[2][64];
+    __shared__ __attribute__((aligned(16))) float lse_lds[4][64];   // four slots: a tile's normalisers outlive its rows
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int g = blockIdx.x % Hkv;
     const int ktile = (blockIdx.x / Hkv) % n_ktiles;
@@ -194,56 +222,54 @@ __global__ __launch_bounds__(256) void score_colsum_mfma_kernel(const __bf16* __
     const int n_qt = (NQG + 63) / 64;
     u32x4 qreg[4];
     float lv = 0.f;
-    auto load_tile = [&](int qt) {
-        const int n0 = qt * 64;
+    auto load_tile = [&](int qt) {   // tiles past the last one re-read it
+        const int n0 = min(qt, n_qt - 1) * 64;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int n = min(n0 + st_row + 16 * i, NQG - 1);
             qreg[i] = *reinterpret_cast<const u32x4*>(q + ((size_t)(n / G) * Hq + g * G + (n % G)) * D + 8 * st_vec);
         }
-        if (tid < 64) lv = (n0 + tid < NQG) ? lrow[n0 + tid] : INFINITY;   // rows past the end contribute exp2(-inf) = 0
+        // all four waves fetch the same 64 normalisers (no branch); rows past the end contribute exp2(-inf) = 0
+        const float lraw = lrow[min(n0 + lane, NQG - 1)];
+        lv = (n0 + lane < NQG) ? lraw : INFINITY;
     };
-    auto write_tile = [&](int buf) {
+    auto write_tile = [&](int qt) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&q_lds[buf][(st_row + 16 * i) * PITCH + 8 * st_vec]) = qreg[i];
-        if (tid < 64) lse_lds[buf][tid] = lv;
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&q_lds[qt & 1][(st_row + 16 * i) * PITCH + 8 * st_vec]) = qreg[i];
+        lse_lds[qt & 3][lane] = lv;
     };
-    load_tile(0);
-    write_tile(0);
-    if (n_qt > 1) load_tile(1);
-    for (int qt = 0; qt < n_qt; ++qt) {
-        const int buf = qt & 1;
-        __syncthreads();
-        if (qt + 1 < n_qt) write_tile(buf ^ 1);
-        if (qt + 2 < n_qt) load_tile(qt + 2);
-
-        f32x16 s[2][2];
+    // weights of one half (32 query rows), summed down the rows into the lane's key columns
+    auto fold_half = [&](const f32x16 (&s)[2], int qt, int mb) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const f32x4 lz = *reinterpret_cast<const f32x4*>(&lse_lds[qt & 3][32 * mb + 8 * q4 + 4 * h]);
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s[mb][nb][v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&q_lds[buf][(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
-                    s[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[nb][ks], s[mb][nb], 0, 0, 0);
-            }
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4 lz = *reinterpret_cast<const f32x4*>(&lse_lds[buf][32 * mb + 8 * q4 + 4 * h]);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int nb = 0; nb < 2; ++nb)
-                        csum[nb] += __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][nb][4 * q4 + e], scale_log2e, -lz[e]));
-            }
+                    csum[nb] += __builtin_amdgcn_exp2f(__builtin_fmaf(s[nb][4 * q4 + e], scale_log2e, -lz[e]));
+        }
+    };
+    // Same half-tile pipeline as pass A; the stale products past the last tile are dropped.
+    f32x16 s_a[2], s_b[2];
+    load_tile(0);
+    write_tile(0);
+    load_tile(1);
+    write_tile(1);
+    load_tile(2);
+    __syncthreads();
+    half_product(q_lds[0], 0, x, h, kf, s_a);
+    for (int qt = 0; qt < n_qt; ++qt) {
+        const int buf = qt & 1;
+        half_product(q_lds[buf], 1, x, h, kf, s_b);
+        fold_half(s_a, qt, 0);
+        interleave_hint();
+        __syncthreads();   // everyone is done with the rows of tile qt; tile qt+1 (written one iteration ago) is visible
+        write_tile(qt + 2);
+        load_tile(qt + 3);
+        half_product(q_lds[buf ^ 1], 0, x, h, kf, s_a);
+        fold_half(s_b, qt, 1);
+        interleave_hint();
     }
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
