@@ -257,7 +257,18 @@ def main():
     torch.cuda.synchronize()
     rope_all_ms = a.elapsed_time(b) / reps
     rope_all_gbps = nl * bytes_rope / (rope_all_ms * 1e-3) / 1e9
-    del big_src, big_dst
+    # the comparison selector's streaming pass (eq. 7) over the same all-layers tensors: two reads, no write to speak of
+    dev_all = torch.empty((nl * w.L_ctx,), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        ctx.fr_kv_deviation(big_src, big_dst, nl * w.L_ctx, dev_all)
+    a.record()
+    for _ in range(reps):
+        ctx.fr_kv_deviation(big_src, big_dst, nl * w.L_ctx, dev_all)
+    b.record()
+    torch.cuda.synchronize()
+    dev_all_ms = a.elapsed_time(b) / reps
+    dev_all_gbps = (nl * bytes_rope + 4 * nl * w.L_ctx) / (dev_all_ms * 1e-3) / 1e9
+    del big_src, big_dst, dev_all
 
     if args.calibrate_copy:   # 2^28 fp32 = 1 GiB read + 1 GiB written by one elementwise copy kernel
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -281,6 +292,8 @@ def main():
         "hbm_gbps": {n: round(v, 1) for n, v in hbm.items()},
         "rope_shift_all_layers": {"layers": nl, "ms": round(rope_all_ms, 4), "gbps": round(rope_all_gbps, 1),
                                   "frac_of_hbm_peak": round(rope_all_gbps / PEAK_HBM_GBPS, 4)},
+        "kv_deviation_all_layers": {"layers": nl, "ms": round(dev_all_ms, 4), "gbps": round(dev_all_gbps, 1),
+                                    "frac_of_hbm_peak": round(dev_all_gbps / PEAK_HBM_GBPS, 4)},
         "roofline": {"kernel": "sparse_prefill_attn", "bound": "mfma", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS if dt == "bf16" else 157.3, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / (PEAK_BF16_TFLOPS if dt == "bf16" else 157.3), 4),

@@ -138,6 +138,16 @@ fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const
 fr_status fr_select_topk(fr_ctx* ctx, const float* scores, int64_t n, int64_t k, int32_t nq,
                          int32_t* q_index_out, void* stream);
 
+/* KV deviation of one layer (eq. 7): deviation_out[t] = sum over the n_kv_heads * head_dim components c of
+ * (kv_a[t, c] - kv_b[t, c])^2, accumulated in fp32.  Followed by fr_select_topk it is the CacheBlend selector
+ * (eq. 8), which the paper compares Query-Guided Selection against.  The paper takes the key half of layer 2.
+ *   kv_a, kv_b     dev [n_tokens, Hkv, d] in the context's dtype, 16-byte aligned (e.g. the keys of full
+ *                  attention and the cached keys of the same tokens); read only
+ *   deviation_out  dev [n_tokens] fp32
+ * n_tokens = 0 is a no-op.  Errors: FR_ERR_INVALID_ARG (NULL or misaligned pointer, n_tokens < 0 or > 2^31 - 1). */
+fr_status fr_kv_deviation(fr_ctx* ctx, const void* kv_a, const void* kv_b, int64_t n_tokens, float* deviation_out,
+                          void* stream);
+
 /* Sparse prefill attention (eq. 9, Sec. 4.3).  Row r holds the query of the token at position
  * q_index[r]; it attends to every key at a position <= q_index[r].  The key/value at a position
  * listed in q_index is the recomputed one (k_new/v_new row of that token), every other position

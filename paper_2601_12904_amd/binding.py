@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "FR_OK", 1: "FR_ERR_INVALID_ARG", 2: "FR_ERR_UNSUPPORTED", 3:
 FR_OPT_ATTN_SOFTMAX = 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_topk_count", "fr_rope_shift",
-           "fr_score_select", "fr_select_topk", "fr_sparse_prefill_attn", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
+           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
            "fr_linear_swiglu", "fr_qkv_rope")
 
 
@@ -70,6 +70,8 @@ def load() -> ctypes.CDLL:
     lib.fr_score_select.restype = i32
     lib.fr_select_topk.argtypes = [vp, vp, i64, i64, i32, vp, vp]
     lib.fr_select_topk.restype = i32
+    lib.fr_kv_deviation.argtypes = [vp, vp, vp, i64, vp, vp]
+    lib.fr_kv_deviation.restype = i32
     lib.fr_sparse_prefill_attn.argtypes = [vp, vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.fr_sparse_prefill_attn.restype = i32
     lib.fr_kv_scatter.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, vp]
@@ -171,6 +173,10 @@ class Context:
     def fr_select_topk(self, scores, n: int, k: int, nq: int, q_index_out, stream=None):
         self._check(self._lib.fr_select_topk(self._h, _ptr(scores), int(n), int(k), int(nq), _ptr(q_index_out),
                                              _stream(stream)))
+
+    def fr_kv_deviation(self, kv_a, kv_b, n_tokens: int, deviation_out, stream=None):
+        self._check(self._lib.fr_kv_deviation(self._h, _ptr(kv_a), _ptr(kv_b), int(n_tokens), _ptr(deviation_out),
+                                              _stream(stream)))
 
     def fr_sparse_prefill_attn(self, q_rows, q_index, R: int, k_cache, v_cache, L: int, k_new, v_new, out,
                                lse_out=None, stream=None):

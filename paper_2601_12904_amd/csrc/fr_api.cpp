@@ -252,6 +252,24 @@ fr_status fr_select_topk(fr_ctx* ctx, const float* scores, int64_t n, int64_t k,
     return FR_OK;
 }
 
+fr_status fr_kv_deviation(fr_ctx* ctx, const void* kv_a, const void* kv_b, int64_t n_tokens, float* deviation_out,
+                          void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    if (n_tokens < 0 || n_tokens > INT32_MAX)
+        return fail(ctx, FR_ERR_INVALID_ARG, "n_tokens = %lld out of range", (long long)n_tokens);
+    if (n_tokens == 0) return FR_OK;
+    if (!kv_a || !kv_b || ((reinterpret_cast<uintptr_t>(kv_a) | reinterpret_cast<uintptr_t>(kv_b)) & 15u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "kv_a / kv_b is NULL or not 16-byte aligned");
+    if (!deviation_out || (reinterpret_cast<uintptr_t>(deviation_out) & 3u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "deviation_out is NULL or not 4-byte aligned");
+    fr_status st = need_device(ctx);
+    if (st != FR_OK) return st;
+    hipError_t e = launch_kv_deviation(ctx->shape, kv_a, kv_b, n_tokens, deviation_out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, "kv deviation launch", e);
+    return FR_OK;
+}
+
 fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const void* k_ctx,
                           const int32_t* chunk_offsets, int32_t n_chunks, int64_t k, int32_t norm, float* scores_out,
                           int32_t* q_index_out, void* stream) {

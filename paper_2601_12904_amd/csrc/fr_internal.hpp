@@ -80,6 +80,9 @@ hipError_t launch_score_mfma(const Shape& s, const void* q, int nq, const void* 
 hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index,
                          uint32_t* tmp, hipStream_t st);
 
+hipError_t launch_kv_deviation(const Shape& s, const void* kv_a, const void* kv_b, int64_t n_tokens, float* out,
+                               hipStream_t st);
+
 hipError_t launch_inv_index(const int32_t* q_index, int R, int64_t L, int32_t* inv, hipStream_t st);
 hipError_t launch_attn_simt(const Shape& s, const void* q_rows, const int32_t* q_index, int R,
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,

@@ -163,6 +163,44 @@ def test_select_topk_exact(n, k, nq):
     ctx.close()
 
 
+@pytest.mark.parametrize("name,seed", CASES)
+def test_kv_deviation_selector(name, seed):
+    """eq. 7-8: per-token squared deviation between the keys of full attention and the reused keys, then the same
+    top-k.  fp32 sums of at most a few thousand exact squared differences: 1e-5 relative."""
+    w = workloads()[name](seed)
+    dt = w.shape.dtype
+    k_ctx, _, k, _ = staged(w)
+    k_fa = w.k_full[: w.L_ctx]
+    ctx = H.make_ctx(w.shape, w.L, len(w.chunk_offsets) - 1, w.nq)
+    dev = torch.full((w.L_ctx,), -1.0, dtype=torch.float32, device="cuda")
+    ctx.fr_kv_deviation(H.dev(k_fa, dt), H.dev(k_ctx, dt), w.L_ctx, dev)
+    qi = torch.full((k + w.nq,), -7, dtype=torch.int32, device="cuda")
+    ctx.fr_select_topk(dev, w.L_ctx, k, w.nq, qi)
+    torch.cuda.synchronize()
+    want = orc.kv_deviation(k_fa, k_ctx)
+    got = dev.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= 1e-5 * np.abs(want) + 1e-30)
+    H.assert_index_set(qi.cpu().numpy(), want, k, w.nq, rel_tie=1e-5)
+    ctx.close()
+
+
+def test_kv_deviation_ragged_sizes():
+    rng = np.random.default_rng(3)
+    for shape in (synth.TINY_F32, BF16_D64_G2):
+        ctx = H.make_ctx(shape, 4096, 4, 8)
+        for n in (1, 3, 4, 5, 1023, 2050):
+            a = synth.round_to_storage(rng.standard_normal((n, shape.n_kv_heads, shape.head_dim)).astype(np.float32), shape.dtype)
+            b = synth.round_to_storage(rng.standard_normal((n, shape.n_kv_heads, shape.head_dim)).astype(np.float32), shape.dtype)
+            out = torch.full((n + 1,), -1.0, dtype=torch.float32, device="cuda")
+            ctx.fr_kv_deviation(H.dev(a, shape.dtype), H.dev(b, shape.dtype), n, out)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy().astype(np.float64)
+            want = orc.kv_deviation(a, b)
+            assert got[n] == -1.0                                 # nothing written past the end
+            assert np.all(np.abs(got[:n] - want) <= 1e-5 * want)
+        ctx.close()
+
+
 def run_attention(ctx, w, qi, k_cache, v_cache, with_new=True, want_lse=True):
     dt = w.shape.dtype
     R = len(qi)

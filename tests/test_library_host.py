@@ -94,6 +94,15 @@ def test_score_select_argument_errors(ctx):
     expect(B.FR_ERR_INVALID_ARG, ctx.fr_select_topk, P, 10, 11, 0, P)
 
 
+def test_kv_deviation_argument_errors(ctx):
+    P = 4096
+    expect(B.FR_ERR_INVALID_ARG, ctx.fr_kv_deviation, P, P, -1, P)
+    expect(B.FR_ERR_INVALID_ARG, ctx.fr_kv_deviation, None, P, 5, P)
+    expect(B.FR_ERR_INVALID_ARG, ctx.fr_kv_deviation, P, P + 8, 5, P)
+    expect(B.FR_ERR_INVALID_ARG, ctx.fr_kv_deviation, P, P, 5, None)
+    ctx.fr_kv_deviation(None, None, 0, None)                                                  # nothing to do
+
+
 def test_attention_and_scatter_argument_errors(ctx):
     P = 4096
     expect(B.FR_ERR_INVALID_ARG, ctx.fr_sparse_prefill_attn, P, P, 5, P, P, 4, P, P, P)      # R > L
@@ -115,4 +124,5 @@ def test_valid_call_without_gpu_reports_device_error(ctx):
     P = 4096
     expect(B.FR_ERR_DEVICE, ctx.fr_rope_shift, P, P, [0, 5], [0])
     expect(B.FR_ERR_DEVICE, ctx.fr_kv_scatter, P, P, P, 5, P, P, 100)
+    expect(B.FR_ERR_DEVICE, ctx.fr_kv_deviation, P, P, 5, P)
     assert ctx.workspace_bytes() == 0

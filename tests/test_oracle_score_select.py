@@ -136,3 +136,18 @@ def test_kv_deviation_closed_form():
     b[1] = 0.5                                               # 16 components differ by 0.5 -> 16 * 0.25
     b[2, 0, 1, 3] = -2.0
     assert np.allclose(orc.kv_deviation(a, b), [0.0, 4.0, 4.0])
+
+
+def test_kv_deviation_polarisation_identity_and_selector():
+    # |a - b|^2 = |a|^2 + |b|^2 - 2 a.b, row by row (a different route to the same number) ...
+    rng = np.random.default_rng(5)
+    a = rng.standard_normal((40, 3, 8))
+    b = a + 0.1 * rng.standard_normal((40, 3, 8))
+    b[[7, 21, 30]] += 1.0                                     # three tokens deviate strongly
+    a2, b2 = a.reshape(40, -1), b.reshape(40, -1)
+    want = (a2 * a2).sum(1) + (b2 * b2).sum(1) - 2.0 * np.einsum("tc,tc->t", a2, b2)
+    assert np.allclose(orc.kv_deviation(a, b), want, rtol=1e-10, atol=1e-12)
+    # ... symmetric, zero only for equal rows, and the top-3 of it are the planted tokens (eq. 8)
+    assert np.array_equal(orc.kv_deviation(a, b), orc.kv_deviation(b, a))
+    assert orc.kv_deviation(a, a).max() == 0.0
+    assert list(orc.select_q_index(orc.kv_deviation(a, b), 3, 2)) == [7, 21, 30, 40, 41]
