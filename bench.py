@@ -146,13 +146,72 @@ def bench_stack(args):
     ctx.close()
 
 
+def bench_offline(args):
+    """Offline preprocessing of one chunk (eq. 10): the cached keys of a 64-token system prompt and of the 10
+    retrieved chunks (1024 tokens each) are moved to their positions in X, then the 1024 rows of the chunk being
+    cached, fed at the positions after X, attend to that prefix and causally to themselves.  A step = the two calls."""
+    from paper_2601_12904_amd import synth
+    from tests import harness as H
+
+    shape = synth.LLAMA3_8B_BF16
+    d = shape.head_dim
+    w = synth.make_workload("llama3_8b_offline_S64+10x1024_chunk1024", shape, [64] + [1024] * 10, nq=1024, ratio=0.0,
+                            seed=args.seed, sigma_q=float(np.sqrt(d)), sigma_kv=float(1.0 / np.sqrt(d)), focus_frac=0.02)
+    dt, tdt = w.shape.dtype, H.TORCH_DTYPE[w.shape.dtype]
+    Hq, Hkv = shape.n_q_heads, shape.n_kv_heads
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    k_cached = H.dev(w.k_cached, dt)
+    k_x = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_x = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_x[: w.L_ctx] = H.dev(w.v_cached, dt)
+    qi_host = np.arange(w.L_ctx, w.L, dtype=np.int32)
+    qi = torch.from_numpy(qi_host).cuda()
+    q_c, k_c, v_c = (H.dev(a[w.L_ctx:], dt) for a in (w.q_full, w.k_full, w.v_full))
+    out = torch.empty((w.nq, Hq, d), dtype=tdt, device="cuda")
+
+    def step(ev=None):
+        ctx.fr_rope_shift(k_cached, k_x, w.chunk_offsets, w.src_pos0)
+        if ev: ev[1].record()
+        ctx.fr_sparse_prefill_attn(q_c, qi, w.nq, k_x, v_x, w.L, k_c, v_c, out)
+        if ev: ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s_ in range(args.steps):
+        evs[s_][0].record()
+        step(evs[s_])
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    attn_ms = float(np.mean([ev[1].elapsed_time(ev[2]) for ev in evs]))
+    flops = 4.0 * d * Hq * attention_pairs(qi_host)
+    tf = flops / (attn_ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "offline preprocessing of one chunk: rope shift + attention of its rows (ms)",
+        "value": round(ms, 4), "unit": "ms/chunk/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": dt,
+        "data": "synthetic",
+        "config": {"workload": w.name, "prefix_tokens": w.L_ctx, "chunk_tokens": w.nq, "retrieved_chunks": 10,
+                   "seed": args.seed},
+        "call_ms": {"rope_shift": round(float(np.mean([ev[0].elapsed_time(ev[1]) for ev in evs])), 4),
+                    "sparse_prefill_attn": round(attn_ms, 4)},
+        "attn_tflops": round(tf, 2),
+        "roofline": {"kernel": "sparse_prefill_attn", "bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None},
+    }))
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4, 5],
-                    help="2 = the headline layer; 5 = the 32-layer Llama-3-8B-shaped stack over config 2's prompt")
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4, 5, 6],
+                    help="2 = the headline layer; 5 = the 32-layer Llama-3-8B-shaped stack over config 2's prompt; "
+                         "6 = offline preprocessing of one chunk (eq. 10)")
     ap.add_argument("--layers", type=int, default=32, help="decoder layers of the --config 5 stack")
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--seed", type=int, default=0)
@@ -173,6 +232,8 @@ def main():
     torch.cuda.set_device(0)
     if args.config == 5:
         return bench_stack(args)
+    if args.config == 6:
+        return bench_offline(args)
     w = synth.CONFIGS[args.config](seed=args.seed) if args.ratio is None else \
         synth.CONFIGS[args.config](seed=args.seed, ratio=args.ratio)
     dt, tdt = w.shape.dtype, H.TORCH_DTYPE[w.shape.dtype]

@@ -90,9 +90,13 @@ int64_t fr_workspace_bytes(const fr_ctx* ctx);
 /* Tuning / test switches.  FR_OPT_ATTN_SOFTMAX chooses how the tiled bf16 attention kernel keeps exp() in
  * range: AUTO (default) fixes each row's exponent reference at the maximum over its first 32 visible keys
  * and recomputes, with a running maximum, only the workgroups whose sums overflowed; RUNNING_MAX uses the
- * running maximum everywhere.  Both give the same softmax; the option exists so that tests reach both. */
-typedef enum { FR_OPT_ATTN_SOFTMAX = 1 } fr_option;
+ * running maximum everywhere.  Both give the same softmax; the option exists so that tests reach both.
+ * FR_OPT_ATTN_SPLIT: AUTO (default) lets two workgroups share the key range of every (row tile, KV head) when
+ * there are too few of those to fill the chip (few recomputed rows, e.g. the offline stage of eq. 10); OFF / ON
+ * force one or the other.  Same results up to fp32 summation order. */
+typedef enum { FR_OPT_ATTN_SOFTMAX = 1, FR_OPT_ATTN_SPLIT = 2 } fr_option;
 typedef enum { FR_ATTN_SOFTMAX_AUTO = 0, FR_ATTN_SOFTMAX_RUNNING_MAX = 1 } fr_attn_softmax;
+typedef enum { FR_ATTN_SPLIT_AUTO = 0, FR_ATTN_SPLIT_OFF = 1, FR_ATTN_SPLIT_ON = 2 } fr_attn_split;
 fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value);
 
 /* Number of context tokens a recompute ratio selects: floor(ratio * L_ctx + 0.5) clamped to

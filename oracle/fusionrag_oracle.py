@@ -247,6 +247,31 @@ def full_causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.nda
 
 
 # --------------------------------------------------------------------------------------
+# eq. 10: similarity-guided offline preprocessing (Sec. 3.1) -- attention of the chunk being cached
+# --------------------------------------------------------------------------------------
+def offline_preprocess_attn(q_chunk: np.ndarray, k_chunk: np.ndarray, v_chunk: np.ndarray,
+                            k_prefix: np.ndarray, v_prefix: np.ndarray) -> np.ndarray:
+    """Attention of chunk C_i while its cache is rebuilt offline (eq. 10): the chunk is fed at the
+    positions that follow X = cat(S, C_top1..C_topn), so its token t attends to every entry of the
+    concatenated prefix cache (already at its positions in X) and to the chunk's own tokens 0..t.
+    q_chunk [n, Hq, d], k_chunk / v_chunk [n, Hkv, d] are rotated at positions |X| + t;
+    k_prefix / v_prefix [|X|, Hkv, d]."""
+    q, kc, vc, kp, vp = (np.asarray(a, dtype=F64) for a in (q_chunk, k_chunk, v_chunk, k_prefix, v_prefix))
+    n, Hq, d = q.shape
+    G = Hq // kc.shape[1]
+    out = np.empty_like(q)
+    for h in range(Hq):
+        g = h // G
+        for t in range(n):
+            keys = np.concatenate([kp[:, g, :], kc[: t + 1, g, :]])
+            vals = np.concatenate([vp[:, g, :], vc[: t + 1, g, :]])
+            s = keys @ q[t, h] / math.sqrt(d)
+            w = np.exp(s - s.max())
+            out[t, h] = (w / w.sum()) @ vals
+    return out
+
+
+# --------------------------------------------------------------------------------------
 # eq. 7-8: KV deviation and the CacheBlend selector (a comparison selector; same top-k)
 # --------------------------------------------------------------------------------------
 def kv_deviation(kv_fa: np.ndarray, kv_fr: np.ndarray) -> np.ndarray:

@@ -136,6 +136,8 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_flags = take(w.attn_flags_elems * 4);
     w.kv_images_bytes = (s.dtype == FR_BF16 && s.d == 128) ? (size_t)((max_tokens + 63) / 64) * s.Hkv * 36864 : 0;
     const size_t o_img = take(w.kv_images_bytes);
+    w.attn_partials_bytes = (s.dtype == FR_BF16 && s.d == 128) ? attn_mfma_partials_bytes(s, max_tokens) : 0;
+    const size_t o_part = take(w.attn_partials_bytes);
     const size_t o_rr = take((size_t)max_tokens * (s.d / 2) * sizeof(float2));
     w.bytes = off;
     hipError_t e = hipMalloc((void**)&w.base, w.bytes);
@@ -151,6 +153,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.select_tmp = (uint32_t*)(w.base + o_sel);
     w.attn_flags = (int32_t*)(w.base + o_flags);
     w.kv_images = (unsigned char*)(w.base + o_img);
+    w.attn_partials = (float*)(w.base + o_part);
     w.rope_rows = (float2*)(w.base + o_rr);
     ctx->has_device = true;
     *out = ctx;
@@ -175,6 +178,11 @@ fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value) {
             if (value != FR_ATTN_SOFTMAX_AUTO && value != FR_ATTN_SOFTMAX_RUNNING_MAX)
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_ATTN_SOFTMAX: unknown value %lld", (long long)value);
             ctx->attn_softmax_mode = (int)value;
+            return FR_OK;
+        case FR_OPT_ATTN_SPLIT:
+            if (value != FR_ATTN_SPLIT_AUTO && value != FR_ATTN_SPLIT_OFF && value != FR_ATTN_SPLIT_ON)
+                return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_ATTN_SPLIT: unknown value %lld", (long long)value);
+            ctx->attn_split_mode = (int)value;
             return FR_OK;
         default:
             return fail(ctx, FR_ERR_INVALID_ARG, "unknown option %d", option);
@@ -350,7 +358,7 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
     hipError_t e;
     if (attn_mfma_supported(s))
         e = launch_attn_mfma(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, ctx->ws,
-                             ctx->attn_softmax_mode, hs);
+                             ctx->attn_softmax_mode, ctx->attn_split_mode, hs);
     else
         e = launch_attn_simt(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, hs);
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);

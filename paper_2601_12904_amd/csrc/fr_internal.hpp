@@ -42,6 +42,8 @@ struct Workspace {
     int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
     size_t attn_flags_elems = 0;
     float2* rope_rows = nullptr;    // [max_tokens][d/2] (cos, sin) of the recomputed rows' positions
+    float* attn_partials = nullptr;      // partial results of the split attention launch
+    size_t attn_partials_bytes = 0;
     unsigned char* kv_images = nullptr;  // [Hkv][ceil(max_tokens / 64)] LDS-ready K / V^T tile images, 32 KB each
     size_t kv_images_bytes = 0;
 };
@@ -57,6 +59,7 @@ struct fr_ctx {
     int device = -1;
     fr::Workspace ws;
     int attn_softmax_mode = FR_ATTN_SOFTMAX_AUTO;
+    int attn_split_mode = FR_ATTN_SPLIT_AUTO;
     std::string err;
 };
 
@@ -91,7 +94,11 @@ bool attn_mfma_supported(const Shape& s);
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R,
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
                             const void* v_new, const int32_t* inv, void* out, float* lse,
-                            const Workspace& ws, int softmax_mode, hipStream_t st);
+                            const Workspace& ws, int softmax_mode, int split_mode, hipStream_t st);
+// Largest number of (row tile, KV head) items for which the attention launch splits the key range in two
+// (1.25 x the 256 CUs), and the partial-result bytes a context for max_tokens then needs.
+constexpr int ATTN_SPLIT_MAX_ITEMS = 320;
+size_t attn_mfma_partials_bytes(const Shape& s, int64_t max_tokens);
 
 hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
                          hipStream_t st);

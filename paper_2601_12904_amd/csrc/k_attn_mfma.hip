@@ -85,19 +85,24 @@ struct Geometry {
     static constexpr int TRW = 64 / G;   // token rows per wave
     static constexpr int TR = 4 * TRW;   // token rows per workgroup
     int g, tile, row0;
+    int split, item;   // which part of the key range this workgroup walks; ordinal of (row tile, KV head)
     int x, h, wave;
     int col_row[2], col_head[2], col_pos[2];
     int wp_max;    // no key beyond it is visible to any row of this wave
     int n_kt;      // key tiles the workgroup walks
     int n_plain;   // leading tiles whose keys are visible to every row of the workgroup
 
-    __device__ __forceinline__ void init(const int32_t* __restrict__ q_index, int R, int Hkv, int n_row_tiles) {
+    __device__ __forceinline__ void init(const int32_t* __restrict__ q_index, int R, int Hkv, int n_row_tiles,
+                                         int n_split = 1) {
         const int tid = threadIdx.x, lane = tid & 63;
         wave = tid >> 6;
         x = lane & 31;
         h = lane >> 5;
         g = blockIdx.x % Hkv;                               // consecutive blocks land on different XCDs
-        tile = n_row_tiles - 1 - (int)(blockIdx.x / Hkv);   // longest tiles first
+        split = (int)(blockIdx.x / Hkv) % n_split;
+        const int ordinal = (int)(blockIdx.x / (Hkv * n_split));
+        tile = n_row_tiles - 1 - ordinal;                   // longest tiles first
+        item = ordinal * Hkv + g;
         row0 = tile * TR;
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
@@ -367,20 +372,37 @@ __device__ __forceinline__ void store_output(const Geometry<G>& ge, f32x16 (&o)[
     }
 }
 
+// Partial result of one workgroup when the key range of a (row tile, KV head) is split over NS workgroups: the
+// 128 output accumulators, the two sums and the two exponent references of every lane, register-major
+// (float r of thread t at [r * 256 + t]: every store and load is one coalesced 1 KB line per wave).
+constexpr int PART_REGS = 132;
+constexpr int PART_FLOATS = PART_REGS * 256;
+
 // ---- fast kernel ---------------------------------------------------------------------------------
-// grid.x = n_row_tiles * Hkv.  Dynamic LDS: the larger of the K/V rings and the epilogue's staging.
-template <int G>
+// grid.x = n_row_tiles * Hkv * NS.  Dynamic LDS: the larger of the K/V rings and the epilogue's staging.
+// NS = 1: the workgroup walks all key tiles of its rows and writes the output.  NS = 2 (few row tiles, CUs
+// would idle): it walks one half of them and leaves a partial result; every part uses the same exponent
+// reference (each derives it from the first 32 keys), so the parts simply add up in attn_combine_kernel.
+template <int G, int NS>
 __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __restrict__ q_rows,
                                                              const int32_t* __restrict__ q_index, int R,
                                                              const unsigned char* __restrict__ images, int n_img_tiles,
                                                              __bf16* __restrict__ out, float* __restrict__ lse_out,
-                                                             int32_t* __restrict__ redo_flags, int Hq, int Hkv,
-                                                             int n_row_tiles, float scale_log2e) {
+                                                             int32_t* __restrict__ redo_flags, float* __restrict__ partials,
+                                                             int Hq, int Hkv, int n_row_tiles, float scale_log2e) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Rings& rg = *reinterpret_cast<Rings*>(smem_raw);
     Geometry<G> ge;
-    ge.init(q_index, R, Hkv, n_row_tiles);
+    ge.init(q_index, R, Hkv, n_row_tiles, NS);
     const int x = ge.x, h = ge.h;
+    // this workgroup's key tiles [kb, ke)
+    const int per_split = (ge.n_kt + NS - 1) / NS;
+    const int kb = ge.split * per_split, ke = min(ge.n_kt, kb + per_split);
+    float* part = (NS > 1) ? partials + ((size_t)ge.item * NS + ge.split) * PART_FLOATS + threadIdx.x : nullptr;
+    if (NS > 1 && kb >= ke) {   // fewer key tiles than parts: this one adds nothing
+        for (int r = 0; r < PART_REGS; ++r) part[r * 256] = 0.f;
+        return;
+    }
     FragOffsets fo;
     fo.init(x, h);
 
@@ -405,9 +427,11 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
     const unsigned char* head_images = images + (size_t)ge.g * n_img_tiles * IMG_BYTES;
     const int wave = ge.wave, lane = threadIdx.x & 63;
     const int n_kt = ge.n_kt;
-    dma_image(head_images, rg.k[0], wave, lane);
-    dma_image(head_images + K_IMG_BYTES, rg.vt[0], wave, lane);
-    if (n_kt > 1) dma_image(head_images + IMG_BYTES, rg.k[1], wave, lane);
+    const unsigned char* first_image = head_images + (size_t)kb * IMG_BYTES;
+    dma_image(first_image, rg.k[0], wave, lane);
+    dma_image(first_image + K_IMG_BYTES, rg.vt[0], wave, lane);
+    if (kb + 1 < n_kt) dma_image(first_image + IMG_BYTES, rg.k[1], wave, lane);
+    if (NS > 1 && kb > 0) dma_image(head_images, rg.k[2], wave, lane);   // K image 0, for the exponent reference only
     {   // V ring slot 2 is read (against all-zero weights) by the very first step: it must hold finite numbers
         const u32x4 z = {0u, 0u, 0u, 0u};
         for (int i = threadIdx.x; i < V_IMG_BYTES / 16; i += 256) *reinterpret_cast<u32x4*>(&rg.vt[2][16 * i]) = z;
@@ -415,9 +439,9 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
     wait_dma();
     __syncthreads();
 
-    // logits of the first 32 keys; exponent reference of each column = their maximum over the visible ones
+    // exponent reference of each column = the maximum of its logits over the visible ones of keys 0..31
     f32x16 s_a[2], s_b[2];
-    qk_half(rg.k[0], 0, qf, fo, s_a);
+    qk_half((NS > 1 && kb > 0) ? rg.k[2] : rg.k[0], 0, qf, fo, s_a);
     float mref[2];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
@@ -429,6 +453,10 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
         }
         t = fmaxf(t, __shfl_xor(t, 32));   // key 0 (held by the h = 0 lane) is visible to every row
         mref[nb] = t * scale_log2e;
+    }
+    if (NS > 1 && kb > 0) {
+        __syncthreads();                     // ring slot 2 is free again before the loop copies into it
+        qk_half(rg.k[0], 0, qf, fo, s_a);    // logits of this part's first 32 keys
     }
     bf16x8 pf_a[2][2], pf_b[2][2];
 #pragma unroll
@@ -445,9 +473,10 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
     //   step (kt, 0): weights of keys [64kt, 64kt+32)    | logits of (kt, 1) from K[kt]     | O += half (kt-1, 1), V[kt-1]
     //   step (kt, 1): weights of keys [64kt+32, 64kt+64) | logits of (kt+1, 0) from K[kt+1] | O += half (kt, 0),   V[kt]
     int k0 = 0, k1 = 1, k2 = 2;   // ring slots of K images kt, kt+1, kt+2; V images kt-1, kt, kt+1 sit in k2, k0, k1
-    int kt = 0;
-    for (; kt < ge.n_plain; ++kt) {   // plain tiles: every key visible to every row; a next tile always exists
-        if (kt > 0) {
+    int kt = kb;
+    const int plain_end = min(ge.n_plain, ke);
+    for (; kt < plain_end; ++kt) {   // plain tiles: every key visible to every row; image kt+1 always exists
+        if (kt > kb) {
             wait_dma();
             __syncthreads();
         }
@@ -460,17 +489,17 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
                                    kt * KT + 32, h, scale_log2e);
         const int t = k0; k0 = k1; k1 = k2; k2 = t;
     }
-    for (; kt < n_kt; ++kt) {         // tiles that cross some row's own position
-        if (kt > 0) {
+    for (; kt < ke; ++kt) {           // tiles that cross some row's own position
+        if (kt > kb) {
             wait_dma();
             __syncthreads();
         }
         const unsigned char* nxt = head_images + (size_t)(kt + 1) * IMG_BYTES;
-        if (kt + 2 < n_kt) dma_image(nxt + IMG_BYTES, rg.k[k2], wave, lane);
-        if (kt + 1 < n_kt) dma_image(nxt + K_IMG_BYTES, rg.vt[k1], wave, lane);
+        if (kt + 2 < ke) dma_image(nxt + IMG_BYTES, rg.k[k2], wave, lane);
+        if (kt + 1 < ke) dma_image(nxt + K_IMG_BYTES, rg.vt[k1], wave, lane);
         pipeline_step<true, true>(rg.k[k0], 1, rg.vt[k2], 1, fo, qf, s_a, s_b, pf_b, pf_a, o, lsum, mref, ge.col_pos,
                                   kt * KT, h, scale_log2e);
-        if (kt + 1 < n_kt)
+        if (kt + 1 < ke)
             pipeline_step<true, true>(rg.k[k1], 0, rg.vt[k0], 0, fo, qf, s_b, s_a, pf_a, pf_b, o, lsum, mref,
                                       ge.col_pos, kt * KT + 32, h, scale_log2e);
         else
@@ -478,7 +507,22 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
                                        ge.col_pos, kt * KT + 32, h, scale_log2e);
         const int t = k0; k0 = k1; k1 = k2; k2 = t;
     }
-    pv_half(rg.vt[k2], 1, pf_b, fo, o);   // the last half: V image n_kt-1 now sits in slot k2
+    pv_half(rg.vt[k2], 1, pf_b, fo, o);   // the last half: V image ke-1 now sits in slot k2
+
+    if (NS > 1) {   // leave the partial result; attn_combine_kernel adds the parts, checks and stores
+#pragma unroll
+        for (int md = 0; md < 4; ++md)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) part[((2 * md + nb) * 16 + v) * 256] = o[md][nb][v];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            part[(128 + nb) * 256] = lsum[nb];
+            part[(130 + nb) * 256] = mref[nb];
+        }
+        return;
+    }
 
     // overflow check: with a fixed reference a runaway logit shows up as inf / nan in the sums
     float l[2];
@@ -494,6 +538,48 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
         bad = bad || !(chk < INFINITY) || !(l[nb] > 0.f);
     }
     const int any_bad = __syncthreads_or(bad ? 1 : 0);   // also: every wave is done with the rings
+    if (threadIdx.x == 0) redo_flags[blockIdx.x] = any_bad;
+    if (any_bad) return;
+    store_output<G>(ge, o, l, mref, R, Hq, smem_raw, out, lse_out);
+}
+
+// ---- combine: adds the two parts of every (row tile, KV head), then checks and stores like the fast kernel's
+//      own epilogue.  grid.x = n_row_tiles * Hkv (the ordinals of the unsplit launch), LDS = the epilogue's staging.
+template <int G>
+__global__ __launch_bounds__(256) void attn_combine_kernel(const int32_t* __restrict__ q_index, int R,
+                                                           const float* __restrict__ partials, __bf16* __restrict__ out,
+                                                           float* __restrict__ lse_out, int32_t* __restrict__ redo_flags,
+                                                           int Hq, int Hkv, int n_row_tiles) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    Geometry<G> ge;
+    ge.init(q_index, R, Hkv, n_row_tiles);
+    const float* p0 = partials + (size_t)ge.item * 2 * PART_FLOATS + threadIdx.x;
+    const float* p1 = p0 + PART_FLOATS;
+    f32x16 o[4][2];
+#pragma unroll
+    for (int md = 0; md < 4; ++md)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = (2 * md + nb) * 16 + v;
+                o[md][nb][v] = p0[r * 256] + p1[r * 256];
+            }
+    float l[2], mref[2];
+    bool bad = false;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const float lsum = p0[(128 + nb) * 256] + p1[(128 + nb) * 256];
+        mref[nb] = p0[(130 + nb) * 256];
+        l[nb] = lsum + __shfl_xor(lsum, 32);
+        float chk = l[nb];
+#pragma unroll
+        for (int md = 0; md < 4; ++md)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) chk += fabsf(o[md][nb][v]);
+        bad = bad || !(chk < INFINITY) || !(l[nb] > 0.f);
+    }
+    const int any_bad = __syncthreads_or(bad ? 1 : 0);
     if (threadIdx.x == 0) redo_flags[blockIdx.x] = any_bad;
     if (any_bad) return;
     store_output<G>(ge, o, l, mref, R, Hq, smem_raw, out, lse_out);
@@ -582,7 +668,7 @@ __global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __r
 template <int G>
 hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                   const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
-                  float* lse, const Workspace& ws, int mode, hipStream_t st) {
+                  float* lse, const Workspace& ws, int mode, int split_mode, hipStream_t st) {
     const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
     constexpr int TR = Geometry<G>::TR;
     const int n_row_tiles = (R + TR - 1) / TR;
@@ -591,8 +677,14 @@ hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, in
     const size_t lds_safe = (size_t)IMG_BYTES > EPILOGUE_LDS ? (size_t)IMG_BYTES : EPILOGUE_LDS;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 1>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_combine_kernel<G>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)EPILOGUE_LDS);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_running_max_kernel<G>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_safe);
@@ -606,12 +698,24 @@ hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, in
         (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
         k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, ws.kv_images);
     const int32_t* flags = ws.attn_flags;
-    if (mode != FR_ATTN_SOFTMAX_RUNNING_MAX)
-        attn_fixed_ref_kernel<G><<<grid, block, lds_fast, st>>>((const __bf16*)q_rows, q_index, R, ws.kv_images,
-                                                                n_img_tiles, (__bf16*)out, lse, ws.attn_flags, s.Hq,
-                                                                s.Hkv, n_row_tiles, scale_log2e);
-    else
+    // Few (row tile, KV head) items: the chip would idle behind the longest ones, so each is walked by two
+    // workgroups.  Not worth the partial results' traffic once the items alone fill the CUs, nor for short prompts.
+    const bool fits = (size_t)grid.x * 2 * PART_FLOATS * sizeof(float) <= ws.attn_partials_bytes;
+    const bool split = fits && (split_mode == FR_ATTN_SPLIT_ON ||
+                                (split_mode == FR_ATTN_SPLIT_AUTO && (int)grid.x <= ATTN_SPLIT_MAX_ITEMS && n_img_tiles >= 32));
+    if (mode == FR_ATTN_SOFTMAX_RUNNING_MAX) {
         flags = nullptr;   // recompute every workgroup with the running maximum
+    } else if (split) {
+        attn_fixed_ref_kernel<G, 2><<<dim3(grid.x * 2), block, lds_fast, st>>>(
+            (const __bf16*)q_rows, q_index, R, ws.kv_images, n_img_tiles, (__bf16*)out, lse, ws.attn_flags,
+            ws.attn_partials, s.Hq, s.Hkv, n_row_tiles, scale_log2e);
+        attn_combine_kernel<G><<<grid, block, EPILOGUE_LDS, st>>>(q_index, R, ws.attn_partials, (__bf16*)out, lse,
+                                                                  ws.attn_flags, s.Hq, s.Hkv, n_row_tiles);
+    } else {
+        attn_fixed_ref_kernel<G, 1><<<grid, block, lds_fast, st>>>((const __bf16*)q_rows, q_index, R, ws.kv_images,
+                                                                   n_img_tiles, (__bf16*)out, lse, ws.attn_flags, nullptr,
+                                                                   s.Hq, s.Hkv, n_row_tiles, scale_log2e);
+    }
     attn_running_max_kernel<G><<<grid, block, lds_safe, st>>>((const __bf16*)q_rows, q_index, R, ws.kv_images,
                                                               n_img_tiles, (__bf16*)out, lse, flags, s.Hq, s.Hkv,
                                                               n_row_tiles, scale_log2e);
@@ -620,19 +724,26 @@ hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, in
 
 }  // namespace
 
+size_t attn_mfma_partials_bytes(const Shape& s, int64_t max_tokens) {
+    const int64_t tr = 4 * (64 / s.G);   // token rows per workgroup
+    int64_t items = ((max_tokens + tr - 1) / tr) * s.Hkv;
+    if (items > ATTN_SPLIT_MAX_ITEMS) items = ATTN_SPLIT_MAX_ITEMS;
+    return (size_t)items * 2 * PART_FLOATS * sizeof(float);
+}
+
 bool attn_mfma_supported(const Shape& s) {
     return s.dtype == FR_BF16 && s.d == 128 && (s.G == 1 || s.G == 2 || s.G == 4 || s.G == 8);
 }
 
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                             const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv,
-                            void* out, float* lse, const Workspace& ws, int mode, hipStream_t st) {
+                            void* out, float* lse, const Workspace& ws, int mode, int split_mode, hipStream_t st) {
     if (R == 0) return hipSuccess;
     switch (s.G) {
-        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st);
-        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st);
-        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st);
-        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, st);
+        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, st);
+        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, st);
+        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, st);
+        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, st);
     }
 }
 

@@ -163,6 +163,30 @@ def test_select_topk_exact(n, k, nq):
     ctx.close()
 
 
+@pytest.mark.parametrize("name", ["tiny_f32", "offline_bf16"])
+def test_offline_preprocess_attention(name):
+    """eq. 10, the offline stage's attention: the retrieved chunks' cached keys are moved to their positions in
+    X = cat(S, C_top1..n) (fr_rope_shift), and the rows of the chunk being cached, fed at the positions after X,
+    attend to that prefix and causally to themselves (fr_sparse_prefill_attn with a contiguous Q index: no context
+    token is recomputed).  The generator's question part stands in for the chunk C_i."""
+    if name == "tiny_f32":
+        w = synth.config_tiny(seed=2)
+    else:   # prefix: system prompt 64 + three retrieved chunks; chunk being cached: 150 tokens (3 row tiles, ragged)
+        w = synth.config_small_bf16(seed=2, chunk_lens=(64, 200, 130, 257), nq=150)
+    dt = w.shape.dtype
+    ctx = H.make_ctx(w.shape, w.L, len(w.chunk_offsets) - 1, w.nq)
+    k_x = torch.zeros((w.L, w.shape.n_kv_heads, w.shape.head_dim), dtype=H.TORCH_DTYPE[dt], device="cuda")
+    v_x = torch.zeros_like(k_x)
+    v_x[: w.L_ctx] = H.dev(w.v_cached, dt)
+    ctx.fr_rope_shift(H.dev(w.k_cached, dt), k_x, w.chunk_offsets, w.src_pos0)
+    qi = np.arange(w.L_ctx, w.L)
+    got, _ = run_attention(ctx, w, qi, H.host(k_x), H.host(v_x))
+    k_prefix = synth.round_to_storage(orc.rope_shift(w.k_cached, w.chunk_offsets, w.src_pos0, None, w.shape.rope_base), dt)
+    want = orc.offline_preprocess_attn(w.q_full[w.L_ctx:], w.k_full[w.L_ctx:], w.v_full[w.L_ctx:], k_prefix, w.v_cached)
+    H.assert_close(got, want, dt, "offline preprocessing attention")
+    ctx.close()
+
+
 @pytest.mark.parametrize("name,seed", CASES)
 def test_kv_deviation_selector(name, seed):
     """eq. 7-8: per-token squared deviation between the keys of full attention and the reused keys, then the same
@@ -354,6 +378,80 @@ def test_attention_logits_far_above_the_first_keys():
     want, want_lse = orc.sparse_prefill_attn(q_all[qi], qi, k_all, v_all, k_all[qi], v_all[qi])
     H.assert_close(got, want, "bf16", "attention with runaway logits")
     assert np.max(np.abs(lse - want_lse) / np.abs(want_lse)) <= 1e-3
+    ctx.close()
+
+
+@pytest.mark.parametrize("ratio", [0.0, 0.15, 1.0])
+@pytest.mark.parametrize("seed", [3, 4])
+def test_attention_split_key_range(seed, ratio):
+    """The key range of every (row tile, KV head) walked by two workgroups (forced; AUTO picks it only for long
+    prompts with few rows): same oracle, same tolerance, and the unsplit launch agrees to fp32 summation order.
+    Row tiles at positions < 64 have a single key tile: their second part is empty."""
+    w = synth.config_small_bf16(seed=seed, ratio=ratio)
+    dt = w.shape.dtype
+    k_ctx, scores, _, _ = staged(w)
+    k = orc.topk_count(w.L_ctx, ratio)
+    qi = orc.select_q_index(scores, k, w.nq)
+    k_cache, v_cache = assembled_cache(w, k_ctx)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    want, want_lse = orc.sparse_prefill_attn(w.q_full[qi], qi, k_cache, v_cache, w.k_full[qi], w.v_full[qi])
+    ctx.fr_set_option(B.FR_OPT_ATTN_SPLIT, B.FR_ATTN_SPLIT_ON)
+    got, lse = run_attention(ctx, w, qi, k_cache, v_cache)
+    H.assert_close(got, want, dt, "split attention")
+    assert np.max(np.abs(lse - want_lse)) <= 2e-3
+    ctx.fr_set_option(B.FR_OPT_ATTN_SPLIT, B.FR_ATTN_SPLIT_OFF)
+    got1, lse1 = run_attention(ctx, w, qi, k_cache, v_cache)
+    assert H.max_rel_err(got, got1) <= 2.0 ** -7          # at most one bf16 rounding step apart
+    assert np.max(np.abs(lse - lse1)) <= 1e-5
+    with pytest.raises(B.FusionRAGError):
+        ctx.fr_set_option(B.FR_OPT_ATTN_SPLIT, 9)
+    ctx.close()
+
+
+def test_attention_split_with_runaway_logits():
+    """Split launch + overflow of the fixed exponent reference: the combine step must flag the workgroups and the
+    running-maximum kernel recompute them."""
+    shape = synth.LLAMA3_8B_BF16
+    rng = np.random.default_rng(12)
+    L_ctx, nq, d = 500, 40, shape.head_dim
+    L = L_ctx + nq
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    ramp = np.linspace(0.0, 1.0, L)[:, None, None]
+    r = lambda a: synth.round_to_storage(a.astype(np.float32), "bf16")
+    k_all = r(rng.standard_normal((L, shape.n_kv_heads, d)) * 0.05 + ramp * 180.0 * u)
+    q_all = r(rng.standard_normal((L, shape.n_q_heads, d)) * 0.05 + 12.0 * u)
+    v_all = r(rng.standard_normal((L, shape.n_kv_heads, d)))
+    sel = np.sort(rng.choice(L_ctx, size=70, replace=False))
+    qi = np.concatenate([sel, L_ctx + np.arange(nq)])
+    w = synth.Workload("ramp", shape, 0, np.array([0, L_ctx], np.int32), np.zeros(1, np.int32), nq, 0.15,
+                       k_all[:L_ctx], v_all[:L_ctx], q_all, k_all, v_all, np.zeros(0, np.int64))
+    ctx = H.make_ctx(shape, L, 1, nq)
+    ctx.fr_set_option(B.FR_OPT_ATTN_SPLIT, B.FR_ATTN_SPLIT_ON)
+    got, lse = run_attention(ctx, w, qi, k_all, v_all)
+    want, want_lse = orc.sparse_prefill_attn(q_all[qi], qi, k_all, v_all, k_all[qi], v_all[qi])
+    H.assert_close(got, want, "bf16", "split attention with runaway logits")
+    assert np.max(np.abs(lse - want_lse) / np.abs(want_lse)) <= 1e-3
+    ctx.close()
+
+
+def test_full_size_low_ratio_split_sampled():
+    """Config 2's prompt at a 5 % recompute ratio: few row tiles, so the default launch splits the key range.
+    Attention output checked against the oracle on sampled rows."""
+    w = synth.config_17k(seed=0, ratio=0.05)
+    dt = w.shape.dtype
+    rng = np.random.default_rng(0)
+    k = orc.topk_count(w.L_ctx, w.ratio)
+    sel = np.sort(rng.choice(w.L_ctx, size=k, replace=False))     # any index set will do for the attention call
+    qi = np.concatenate([sel, w.L_ctx + np.arange(w.nq)]).astype(np.int64)
+    k_cache = np.concatenate([w.k_cached, w.k_full[w.L_ctx:]])   # stale keys as they are: the call takes any cache
+    v_cache = np.concatenate([w.v_cached, w.v_full[w.L_ctx:]])
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    got, lse = run_attention(ctx, w, qi, k_cache, v_cache)
+    rows = np.unique(np.concatenate([[0, 1, len(qi) - 1], rng.choice(len(qi), size=48, replace=False)]))
+    want, want_lse = orc.sparse_prefill_attn(w.q_full[qi], qi, k_cache, v_cache, w.k_full[qi], w.v_full[qi], rows=rows)
+    H.assert_close(got[rows], want, dt, "sampled rows of the split launch")
+    assert np.max(np.abs(lse[rows] - want_lse)) <= 2e-3
     ctx.close()
 
 

@@ -153,3 +153,31 @@ def test_scatter_exact_untouched_idempotent():
     a, _ = orc.sparse_prefill_attn(q_full[qi], qi, k_cache, v_cache, k_full[qi], v_full[qi])
     b, _ = orc.sparse_prefill_attn(q_full[qi], qi, k1, v1, None, None)
     assert np.allclose(a, b, rtol=1e-13)
+
+
+def test_offline_preprocess_attn_pins():
+    """eq. 10 against three things it must reduce to."""
+    rng = np.random.default_rng(11)
+    Hq, Hkv, d, P, n = 4, 2, 8, 13, 6
+    q = rng.standard_normal((P + n, Hq, d))
+    k = rng.standard_normal((P + n, Hkv, d))
+    v = rng.standard_normal((P + n, Hkv, d))
+    got = orc.offline_preprocess_attn(q[P:], k[P:], v[P:], k[:P], v[:P])
+    # (1) the last n rows of ordinary causal attention over cat(prefix, chunk)
+    assert np.allclose(got, orc.full_causal_attention(q, k, v)[P:], rtol=1e-12, atol=1e-12)
+    # (2) no prefix: causal attention of the chunk alone
+    empty = np.zeros((0, Hkv, d))
+    assert np.allclose(orc.offline_preprocess_attn(q[P:], k[P:], v[P:], empty, empty),
+                       orc.full_causal_attention(q[P:], k[P:], v[P:]), rtol=1e-12, atol=1e-12)
+    # (3) the sparse prefill with no context token chosen: Q index = the chunk's own positions
+    qi = np.arange(P, P + n)
+    cache_k = np.concatenate([k[:P], rng.standard_normal((n, Hkv, d))])     # reserved rows: never read
+    cache_v = np.concatenate([v[:P], rng.standard_normal((n, Hkv, d))])
+    sp, _ = orc.sparse_prefill_attn(q[P:], qi, cache_k, cache_v, k[P:], v[P:])
+    assert np.allclose(got, sp, rtol=1e-12, atol=1e-12)
+    # first chunk token with a one-entry prefix: two keys, weights by hand
+    q1, k1, v1 = q[P:P + 1], k[P:P + 1], v[P:P + 1]
+    o = orc.offline_preprocess_attn(q1, k1, v1, k[:1], v[:1])
+    s0, s1 = (k[0, 0] @ q1[0, 0]) / np.sqrt(d), (k1[0, 0] @ q1[0, 0]) / np.sqrt(d)
+    w0 = 1.0 / (1.0 + np.exp(s1 - s0))
+    assert np.allclose(o[0, 0], w0 * v[0, 0] + (1.0 - w0) * v1[0, 0], rtol=1e-12)
