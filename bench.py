@@ -25,10 +25,11 @@ import torch
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E peak
 
-# HBM traffic of one sparse-attention launch (bytes), from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of
-# this script scaled by a plain copy of known size (profiles/bench_config2_hbm_traffic.md): 146.0 MB fetched
-# + 27.0 MB written.  Workloads that were not measured report null.
-MEASURED_ATTN_TRAFFIC = {"llama3_8b_layer_16x1024+512": 173.0e6}
+# HBM traffic of the dominant kernel per launch (bytes), from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of
+# this script scaled by a plain copy of known size (profiles/bench_config2_hbm_traffic.md): 335.5 MB fetched +
+# 101.6 MB written by the split launch this workload gets (173 MB unsplit).  Workloads that were not measured
+# report null.
+MEASURED_ATTN_TRAFFIC = {"llama3_8b_layer_16x1024+512": 437.1e6}
 
 
 def attention_pairs(q_index: np.ndarray) -> int:
@@ -217,6 +218,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rope-layers", type=int, default=32, help="layers in the batched rope-shift bandwidth run")
+    ap.add_argument("--attn-split", choices=["auto", "off", "on"], default="auto",
+                    help="key-range split of the attention launch (default: the library's own choice)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -243,6 +246,8 @@ def main():
     R = k + w.nq
 
     ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    ctx.fr_set_option(B.FR_OPT_ATTN_SPLIT, {"auto": B.FR_ATTN_SPLIT_AUTO, "off": B.FR_ATTN_SPLIT_OFF,
+                                            "on": B.FR_ATTN_SPLIT_ON}[args.attn_split])
     k_cached = H.dev(w.k_cached, dt)
     k_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
     v_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
@@ -358,7 +363,8 @@ def main():
         "roofline": {"kernel": "sparse_prefill_attn", "bound": "mfma", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS if dt == "bf16" else 157.3, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / (PEAK_BF16_TFLOPS if dt == "bf16" else 157.3), 4),
-                     "traffic": MEASURED_ATTN_TRAFFIC.get(w.name)},
+                     "traffic": MEASURED_ATTN_TRAFFIC.get(w.name) if args.ratio is None and args.attn_split == "auto"
+                     else None},
     }
     if not args.no_cpu_baseline:
         base, qi_o, scores_o = cpu_baseline(w, k)

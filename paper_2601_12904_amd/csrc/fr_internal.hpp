@@ -95,9 +95,12 @@ hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
                             const void* v_new, const int32_t* inv, void* out, float* lse,
                             const Workspace& ws, int softmax_mode, int split_mode, hipStream_t st);
-// Largest number of (row tile, KV head) items for which the attention launch splits the key range in two
-// (1.25 x the 256 CUs), and the partial-result bytes a context for max_tokens then needs.
-constexpr int ATTN_SPLIT_MAX_ITEMS = 320;
+// The attention launch splits the key range in two on its own up to ATTN_SPLIT_AUTO_ITEMS (row tile, KV head)
+// items (about 1.5 x the 256 CUs: beyond that the items alone keep the chip busy and the partial results' traffic
+// costs more than the better balance gains), and on request (FR_ATTN_SPLIT_ON) up to ATTN_SPLIT_MAX_ITEMS, which
+// sizes the partial-result buffer.
+constexpr int ATTN_SPLIT_AUTO_ITEMS = 400;
+constexpr int ATTN_SPLIT_MAX_ITEMS = 768;
 size_t attn_mfma_partials_bytes(const Shape& s, int64_t max_tokens);
 
 hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,

@@ -700,9 +700,11 @@ hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, in
     const int32_t* flags = ws.attn_flags;
     // Few (row tile, KV head) items: the chip would idle behind the longest ones, so each is walked by two
     // workgroups.  Not worth the partial results' traffic once the items alone fill the CUs, nor for short prompts.
+    // (Letting the part that finishes last add the other's sums inside the same kernel was measured too: the
+    // device-scope fences it needs write back and invalidate the whole L2 at every arrival and cost 110 us.)
     const bool fits = (size_t)grid.x * 2 * PART_FLOATS * sizeof(float) <= ws.attn_partials_bytes;
     const bool split = fits && (split_mode == FR_ATTN_SPLIT_ON ||
-                                (split_mode == FR_ATTN_SPLIT_AUTO && (int)grid.x <= ATTN_SPLIT_MAX_ITEMS && n_img_tiles >= 32));
+                                (split_mode == FR_ATTN_SPLIT_AUTO && (int)grid.x <= ATTN_SPLIT_AUTO_ITEMS && n_img_tiles >= 32));
     if (mode == FR_ATTN_SOFTMAX_RUNNING_MAX) {
         flags = nullptr;   // recompute every workgroup with the running maximum
     } else if (split) {
