@@ -247,6 +247,51 @@ def full_causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.nda
 
 
 # --------------------------------------------------------------------------------------
+# Sec. 4.3: batch decoding over shared chunk caches and per-query exclusive pages
+# --------------------------------------------------------------------------------------
+def decode_attn(q: np.ndarray, k_shared: np.ndarray, v_shared: np.ndarray, segments: Sequence[Sequence[tuple]],
+                stale_rows: Sequence[Sequence[int]], k_pages: Sequence[np.ndarray], v_pages: Sequence[np.ndarray],
+                base: float, layout: str = "interleaved", index_base: int = 0):
+    """One decoding step for a batch of queries (Sec. 2.1: the last token attends to all past
+    K/V; Sec. 4.3: the chunk caches are shared by the batch and never modified, every query keeps
+    the recomputed K/V of its critical tokens, of its question and of its generated tokens in an
+    exclusive page, and the shared entries of its critical tokens are masked out).
+
+    q [B, Hq, d]: the decoding token's queries, rotated at their positions.
+    k_shared / v_shared [N, Hkv, d]: the chunk store as cached.  ``segments[b]`` lists
+    (row0, length, delta): query b's prompt contains store rows [row0, row0 + length), and their
+    keys, cached ``delta`` positions away from where they sit in this prompt, are first moved
+    there (Appendix A: one more rotation by delta).  ``stale_rows[b]``: store rows whose entries
+    query b must not read.  k_pages[b] / v_pages[b] [P_b, Hkv, d]: the exclusive page, keys at their
+    positions in the prompt (the decoding token's own entry included).
+    Returns (O [B, Hq, d], lse [B, Hq])."""
+    q = np.asarray(q, dtype=F64)
+    ks, vs = np.asarray(k_shared, dtype=F64), np.asarray(v_shared, dtype=F64)
+    B, Hq, d = q.shape
+    G = Hq // ks.shape[1]
+    out = np.empty_like(q)
+    lse = np.empty((B, Hq), dtype=F64)
+    for b in range(B):
+        stale = set(int(r) for r in stale_rows[b])
+        keys, vals = [], []
+        for (row0, length, delta) in segments[b]:
+            rows = [r for r in range(row0, row0 + length) if r not in stale]
+            if rows:
+                keys.append(rope_rotate(ks[rows], np.full(len(rows), delta, dtype=np.int64), base, layout, index_base))
+                vals.append(vs[rows])
+        keys.append(np.asarray(k_pages[b], dtype=F64))
+        vals.append(np.asarray(v_pages[b], dtype=F64))
+        kb, vb = np.concatenate(keys), np.concatenate(vals)            # [n_b, Hkv, d]
+        for h in range(Hq):
+            s = kb[:, h // G, :] @ q[b, h] / math.sqrt(d)
+            m = s.max()
+            w = np.exp(s - m)
+            out[b, h] = (w / w.sum()) @ vb[:, h // G, :]
+            lse[b, h] = m + math.log(w.sum())
+    return out, lse
+
+
+# --------------------------------------------------------------------------------------
 # eq. 10: similarity-guided offline preprocessing (Sec. 3.1) -- attention of the chunk being cached
 # --------------------------------------------------------------------------------------
 def offline_preprocess_attn(q_chunk: np.ndarray, k_chunk: np.ndarray, v_chunk: np.ndarray,
