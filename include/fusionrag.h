@@ -168,6 +168,40 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
                                  const void* k_new, const void* v_new, void* out, float* lse_out,
                                  void* stream);
 
+/* Batch decoding attention over shared chunk caches and per-query exclusive pages (Sec. 4.3; decoding step of
+ * Sec. 2.1).  The chunk store (k_shared, v_shared) is shared by all queries of the batch and is never written.
+ * Query b's prompt consists of the store segments seg_*[seg_offsets[b] .. seg_offsets[b+1]): rows
+ * [seg_row0, seg_row0 + seg_len) of the store, whose keys were cached seg_delta positions before the place they
+ * take in this prompt (Appendix A: they are used as if rotated by seg_delta; the kernel rotates the query by
+ * -seg_delta instead, so no copy of the keys is made).  Store rows whose bit is set in query b's mask are skipped:
+ * they are the query's recomputed tokens, whose fresh K/V sit in its exclusive page together with the K/V of its
+ * question and of its generated tokens (all page keys rotated at their positions in the prompt; the decoding
+ * token's own entry included).  out[b, h] = softmax over all those keys of (q[b, h] . key / sqrt(d)) applied to
+ * the values.
+ *   q            dev [n_queries, Hq, d]: the decoding tokens' queries, rotated at their positions
+ *   k_shared, v_shared  dev [n_shared_rows, Hkv, d]
+ *   seg_offsets  dev [n_queries + 1] int32, ascending, seg_offsets[0] = 0, last = n_segments
+ *   seg_row0, seg_len, seg_delta  dev [n_segments] int32
+ *   stale_bits   dev [n_queries][stale_words] uint32, bit (r & 31) of word r >> 5 = store row r is stale for the
+ *                query; NULL = no row is stale (see fr_mark_stale_rows)
+ *   k_pages, v_pages  dev [n_queries][page_stride_rows][Hkv][d]; page_len dev [n_queries] int32 rows in use
+ *   out          dev [n_queries, Hq, d];  lse_out dev [n_queries, Hq] fp32 natural-log normalisers, or NULL
+ * All tensors 16-byte aligned, in the context's dtype.  The descriptor arrays live on the device, so the host does
+ * not check their contents: the kernels clamp every row range to its tensor (rows outside are not read and do not
+ * count).  Errors: FR_ERR_INVALID_ARG (NULL / misaligned pointers, negative sizes), FR_ERR_WORKSPACE
+ * (n_segments + n_queries > 4096). */
+fr_status fr_decode_attn(fr_ctx* ctx, const void* q, int32_t n_queries, const void* k_shared, const void* v_shared,
+                         int64_t n_shared_rows, const int32_t* seg_offsets, const int32_t* seg_row0,
+                         const int32_t* seg_len, const int32_t* seg_delta, int32_t n_segments,
+                         const uint32_t* stale_bits, int64_t stale_words, const void* k_pages, const void* v_pages,
+                         int64_t page_stride_rows, const int32_t* page_len, void* out, float* lse_out, void* stream);
+
+/* Sets, in one query's mask of fr_decode_attn, the bits of the listed store rows (its recomputed tokens).
+ *   stale_bits dev [n_words] uint32 (one query's words); rows dev [n_rows] int32; clear != 0 zeroes the words first.
+ * Rows outside [0, 32 * n_words) are ignored. */
+fr_status fr_mark_stale_rows(fr_ctx* ctx, uint32_t* stale_bits, int64_t n_words, const int32_t* rows, int32_t n_rows,
+                             int32_t clear, void* stream);
+
 /* Write-back (Sec. 4.3): k_cache[q_index[r]] = k_new[r], v_cache[q_index[r]] = v_new[r],
  * bit-exact copies; other rows are not touched.  Shapes as above. */
 fr_status fr_kv_scatter(fr_ctx* ctx, const void* k_new, const void* v_new, const int32_t* q_index,

@@ -24,7 +24,7 @@ FR_OPT_ATTN_SPLIT = 2
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 FR_ATTN_SPLIT_AUTO, FR_ATTN_SPLIT_OFF, FR_ATTN_SPLIT_ON = 0, 1, 2
 EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_topk_count", "fr_rope_shift",
-           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
+           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
            "fr_linear_swiglu", "fr_qkv_rope")
 
 
@@ -76,6 +76,10 @@ def load() -> ctypes.CDLL:
     lib.fr_kv_deviation.restype = i32
     lib.fr_sparse_prefill_attn.argtypes = [vp, vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.fr_sparse_prefill_attn.restype = i32
+    lib.fr_decode_attn.argtypes = [vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, i32, vp, i64, vp, vp, i64, vp, vp, vp, vp]
+    lib.fr_decode_attn.restype = i32
+    lib.fr_mark_stale_rows.argtypes = [vp, vp, i64, vp, i32, i32, vp]
+    lib.fr_mark_stale_rows.restype = i32
     lib.fr_kv_scatter.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, vp]
     lib.fr_kv_scatter.restype = i32
     lib.fr_rmsnorm.argtypes = [vp, vp, vp, i32, i32, ctypes.c_float, vp, vp]
@@ -185,6 +189,19 @@ class Context:
         self._check(self._lib.fr_sparse_prefill_attn(self._h, _ptr(q_rows), _ptr(q_index), int(R), _ptr(k_cache),
                                                      _ptr(v_cache), int(L), _ptr(k_new), _ptr(v_new), _ptr(out),
                                                      _ptr(lse_out), _stream(stream)))
+
+    def fr_decode_attn(self, q, n_queries: int, k_shared, v_shared, n_shared_rows: int, seg_offsets, seg_row0, seg_len,
+                       seg_delta, n_segments: int, stale_bits, stale_words: int, k_pages, v_pages, page_stride_rows: int,
+                       page_len, out, lse_out=None, stream=None):
+        self._check(self._lib.fr_decode_attn(self._h, _ptr(q), int(n_queries), _ptr(k_shared), _ptr(v_shared),
+                                             int(n_shared_rows), _ptr(seg_offsets), _ptr(seg_row0), _ptr(seg_len),
+                                             _ptr(seg_delta), int(n_segments), _ptr(stale_bits), int(stale_words),
+                                             _ptr(k_pages), _ptr(v_pages), int(page_stride_rows), _ptr(page_len),
+                                             _ptr(out), _ptr(lse_out), _stream(stream)))
+
+    def fr_mark_stale_rows(self, stale_bits, n_words: int, rows, n_rows: int, clear: bool = True, stream=None):
+        self._check(self._lib.fr_mark_stale_rows(self._h, _ptr(stale_bits), int(n_words), _ptr(rows), int(n_rows),
+                                                 int(bool(clear)), _stream(stream)))
 
     def fr_kv_scatter(self, k_new, v_new, q_index, R: int, k_cache, v_cache, L: int, stream=None):
         self._check(self._lib.fr_kv_scatter(self._h, _ptr(k_new), _ptr(v_new), _ptr(q_index), int(R), _ptr(k_cache),

@@ -138,6 +138,8 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_img = take(w.kv_images_bytes);
     w.attn_partials_bytes = (s.dtype == FR_BF16 && s.d == 128) ? attn_mfma_partials_bytes(s, max_tokens) : 0;
     const size_t o_part = take(w.attn_partials_bytes);
+    const size_t o_dpart = take(decode_partials_bytes(s));
+    const size_t o_drot = take(decode_rot_table_bytes(s));
     const size_t o_rr = take((size_t)max_tokens * (s.d / 2) * sizeof(float2));
     w.bytes = off;
     hipError_t e = hipMalloc((void**)&w.base, w.bytes);
@@ -154,6 +156,8 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.attn_flags = (int32_t*)(w.base + o_flags);
     w.kv_images = (unsigned char*)(w.base + o_img);
     w.attn_partials = (float*)(w.base + o_part);
+    w.decode_partials = (float*)(w.base + o_dpart);
+    w.decode_rot = (float2*)(w.base + o_drot);
     w.rope_rows = (float2*)(w.base + o_rr);
     ctx->has_device = true;
     *out = ctx;
@@ -362,6 +366,61 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
     else
         e = launch_attn_simt(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, hs);
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
+    return FR_OK;
+}
+
+fr_status fr_decode_attn(fr_ctx* ctx, const void* q, int32_t n_queries, const void* k_shared, const void* v_shared,
+                         int64_t n_shared_rows, const int32_t* seg_offsets, const int32_t* seg_row0,
+                         const int32_t* seg_len, const int32_t* seg_delta, int32_t n_segments,
+                         const uint32_t* stale_bits, int64_t stale_words, const void* k_pages, const void* v_pages,
+                         int64_t page_stride_rows, const int32_t* page_len, void* out, float* lse_out, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    if (n_queries < 0 || n_segments < 0 || n_shared_rows < 0 || page_stride_rows < 0 || stale_words < 0)
+        return fail(ctx, FR_ERR_INVALID_ARG, "negative size");
+    if (n_queries == 0) return FR_OK;
+    if ((int64_t)n_queries + n_segments > DECODE_MAX_UNITS)
+        return fail(ctx, FR_ERR_WORKSPACE, "n_segments + n_queries = %lld exceeds %d", (long long)n_queries + n_segments,
+                    DECODE_MAX_UNITS);
+    auto bad16 = [](const void* p) { return !p || (reinterpret_cast<uintptr_t>(p) & 15u); };
+    auto bad4 = [](const void* p) { return !p || (reinterpret_cast<uintptr_t>(p) & 3u); };
+    if (bad16(q) || bad16(out) || bad16(k_pages) || bad16(v_pages))
+        return fail(ctx, FR_ERR_INVALID_ARG, "q / out / k_pages / v_pages is NULL or not 16-byte aligned");
+    if (n_segments > 0 && (bad16(k_shared) || bad16(v_shared)))
+        return fail(ctx, FR_ERR_INVALID_ARG, "k_shared / v_shared is NULL or not 16-byte aligned");
+    if (bad4(seg_offsets) || bad4(page_len) || (n_segments > 0 && (bad4(seg_row0) || bad4(seg_len) || bad4(seg_delta))))
+        return fail(ctx, FR_ERR_INVALID_ARG, "a descriptor array is NULL or not 4-byte aligned");
+    if ((stale_bits && (reinterpret_cast<uintptr_t>(stale_bits) & 3u)) || (lse_out && (reinterpret_cast<uintptr_t>(lse_out) & 3u)))
+        return fail(ctx, FR_ERR_INVALID_ARG, "stale_bits / lse_out not 4-byte aligned");
+    if (!decode_supported(ctx->shape)) return fail(ctx, FR_ERR_UNSUPPORTED, "group size %d", ctx->shape.G);
+    fr_status st = need_device(ctx);
+    if (st != FR_OK) return st;
+    DecodeArgs a;
+    a.q = q; a.B = n_queries;
+    a.k_shared = k_shared; a.v_shared = v_shared; a.n_shared = n_shared_rows;
+    a.seg_offsets = seg_offsets; a.seg_row0 = seg_row0; a.seg_len = seg_len; a.seg_delta = seg_delta; a.n_seg = n_segments;
+    a.stale_bits = stale_bits; a.stale_words = stale_words;
+    a.k_pages = k_pages; a.v_pages = v_pages; a.page_stride = page_stride_rows; a.page_len = page_len;
+    a.out = out; a.lse_out = lse_out;
+    hipError_t e = launch_decode_attn(ctx->shape, a, ctx->ws.decode_partials, ctx->ws.decode_rot, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, "decode attention launch", e);
+    return FR_OK;
+}
+
+fr_status fr_mark_stale_rows(fr_ctx* ctx, uint32_t* stale_bits, int64_t n_words, const int32_t* rows, int32_t n_rows,
+                             int32_t clear, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    if (n_words < 0 || n_rows < 0) return fail(ctx, FR_ERR_INVALID_ARG, "negative size");
+    if (n_words == 0 || (n_rows == 0 && !clear)) return FR_OK;
+    if (!stale_bits || (reinterpret_cast<uintptr_t>(stale_bits) & 3u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "stale_bits is NULL or not 4-byte aligned");
+    if (n_rows > 0 && (!rows || (reinterpret_cast<uintptr_t>(rows) & 3u)))
+        return fail(ctx, FR_ERR_INVALID_ARG, "rows is NULL or not 4-byte aligned");
+    fr_status st = need_device(ctx);
+    if (st != FR_OK) return st;
+    hipError_t e = launch_mark_stale(stale_bits, n_words, rows, n_rows, clear, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, "mark stale launch", e);
     return FR_OK;
 }
 

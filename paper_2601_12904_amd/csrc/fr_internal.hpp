@@ -42,6 +42,8 @@ struct Workspace {
     int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
     size_t attn_flags_elems = 0;
     float2* rope_rows = nullptr;    // [max_tokens][d/2] (cos, sin) of the recomputed rows' positions
+    float* decode_partials = nullptr;    // [DECODE_MAX_UNITS][Hq][d + 2] partial softmax results of fr_decode_attn
+    float2* decode_rot = nullptr;        // [DECODE_MAX_UNITS][d/2] (cos, sin) of the segments' position shifts
     float* attn_partials = nullptr;      // partial results of the split attention launch
     size_t attn_partials_bytes = 0;
     unsigned char* kv_images = nullptr;  // [Hkv][ceil(max_tokens / 64)] LDS-ready K / V^T tile images, 32 KB each
@@ -85,6 +87,22 @@ hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int3
 
 hipError_t launch_kv_deviation(const Shape& s, const void* kv_a, const void* kv_b, int64_t n_tokens, float* out,
                                hipStream_t st);
+
+// Batch decoding (all pointers device memory unless noted; see fr_decode_attn in the public header).
+struct DecodeArgs {
+    const void* q; int B;
+    const void *k_shared, *v_shared; int64_t n_shared;
+    const int32_t *seg_offsets, *seg_row0, *seg_len, *seg_delta; int n_seg;
+    const uint32_t* stale_bits; int64_t stale_words;
+    const void *k_pages, *v_pages; int64_t page_stride; const int32_t* page_len;
+    void* out; float* lse_out;
+};
+constexpr int DECODE_MAX_UNITS = 4096;   // segments + queries of one call (sizes the partial-result buffer)
+bool decode_supported(const Shape& s);
+size_t decode_partials_bytes(const Shape& s);
+size_t decode_rot_table_bytes(const Shape& s);
+hipError_t launch_decode_attn(const Shape& s, const DecodeArgs& a, float* partials, float2* rot_table, hipStream_t st);
+hipError_t launch_mark_stale(uint32_t* bits, int64_t n_words, const int32_t* rows, int n_rows, int clear, hipStream_t st);
 
 hipError_t launch_inv_index(const int32_t* q_index, int R, int64_t L, int32_t* inv, hipStream_t st);
 hipError_t launch_attn_simt(const Shape& s, const void* q_rows, const int32_t* q_index, int R,

@@ -1,0 +1,349 @@
+// Batch decoding attention over shared chunk caches and per-query exclusive pages (Sec. 4.3; decoding
+// step of Sec. 2.1: the last token attends to all past K/V).
+//
+// The chunk store is shared by the batch and never written.  A query's prompt is a list of segments of store
+// rows; the keys of a segment were cached `delta` positions away from where they sit in this prompt.  Instead
+// of rotating the keys (which would need a private copy per query), the kernel rotates the query the other way
+// once per segment: <RoPE(k, +delta), q> = <k, RoPE(q, -delta)> (Appendix A: RoPE is a rotation, additive in the
+// position).  Store rows whose tokens the query recomputed are skipped by a per-query bit mask; their fresh
+// K/V, the question's and the generated tokens' live in the query's exclusive page, which is one more segment
+// (delta 0, no mask).
+//
+// HBM-bound streaming (2 flop per byte): one workgroup per (segment or page, KV head), every lane reads 16
+// bytes of a key row and of the matching value row, the LPK lanes of a row reduce their partial dot products
+// by shuffles, all vector-ALU work is in fp32.  Every lane keeps an online-softmax state for the rows it has
+// seen; lanes, waves and finally the segments of a query are merged in a fixed order (reproducible results).
+#include "fr_internal.hpp"
+
+namespace fr {
+
+namespace {
+
+constexpr float NEG_BIG = -1.0e30f;
+constexpr int UNROLL = 4;   // key rows in flight per lane group
+
+template <typename T>
+struct Row16;
+template <>
+struct Row16<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void unpack(const uint4& w, float (&f)[4]) {
+        f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y); f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
+    }
+};
+template <>
+struct Row16<__bf16> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void unpack(const uint4& w, float (&f)[8]) {   // a bf16 is the upper half of an fp32
+        const uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f[2 * e] = __uint_as_float(u[e] << 16);
+            f[2 * e + 1] = __uint_as_float(u[e] & 0xFFFF0000u);
+        }
+    }
+};
+
+// Partial result of one (unit, query head): [m (base-2 exponent reference), l, o[D]] in fp32.
+template <int D>
+constexpr int part_floats() { return D + 2; }
+
+// unit u < n_seg: segment u of the shared store; unit n_seg + b: the exclusive page of query b.
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void decode_partial_kernel(
+    const T* __restrict__ q, int B, const T* __restrict__ k_shared, const T* __restrict__ v_shared, int64_t n_shared,
+    const int32_t* __restrict__ seg_offsets, const int32_t* __restrict__ seg_row0, const int32_t* __restrict__ seg_len,
+    const int32_t* __restrict__ seg_delta, int n_seg, const uint32_t* __restrict__ stale_bits, int64_t stale_words,
+    const T* __restrict__ k_pages, const T* __restrict__ v_pages, int64_t page_stride, const int32_t* __restrict__ page_len,
+    int Hq, int Hkv, const float2* __restrict__ rot_table, int rope_layout, float scale_log2e,
+    float* __restrict__ partials) {
+    constexpr int N = Row16<T>::N;              // elements per 16-byte vector
+    constexpr int LPK = D / N;                  // lanes per key row (8, 16 or 32)
+    constexpr int KPW = 64 / LPK;               // key rows per wave and step
+    constexpr int PF = part_floats<D>();
+    __shared__ float merge[4][G][PF];           // per-wave results
+
+    const int unit = blockIdx.x, g = blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c = lane % LPK, r = lane / LPK;
+
+    // ---- which rows ----------------------------------------------------------------------------------
+    int b, delta;
+    int64_t row0, len, limit;
+    const T *kbase, *vbase;
+    const uint32_t* stale = nullptr;
+    if (unit < n_seg) {
+        int lo = 0, hi = B;   // largest b with seg_offsets[b] <= unit
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (seg_offsets[mid] <= unit) lo = mid; else hi = mid;
+        }
+        b = lo;
+        row0 = seg_row0[unit];
+        len = seg_len[unit];
+        delta = seg_delta[unit];
+        kbase = k_shared;
+        vbase = v_shared;
+        limit = n_shared;
+        if (stale_bits != nullptr && stale_words > 0) stale = stale_bits + (size_t)b * stale_words;
+    } else {
+        b = unit - n_seg;
+        row0 = 0;
+        len = page_len[b];
+        delta = 0;
+        kbase = k_pages + (size_t)b * page_stride * Hkv * D;
+        vbase = v_pages + (size_t)b * page_stride * Hkv * D;
+        limit = page_stride;
+    }
+    // rows outside the tensors are never read, whatever the descriptors say
+    if (row0 < 0) { len += row0; row0 = 0; }
+    if (row0 + len > limit) len = limit - row0;
+    if (len < 0) len = 0;
+
+    // ---- this lane's slice of the G query heads, rotated by -delta ---------------------------------------
+    float qr[G][N];
+    {
+        const int e0 = c * N;
+        float cs[N], sn[N];   // per element: cos / signed sin of its pair's angle
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+            const int idx = e0 + e;
+            const int pair = (rope_layout == FR_ROPE_INTERLEAVED) ? (idx >> 1) : (idx % (D / 2));
+            const bool first = (rope_layout == FR_ROPE_INTERLEAVED) ? ((idx & 1) == 0) : (idx < D / 2);
+            float2 t = make_float2(1.f, 0.f);
+            if (delta != 0) t = rot_table[(size_t)unit * (D / 2) + pair];   // (cos, sin)(delta theta_pair)
+            cs[e] = t.x;
+            sn[e] = first ? t.y : -t.y;   // RoPE(q, -delta): a' = a cos + b sin, b' = b cos - a sin
+        }
+#pragma unroll
+        for (int col = 0; col < G; ++col) {
+            const T* qp = q + ((size_t)b * Hq + g * G + col) * D;
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
+                const int idx = e0 + e;
+                const int partner = (rope_layout == FR_ROPE_INTERLEAVED) ? (idx ^ 1) : ((idx + D / 2) % D);
+                qr[col][e] = Elem<T>::to_f32(qp[idx]) * cs[e] + Elem<T>::to_f32(qp[partner]) * sn[e];
+            }
+        }
+    }
+
+    // ---- stream the rows -------------------------------------------------------------------------------
+    float m[G], l[G], o[G][N];
+#pragma unroll
+    for (int col = 0; col < G; ++col) {
+        m[col] = NEG_BIG;
+        l[col] = 0.f;
+#pragma unroll
+        for (int e = 0; e < N; ++e) o[col][e] = 0.f;
+    }
+    const size_t row_elems = (size_t)Hkv * D;
+    const T* kp = kbase + (size_t)g * D + c * N;
+    const T* vp = vbase + (size_t)g * D + c * N;
+    // row i of the unit belongs to (step, wave, r) with i = (step * 4 + wave) * KPW + r; the trip count is the same
+    // for all lanes of a wave (the shuffles below need every lane)
+    for (int64_t w0 = (int64_t)wave * KPW; w0 < len; w0 += (int64_t)UNROLL * 4 * KPW) {
+        uint4 kw[UNROLL], vw[UNROLL];
+        bool ok[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int64_t i = w0 + r + (int64_t)u * 4 * KPW;
+            const int64_t row = row0 + min(i, len - 1);   // clamped: the load is always in bounds
+            const int64_t wd = row >> 5;
+            uint32_t word = 0u;   // (uniform branch; the per-lane part is branch-free so that the loads stay in flight)
+            if (stale != nullptr) word = stale[min(wd, stale_words - 1)];
+            ok[u] = (i < len) && !((wd < stale_words) && ((word >> (row & 31)) & 1u));
+            kw[u] = *reinterpret_cast<const uint4*>(kp + (size_t)row * row_elems);
+            vw[u] = *reinterpret_cast<const uint4*>(vp + (size_t)row * row_elems);
+        }
+        float s[UNROLL][G];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float kf[N];
+            Row16<T>::unpack(kw[u], kf);
+#pragma unroll
+            for (int col = 0; col < G; ++col) {
+                float t = 0.f;
+#pragma unroll
+                for (int e = 0; e < N; ++e) t = __builtin_fmaf(kf[e], qr[col][e], t);
+#pragma unroll
+                for (int sft = 1; sft < LPK; sft <<= 1) t += __shfl_xor(t, sft);
+                s[u][col] = ok[u] ? t * scale_log2e : -INFINITY;
+            }
+        }
+#pragma unroll
+        for (int col = 0; col < G; ++col) {
+            float m_new = m[col];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) m_new = fmaxf(m_new, s[u][col]);
+            const float alpha = __builtin_amdgcn_exp2f(m[col] - m_new);
+            m[col] = m_new;
+            l[col] *= alpha;
+#pragma unroll
+            for (int e = 0; e < N; ++e) o[col][e] *= alpha;
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float vf[N];
+            Row16<T>::unpack(vw[u], vf);
+#pragma unroll
+            for (int col = 0; col < G; ++col) {
+                const float p = __builtin_amdgcn_exp2f(s[u][col] - m[col]);
+                l[col] += p;
+#pragma unroll
+                for (int e = 0; e < N; ++e) o[col][e] = __builtin_fmaf(p, vf[e], o[col][e]);
+            }
+        }
+    }
+
+    // ---- merge the KPW lane groups of the wave (same slice c, different rows) ------------------------------
+#pragma unroll
+    for (int col = 0; col < G; ++col) {
+        float mt = m[col];
+        for (int sft = LPK; sft < 64; sft <<= 1) mt = fmaxf(mt, __shfl_xor(mt, sft));
+        const float a = __builtin_amdgcn_exp2f(m[col] - mt);
+        float lt = l[col] * a;
+        for (int sft = LPK; sft < 64; sft <<= 1) lt += __shfl_xor(lt, sft);
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+            float t = o[col][e] * a;
+            for (int sft = LPK; sft < 64; sft <<= 1) t += __shfl_xor(t, sft);
+            o[col][e] = t;
+        }
+        m[col] = mt;
+        l[col] = lt;
+        if (r == 0) {
+            if (c == 0) { merge[wave][col][0] = mt; merge[wave][col][1] = lt; }
+#pragma unroll
+            for (int e = 0; e < N; ++e) merge[wave][col][2 + c * N + e] = o[col][e];
+        }
+    }
+    __syncthreads();
+    // ---- merge the four waves, in wave order; thread t handles element t of the G x D outputs ---------------
+    for (int idx = tid; idx < G * D; idx += 256) {
+        const int col = idx / D, e = idx % D;
+        float mt = NEG_BIG;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mt = fmaxf(mt, merge[w][col][0]);
+        float lt = 0.f, ot = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float a = __builtin_amdgcn_exp2f(merge[w][col][0] - mt);
+            lt += merge[w][col][1] * a;
+            ot += merge[w][col][2 + e] * a;
+        }
+        float* dst = partials + ((size_t)unit * Hq + g * G + col) * PF;
+        if (e == 0) { dst[0] = mt; dst[1] = lt; }
+        dst[2 + e] = ot;
+    }
+}
+
+// rot_table[u][p] = (cos, sin)(seg_delta[u] * theta_p), theta_p = base^(-2 (p + index_base) / d): fp64, rounded once.
+__global__ void decode_rot_table_kernel(const int32_t* __restrict__ seg_delta, int half_d, int d, double base,
+                                        int index_base, float2* __restrict__ table) {
+    const int u = blockIdx.x;
+    const double delta = (double)seg_delta[u];
+    for (int p = threadIdx.x; p < half_d; p += blockDim.x) {
+        const double theta = pow(base, -2.0 * (double)(p + index_base) / (double)d);
+        double sn, cs;
+        sincos(delta * theta, &sn, &cs);
+        table[(size_t)u * half_d + p] = make_float2((float)cs, (float)sn);
+    }
+}
+
+// One wave per (query, query head): merges the units of the query in a fixed order (its segments, then its page).
+template <typename T, int D>
+__global__ __launch_bounds__(64) void decode_combine_kernel(const float* __restrict__ partials,
+                                                            const int32_t* __restrict__ seg_offsets, int n_seg, int Hq,
+                                                            T* __restrict__ out, float* __restrict__ lse_out) {
+    constexpr int PF = part_floats<D>();
+    constexpr int EPT = D / 64;   // elements per lane
+    const int b = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    int s0 = seg_offsets[b], s1 = seg_offsets[b + 1];
+    s0 = max(0, min(s0, n_seg));
+    s1 = max(s0, min(s1, n_seg));
+    float mt = NEG_BIG, lt = 0.f, ot[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) ot[e] = 0.f;
+    for (int u = s0; u <= s1; ++u) {   // u == s1 stands for the page
+        const int unit = (u < s1) ? u : n_seg + b;
+        const float* p = partials + ((size_t)unit * Hq + h) * PF;
+        const float mu = p[0], lu = p[1];
+        const float m_new = fmaxf(mt, mu);
+        const float a_old = __builtin_amdgcn_exp2f(mt - m_new), a_new = __builtin_amdgcn_exp2f(mu - m_new);
+        lt = lt * a_old + lu * a_new;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) ot[e] = ot[e] * a_old + p[2 + lane * EPT + e] * a_new;
+        mt = m_new;
+    }
+    const float inv = 1.0f / lt;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) out[((size_t)b * Hq + h) * D + lane * EPT + e] = Elem<T>::from_f32(ot[e] * inv);
+    if (lse_out != nullptr && lane == 0) lse_out[(size_t)b * Hq + h] = (mt + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f;
+}
+
+// Sets the bits of the listed store rows in one query's mask (optionally clearing the mask first).
+__global__ void mark_stale_kernel(uint32_t* __restrict__ bits, int64_t n_words, const int32_t* __restrict__ rows,
+                                  int n_rows) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_rows) return;
+    const int64_t row = rows[i];
+    if (row < 0 || (row >> 5) >= n_words) return;
+    atomicOr(&bits[row >> 5], 1u << (row & 31));
+}
+__global__ void clear_words_kernel(uint32_t* __restrict__ bits, int64_t n_words) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_words) bits[i] = 0u;
+}
+
+template <typename T, int D, int G>
+hipError_t run(const Shape& s, const DecodeArgs& a, float* partials, float2* rot_table, hipStream_t st) {
+    const float scale_log2e = (1.0f / sqrtf((float)D)) * 1.4426950408889634f;
+    const int units = a.n_seg + a.B;
+    if (a.n_seg > 0)
+        decode_rot_table_kernel<<<dim3(a.n_seg), dim3(64), 0, st>>>(a.seg_delta, D / 2, D, s.rope_base, s.rope_index_base,
+                                                                    rot_table);
+    decode_partial_kernel<T, D, G><<<dim3(units, s.Hkv), dim3(256), 0, st>>>(
+        (const T*)a.q, a.B, (const T*)a.k_shared, (const T*)a.v_shared, a.n_shared, a.seg_offsets, a.seg_row0, a.seg_len,
+        a.seg_delta, a.n_seg, a.stale_bits, a.stale_words, (const T*)a.k_pages, (const T*)a.v_pages, a.page_stride,
+        a.page_len, s.Hq, s.Hkv, rot_table, s.rope_layout, scale_log2e, partials);
+    decode_combine_kernel<T, D><<<dim3(a.B, s.Hq), dim3(64), 0, st>>>(partials, a.seg_offsets, a.n_seg, s.Hq, (T*)a.out,
+                                                                      a.lse_out);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t run_g(const Shape& s, const DecodeArgs& a, float* partials, float2* rot_table, hipStream_t st) {
+    switch (s.G) {
+        case 1: return run<T, D, 1>(s, a, partials, rot_table, st);
+        case 2: return run<T, D, 2>(s, a, partials, rot_table, st);
+        case 4: return run<T, D, 4>(s, a, partials, rot_table, st);
+        case 8: return run<T, D, 8>(s, a, partials, rot_table, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+bool decode_supported(const Shape& s) { return s.G == 1 || s.G == 2 || s.G == 4 || s.G == 8; }
+
+size_t decode_partials_bytes(const Shape& s) {
+    return (size_t)DECODE_MAX_UNITS * s.Hq * (s.d + 2) * sizeof(float);
+}
+
+size_t decode_rot_table_bytes(const Shape& s) { return (size_t)DECODE_MAX_UNITS * (s.d / 2) * sizeof(float2); }
+
+hipError_t launch_decode_attn(const Shape& s, const DecodeArgs& a, float* partials, float2* rot_table, hipStream_t st) {
+    if (a.B == 0) return hipSuccess;
+    if (s.dtype == FR_BF16)
+        return s.d == 128 ? run_g<__bf16, 128>(s, a, partials, rot_table, st) : run_g<__bf16, 64>(s, a, partials, rot_table, st);
+    return s.d == 128 ? run_g<float, 128>(s, a, partials, rot_table, st) : run_g<float, 64>(s, a, partials, rot_table, st);
+}
+
+hipError_t launch_mark_stale(uint32_t* bits, int64_t n_words, const int32_t* rows, int n_rows, int clear, hipStream_t st) {
+    if (clear && n_words > 0)
+        clear_words_kernel<<<dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st>>>(bits, n_words);
+    if (n_rows > 0) mark_stale_kernel<<<dim3((n_rows + 255) / 256), dim3(256), 0, st>>>(bits, n_words, rows, n_rows);
+    return hipGetLastError();
+}
+
+}  // namespace fr
