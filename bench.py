@@ -205,14 +205,96 @@ def bench_offline(args):
     ctx.close()
 
 
+def bench_decode(args):
+    """One decoding step of a batch (Sec. 4.3): 32 queries, each over 16 cached chunks of 1024 tokens (15 % of them
+    recomputed and therefore masked in the shared store) plus its exclusive page (2458 fresh + 512 question + 8
+    generated rows).  Two stores: every query has its own chunks (2.1 GB of K/V: nothing is shared, HBM streaming),
+    or all queries draw their chunks from 64 shared ones (134 MB: the caches serve the re-reads)."""
+    from paper_2601_12904_amd import binding as B
+    from paper_2601_12904_amd import synth
+    from tests import harness as H
+
+    shape = synth.LLAMA3_8B_BF16
+    Hq, Hkv, d, e = shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 2
+    bf = torch.bfloat16
+    nb, chunks_per_q, clen, ratio, nq, n_gen = 32, 16, 1024, 0.15, 512, 8
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(args.seed)
+    rng = np.random.default_rng(args.seed)
+    ctx = H.make_ctx(shape, 1024, 4, 8)
+    sig = 1.0 / np.sqrt(d)
+    L_ctx = chunks_per_q * clen
+    k_crit = B.fr_topk_count(L_ctx, ratio)
+    P = k_crit + nq + n_gen
+    q = (torch.randn((nb, Hq, d), generator=gen, device="cuda") * np.sqrt(d)).to(bf)
+    kp = (torch.randn((nb, P, Hkv, d), generator=gen, device="cuda") * sig).to(bf)
+    vp = (torch.randn((nb, P, Hkv, d), generator=gen, device="cuda") * sig).to(bf)
+    plen = torch.full((nb,), P, dtype=torch.int32, device="cuda")
+    out = torch.empty((nb, Hq, d), dtype=bf, device="cuda")
+    results = {}
+    for mode, n_store_chunks in (("private_chunks", nb * chunks_per_q), ("shared_chunks", 64)):
+        N = n_store_chunks * clen
+        ks = (torch.randn((N, Hkv, d), generator=gen, device="cuda") * sig).to(bf)
+        vs = (torch.randn((N, Hkv, d), generator=gen, device="cuda") * sig).to(bf)
+        words = (N + 31) // 32
+        bits = torch.zeros((nb, words), dtype=torch.int32, device="cuda")
+        row0, ln, dl = [], [], []
+        for b in range(nb):
+            ids = (np.arange(chunks_per_q) + b * chunks_per_q) if mode == "private_chunks" else \
+                rng.choice(n_store_chunks, size=chunks_per_q, replace=False)
+            rows = []
+            for j, c in enumerate(ids):
+                row0.append(int(c) * clen); ln.append(clen); dl.append(j * clen - int(rng.integers(0, 4096)))
+                rows.append(np.arange(int(c) * clen, int(c) * clen + clen))
+            crit = rng.choice(np.concatenate(rows), size=k_crit, replace=False).astype(np.int32)
+            ctx.fr_mark_stale_rows(bits[b], words, torch.from_numpy(crit).cuda(), k_crit, clear=True)
+        i32 = lambda a: torch.tensor(a, dtype=torch.int32, device="cuda")
+        seg_off = i32(list(range(0, nb * chunks_per_q + 1, chunks_per_q)))
+        row0, ln, dl = i32(row0), i32(ln), i32(dl)
+        n_seg = nb * chunks_per_q
+
+        def step():
+            ctx.fr_decode_attn(q, nb, ks, vs, N, seg_off, row0, ln, dl, n_seg, bits, words, kp, vp, P, plen, out)
+
+        for _ in range(args.warmup):
+            step()
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            step()
+        b_.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b_) / args.steps
+        assert bool(torch.isfinite(out.float()).all())
+        # rows the method must read: the unmasked store rows and the page rows of every query, K and V
+        needed = nb * ((L_ctx - k_crit) + P) * Hkv * d * e * 2
+        streamed = nb * (L_ctx + P) * Hkv * d * e * 2          # what the kernel touches (masked rows are read, then dropped)
+        results[mode] = {"ms": round(ms, 4), "needed_gbps": round(needed / (ms * 1e-3) / 1e9, 1),
+                         "streamed_gbps": round(streamed / (ms * 1e-3) / 1e9, 1), "store_gb": round(2 * N * Hkv * d * e / 1e9, 3)}
+        del ks, vs, bits
+    r = results["private_chunks"]
+    print(json.dumps({
+        "metric": "batch decoding step over shared chunk caches + exclusive pages (ms), 32 queries x 17k ctx",
+        "value": r["ms"], "unit": "ms/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama3_8b_decode_32q_x_(16x1024_chunks+2978_page_rows)", "queries": nb,
+                   "chunks_per_query": chunks_per_q, "chunk_tokens": clen, "recompute_ratio": ratio, "page_rows": P,
+                   "seed": args.seed},
+        "stores": results,
+        "roofline": {"kernel": "decode_partial_kernel", "bound": "hbm", "achieved": r["needed_gbps"], "peak": PEAK_HBM_GBPS,
+                     "unit": "GB/s", "frac": round(r["needed_gbps"] / PEAK_HBM_GBPS, 4), "traffic": None},
+    }))
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4, 5, 6],
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4, 5, 6, 7],
                     help="2 = the headline layer; 5 = the 32-layer Llama-3-8B-shaped stack over config 2's prompt; "
-                         "6 = offline preprocessing of one chunk (eq. 10)")
+                         "6 = offline preprocessing of one chunk (eq. 10); 7 = one batch-decoding step (Sec. 4.3)")
     ap.add_argument("--layers", type=int, default=32, help="decoder layers of the --config 5 stack")
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--seed", type=int, default=0)
@@ -237,6 +319,8 @@ def main():
         return bench_stack(args)
     if args.config == 6:
         return bench_offline(args)
+    if args.config == 7:
+        return bench_decode(args)
     w = synth.CONFIGS[args.config](seed=args.seed) if args.ratio is None else \
         synth.CONFIGS[args.config](seed=args.seed, ratio=args.ratio)
     dt, tdt = w.shape.dtype, H.TORCH_DTYPE[w.shape.dtype]

@@ -93,8 +93,11 @@ int64_t fr_workspace_bytes(const fr_ctx* ctx);
  * running maximum everywhere.  Both give the same softmax; the option exists so that tests reach both.
  * FR_OPT_ATTN_SPLIT: AUTO (default) lets two workgroups share the key range of every (row tile, KV head) when
  * there are too few of those to fill the chip (few recomputed rows, e.g. the offline stage of eq. 10); OFF / ON
- * force one or the other.  Same results up to fp32 summation order. */
-typedef enum { FR_OPT_ATTN_SOFTMAX = 1, FR_OPT_ATTN_SPLIT = 2 } fr_option;
+ * force one or the other.  Same results up to fp32 summation order.
+ * FR_OPT_DECODE_KERNEL: AUTO (default) lets fr_decode_attn form the logits on the matrix cores where it can (bf16,
+ * head_dim 128); GENERIC forces the all-vector-ALU kernel that every other shape uses (so that tests reach both). */
+typedef enum { FR_OPT_ATTN_SOFTMAX = 1, FR_OPT_ATTN_SPLIT = 2, FR_OPT_DECODE_KERNEL = 3 } fr_option;
+typedef enum { FR_DECODE_KERNEL_AUTO = 0, FR_DECODE_KERNEL_GENERIC = 1 } fr_decode_kernel;
 typedef enum { FR_ATTN_SOFTMAX_AUTO = 0, FR_ATTN_SOFTMAX_RUNNING_MAX = 1 } fr_attn_softmax;
 typedef enum { FR_ATTN_SPLIT_AUTO = 0, FR_ATTN_SPLIT_OFF = 1, FR_ATTN_SPLIT_ON = 2 } fr_attn_split;
 fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value);

@@ -21,6 +21,8 @@ STATUS_NAMES = {0: "FR_OK", 1: "FR_ERR_INVALID_ARG", 2: "FR_ERR_UNSUPPORTED", 3:
                 4: "FR_ERR_DEVICE"}
 FR_OPT_ATTN_SOFTMAX = 1
 FR_OPT_ATTN_SPLIT = 2
+FR_OPT_DECODE_KERNEL = 3
+FR_DECODE_KERNEL_AUTO, FR_DECODE_KERNEL_GENERIC = 0, 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 FR_ATTN_SPLIT_AUTO, FR_ATTN_SPLIT_OFF, FR_ATTN_SPLIT_ON = 0, 1, 2
 EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_topk_count", "fr_rope_shift",

@@ -183,6 +183,11 @@ fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value) {
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_ATTN_SOFTMAX: unknown value %lld", (long long)value);
             ctx->attn_softmax_mode = (int)value;
             return FR_OK;
+        case FR_OPT_DECODE_KERNEL:
+            if (value != FR_DECODE_KERNEL_AUTO && value != FR_DECODE_KERNEL_GENERIC)
+                return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_DECODE_KERNEL: unknown value %lld", (long long)value);
+            ctx->decode_generic = (value == FR_DECODE_KERNEL_GENERIC) ? 1 : 0;
+            return FR_OK;
         case FR_OPT_ATTN_SPLIT:
             if (value != FR_ATTN_SPLIT_AUTO && value != FR_ATTN_SPLIT_OFF && value != FR_ATTN_SPLIT_ON)
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_ATTN_SPLIT: unknown value %lld", (long long)value);
@@ -402,6 +407,7 @@ fr_status fr_decode_attn(fr_ctx* ctx, const void* q, int32_t n_queries, const vo
     a.stale_bits = stale_bits; a.stale_words = stale_words;
     a.k_pages = k_pages; a.v_pages = v_pages; a.page_stride = page_stride_rows; a.page_len = page_len;
     a.out = out; a.lse_out = lse_out;
+    a.force_generic = ctx->decode_generic;
     hipError_t e = launch_decode_attn(ctx->shape, a, ctx->ws.decode_partials, ctx->ws.decode_rot, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "decode attention launch", e);
     return FR_OK;

@@ -62,6 +62,7 @@ struct fr_ctx {
     fr::Workspace ws;
     int attn_softmax_mode = FR_ATTN_SOFTMAX_AUTO;
     int attn_split_mode = FR_ATTN_SPLIT_AUTO;
+    int decode_generic = 0;
     std::string err;
 };
 
@@ -96,6 +97,7 @@ struct DecodeArgs {
     const uint32_t* stale_bits; int64_t stale_words;
     const void *k_pages, *v_pages; int64_t page_stride; const int32_t* page_len;
     void* out; float* lse_out;
+    int force_generic;   // 1: the all-vector-ALU kernel also where the matrix-core one applies (tests)
 };
 constexpr int DECODE_MAX_UNITS = 4096;   // segments + queries of one call (sizes the partial-result buffer)
 bool decode_supported(const Shape& s);

@@ -5,6 +5,7 @@ import pytest
 import torch
 
 from oracle import fusionrag_oracle as orc
+from paper_2601_12904_amd import binding as B
 from paper_2601_12904_amd import synth
 from tests import harness as H
 
@@ -28,8 +29,8 @@ def make_batch(shape, seed, chunk_lens=(70, 130, 3, 257, 64), prompts=((0, 1, 3)
     N = int(offs[-1])
     src_pos0 = rng.integers(0, 3000, size=len(chunk_lens))
     k_store, v_store = rnd(N, Hkv, 1.0 / np.sqrt(d)), rnd(N, Hkv, 1.0 / np.sqrt(d))
-    B = len(prompts)
-    q = rnd(B, Hq, float(np.sqrt(d)))
+    nb = len(prompts)
+    q = rnd(nb, Hq, float(np.sqrt(d)))
     segments, stale, k_pages, v_pages = [], [], [], []
     for b, chunks in enumerate(prompts):
         pos, segs, rows = 0, [], []
@@ -48,12 +49,14 @@ def make_batch(shape, seed, chunk_lens=(70, 130, 3, 257, 64), prompts=((0, 1, 3)
                 v_pages=v_pages, page_stride=page_stride or max(len(p) for p in k_pages) + 3)
 
 
-def run_gpu(bt, use_mark=True, with_stale=True):
+def run_gpu(bt, use_mark=True, with_stale=True, generic=False):
     shape = bt["shape"]
     dt, tdt = shape.dtype, H.TORCH_DTYPE[shape.dtype]
     Hq, Hkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
-    B = len(bt["segments"])
+    nb = len(bt["segments"])
     ctx = H.make_ctx(shape, 1024, 4, 8)
+    if generic:
+        ctx.fr_set_option(B.FR_OPT_DECODE_KERNEL, B.FR_DECODE_KERNEL_GENERIC)
     seg_off = np.concatenate([[0], np.cumsum([len(s) for s in bt["segments"]])]).astype(np.int32)
     flat = [s for segs in bt["segments"] for s in segs]
     n_seg = len(flat)
@@ -62,8 +65,8 @@ def run_gpu(bt, use_mark=True, with_stale=True):
     words = (bt["N"] + 31) // 32
     bits = None
     if with_stale:
-        bits = torch.full((B, words), 0x5A5A5A5A, dtype=torch.int32, device="cuda")   # garbage: must be cleared
-        for b in range(B):
+        bits = torch.full((nb, words), 0x5A5A5A5A, dtype=torch.int32, device="cuda")   # garbage: must be cleared
+        for b in range(nb):
             if use_mark:
                 rows = i32(bt["stale"][b]) if len(bt["stale"][b]) else None
                 ctx.fr_mark_stale_rows(bits[b], words, rows, len(bt["stale"][b]), clear=True)
@@ -73,17 +76,17 @@ def run_gpu(bt, use_mark=True, with_stale=True):
                     w[r >> 5] |= np.uint32(1) << np.uint32(r & 31)
                 bits[b] = torch.from_numpy(w.view(np.int32)).cuda()
     ps = bt["page_stride"]
-    kp = torch.zeros((B, ps, Hkv, d), dtype=tdt, device="cuda")
-    vp = torch.zeros((B, ps, Hkv, d), dtype=tdt, device="cuda")
-    for b in range(B):
+    kp = torch.zeros((nb, ps, Hkv, d), dtype=tdt, device="cuda")
+    vp = torch.zeros((nb, ps, Hkv, d), dtype=tdt, device="cuda")
+    for b in range(nb):
         P = len(bt["k_pages"][b])
         kp[b, :P] = H.dev(bt["k_pages"][b], dt)
         vp[b, :P] = H.dev(bt["v_pages"][b], dt)
         kp[b, P:] = 1000.0          # rows past page_len must not be read
     plen = i32([len(p) for p in bt["k_pages"]])
-    out = torch.zeros((B, Hq, d), dtype=tdt, device="cuda")
-    lse = torch.zeros((B, Hq), dtype=torch.float32, device="cuda")
-    ctx.fr_decode_attn(H.dev(bt["q"], dt), B, H.dev(bt["k_store"], dt), H.dev(bt["v_store"], dt), bt["N"], i32(seg_off),
+    out = torch.zeros((nb, Hq, d), dtype=tdt, device="cuda")
+    lse = torch.zeros((nb, Hq), dtype=torch.float32, device="cuda")
+    ctx.fr_decode_attn(H.dev(bt["q"], dt), nb, H.dev(bt["k_store"], dt), H.dev(bt["v_store"], dt), bt["N"], i32(seg_off),
                        row0, ln, dl, n_seg, bits, words if with_stale else 0, kp, vp, ps, plen, out, lse)
     torch.cuda.synchronize()
     res = H.host(out), lse.cpu().numpy().astype(np.float64), (bits.cpu().numpy().view(np.uint32) if with_stale else None)
@@ -136,3 +139,18 @@ def test_decode_attn_descriptor_ranges_are_clamped():
     want, _ = orc.decode_attn(bt["q"], bt["k_store"], bt["v_store"], bt_ref["segments"], bt["stale"], bt["k_pages"],
                               bt["v_pages"], shape.rope_base)
     H.assert_close(got, want, "bf16", "clamped segments")
+
+
+@pytest.mark.parametrize("seed", [2, 3])
+def test_decode_attn_both_kernels(seed):
+    """bf16, head_dim 128: the matrix-core kernel (default) and the generic one (forced) against the oracle, on a
+    batch with long ragged segments (several 32-row blocks per wave, ragged tails, unaligned mask words)."""
+    shape = SHAPES["llama_bf16"]
+    bt = make_batch(shape, seed, chunk_lens=(333, 1, 1025, 31, 640), prompts=((2, 0, 4), (1, 3), (4, 2, 1, 0, 3)),
+                    nq=(40, 3, 11), n_gen=(2, 1, 5))
+    want, want_lse = orc.decode_attn(bt["q"], bt["k_store"], bt["v_store"], bt["segments"], bt["stale"], bt["k_pages"],
+                                     bt["v_pages"], shape.rope_base)
+    for generic in (False, True):
+        got, lse, _ = run_gpu(bt, generic=generic)
+        H.assert_close(got, want, "bf16", f"decode attention (generic={generic})")
+        assert np.max(np.abs(lse - want_lse)) <= 2e-3

@@ -103,6 +103,29 @@ def test_kv_deviation_argument_errors(ctx):
     ctx.fr_kv_deviation(None, None, 0, None)                                                  # nothing to do
 
 
+def test_decode_argument_errors(ctx):
+    P = 4096
+    ok = (P, 2, P, P, 100, P, P, P, P, 3, P, 4, P, P, 64, P, P)
+    def call(**kw):
+        names = ("q", "n_queries", "k_shared", "v_shared", "n_shared_rows", "seg_offsets", "seg_row0", "seg_len", "seg_delta",
+                 "n_segments", "stale_bits", "stale_words", "k_pages", "v_pages", "page_stride_rows", "page_len", "out")
+        a = dict(zip(names, ok))
+        a.update(kw)
+        return lambda: ctx.fr_decode_attn(*[a[n] for n in names])
+    expect(B.FR_ERR_INVALID_ARG, call(n_queries=-1))
+    expect(B.FR_ERR_INVALID_ARG, call(q=None))
+    expect(B.FR_ERR_INVALID_ARG, call(k_pages=P + 4))
+    expect(B.FR_ERR_INVALID_ARG, call(seg_row0=None))
+    expect(B.FR_ERR_INVALID_ARG, call(k_shared=None))
+    expect(B.FR_ERR_INVALID_ARG, call(page_len=None))
+    expect(B.FR_ERR_WORKSPACE, call(n_segments=4095))
+    call(n_queries=0, q=None)()                                                               # nothing to do
+    expect(B.FR_ERR_INVALID_ARG, ctx.fr_mark_stale_rows, None, 4, P, 3)
+    expect(B.FR_ERR_INVALID_ARG, ctx.fr_mark_stale_rows, P, 4, None, 3)
+    ctx.fr_mark_stale_rows(P, 0, P, 3)                                                        # no words: nothing to do
+    expect(B.FR_ERR_INVALID_ARG, ctx.fr_set_option, B.FR_OPT_DECODE_KERNEL, 5)
+
+
 def test_attention_and_scatter_argument_errors(ctx):
     P = 4096
     expect(B.FR_ERR_INVALID_ARG, ctx.fr_sparse_prefill_attn, P, P, 5, P, P, 4, P, P, P)      # R > L
@@ -125,4 +148,6 @@ def test_valid_call_without_gpu_reports_device_error(ctx):
     expect(B.FR_ERR_DEVICE, ctx.fr_rope_shift, P, P, [0, 5], [0])
     expect(B.FR_ERR_DEVICE, ctx.fr_kv_scatter, P, P, P, 5, P, P, 100)
     expect(B.FR_ERR_DEVICE, ctx.fr_kv_deviation, P, P, 5, P)
+    expect(B.FR_ERR_DEVICE, ctx.fr_decode_attn, P, 2, P, P, 100, P, P, P, P, 3, P, 4, P, P, 64, P, P)
+    expect(B.FR_ERR_DEVICE, ctx.fr_mark_stale_rows, P, 4, P, 3)
     assert ctx.workspace_bytes() == 0
