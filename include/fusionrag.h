@@ -95,8 +95,10 @@ int64_t fr_workspace_bytes(const fr_ctx* ctx);
  * there are too few of those to fill the chip (few recomputed rows, e.g. the offline stage of eq. 10); OFF / ON
  * force one or the other.  Same results up to fp32 summation order.
  * FR_OPT_DECODE_KERNEL: AUTO (default) lets fr_decode_attn form the logits on the matrix cores where it can (bf16,
- * head_dim 128); GENERIC forces the all-vector-ALU kernel that every other shape uses (so that tests reach both). */
-typedef enum { FR_OPT_ATTN_SOFTMAX = 1, FR_OPT_ATTN_SPLIT = 2, FR_OPT_DECODE_KERNEL = 3 } fr_option;
+ * head_dim 128); GENERIC forces the all-vector-ALU kernel that every other shape uses (so that tests reach both).
+ * FR_OPT_GEMM_TILE: output features per workgroup of the projection kernels, 0 (default: 256 where the feature count
+ * is a multiple of 256, else 128), 128 or 256; process-wide, for tests and tuning. */
+typedef enum { FR_OPT_ATTN_SOFTMAX = 1, FR_OPT_ATTN_SPLIT = 2, FR_OPT_DECODE_KERNEL = 3, FR_OPT_GEMM_TILE = 4 } fr_option;
 typedef enum { FR_DECODE_KERNEL_AUTO = 0, FR_DECODE_KERNEL_GENERIC = 1 } fr_decode_kernel;
 typedef enum { FR_ATTN_SOFTMAX_AUTO = 0, FR_ATTN_SOFTMAX_RUNNING_MAX = 1 } fr_attn_softmax;
 typedef enum { FR_ATTN_SPLIT_AUTO = 0, FR_ATTN_SPLIT_OFF = 1, FR_ATTN_SPLIT_ON = 2 } fr_attn_split;

@@ -22,6 +22,7 @@ STATUS_NAMES = {0: "FR_OK", 1: "FR_ERR_INVALID_ARG", 2: "FR_ERR_UNSUPPORTED", 3:
 FR_OPT_ATTN_SOFTMAX = 1
 FR_OPT_ATTN_SPLIT = 2
 FR_OPT_DECODE_KERNEL = 3
+FR_OPT_GEMM_TILE = 4
 FR_DECODE_KERNEL_AUTO, FR_DECODE_KERNEL_GENERIC = 0, 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 FR_ATTN_SPLIT_AUTO, FR_ATTN_SPLIT_OFF, FR_ATTN_SPLIT_ON = 0, 1, 2

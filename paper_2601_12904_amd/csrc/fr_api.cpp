@@ -188,6 +188,11 @@ fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value) {
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_DECODE_KERNEL: unknown value %lld", (long long)value);
             ctx->decode_generic = (value == FR_DECODE_KERNEL_GENERIC) ? 1 : 0;
             return FR_OK;
+        case FR_OPT_GEMM_TILE:
+            if (value != 0 && value != 128 && value != 256)
+                return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_GEMM_TILE: %lld is not 0, 128 or 256", (long long)value);
+            launch_gemm_set_tile((int)value);
+            return FR_OK;
         case FR_OPT_ATTN_SPLIT:
             if (value != FR_ATTN_SPLIT_AUTO && value != FR_ATTN_SPLIT_OFF && value != FR_ATTN_SPLIT_ON)
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_ATTN_SPLIT: unknown value %lld", (long long)value);

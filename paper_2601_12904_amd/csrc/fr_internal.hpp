@@ -123,6 +123,7 @@ constexpr int ATTN_SPLIT_AUTO_ITEMS = 400;
 constexpr int ATTN_SPLIT_MAX_ITEMS = 768;
 size_t attn_mfma_partials_bytes(const Shape& s, int64_t max_tokens);
 
+void launch_gemm_set_tile(int features_per_workgroup);   // 0 = choose, 128, 256
 hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
                          hipStream_t st);
 hipError_t launch_linear_swiglu(const void* a, const void* w_gate_up, int M, int F, int K, void* out, hipStream_t st);

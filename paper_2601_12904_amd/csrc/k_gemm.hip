@@ -6,8 +6,10 @@
 // kernel computes the transposed tile C^T = W A^T with v_mfma_f32_32x32x16_bf16: output features run along the
 // accumulator's register dimension and activation rows along lanes, which puts four consecutive features of one
 // row into one lane -- rotary pairs and (gate, up) pairs are then combined without any lane exchange.
-// One workgroup (4 waves, 2 x 2) computes 128 features x 128 rows; each wave 64 x 64.  K is walked in tiles of
-// 64: both operand tiles (128 rows of 128 bytes) are copied straight into an LDS ring with direct-to-LDS loads
+// One workgroup computes (64 WF) features x 128 rows with WF x 2 waves of 64 x 64 each: WF = 4 (8 waves, two per
+// SIMD, so one wave's LDS reads and barriers hide behind the other's matrix instructions; 48 KB per K tile, ring
+// of 3) where the feature count allows, else WF = 2 (4 waves, 32 KB per K tile, ring of 4).  K is walked in tiles
+// of 64: both operand tiles (rows of 128 bytes) are copied straight into an LDS ring with direct-to-LDS loads
 // (no staging registers); each lane chooses which 16-byte chunk of its row it fetches so that chunk c of row r
 // lands at chunk position c ^ swz(r), swz(r) = (r ^ (r >> 3)) & 7: the 16-byte fragment reads (one lane per row)
 // of any 16 consecutive rows then fall into 16 distinct bank groups.
@@ -23,29 +25,51 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int BF = 128;   // output features per workgroup (MFMA M side)
 constexpr int BR = 128;   // activation rows per workgroup (MFMA N side)
 constexpr int BK = 64;    // K elements per tile: 128 bytes per row
-constexpr int TILE_BYTES = 128 * BK * 2;            // one operand tile: 16 KB
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;         // W tile then A tile
-constexpr int N_STAGE = 4;
 constexpr int EPI_PITCH = 64 + 4;                   // fp32 elements per row of a wave's epilogue staging
+
+template <int WF>
+struct Tiling {
+    static constexpr int NW = 2 * WF;                    // waves per workgroup
+    static constexpr int BF = 64 * WF;                   // output features per workgroup (MFMA M side)
+    static constexpr int W_TILE_BYTES = BF * BK * 2;     // 16 or 32 KB
+    static constexpr int A_TILE_BYTES = BR * BK * 2;     // 16 KB
+    static constexpr int STAGE_BYTES = W_TILE_BYTES + A_TILE_BYTES;
+    static constexpr int N_STAGE = (WF == 4) ? 3 : 4;
+    static constexpr int W_ROUNDS = BF * 8 / (NW * 64);  // direct-to-LDS instructions per lane and W tile
+    static constexpr int A_ROUNDS = BR * 8 / (NW * 64);
+    static constexpr int LDS_BYTES = N_STAGE * STAGE_BYTES;
+    static_assert(NW * 64 * EPI_PITCH * 4 <= LDS_BYTES, "epilogue staging must fit into the ring");
+};
 
 __device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
 
-// Copy one 128-row x 128-byte operand tile into LDS.  Chunk u (16 bytes) of the tile sits at byte 16 u; the
-// four waves move 4 KB each.  `rows` bounds the operand (rows past the end are clamped and never stored).
+// Copy one operand tile (rows of 128 bytes) into LDS.  Chunk u (16 bytes) of the tile sits at byte 16 u; every wave
+// moves 1 KB per round.  `rows` bounds the operand (rows past the end are clamped and never stored).
+template <int ROUNDS, int NW>
 __device__ __forceinline__ void dma_tile(const __bf16* __restrict__ base, int64_t ld, int row0, int rows, int k0,
                                          unsigned char* lds_tile, int wave, int lane) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int u = (wave * 4 + j) * 64 + lane;
+    for (int j = 0; j < ROUNDS; ++j) {
+        const int blk = j * NW + wave;
+        const int u = blk * 64 + lane;
         const int r = u >> 3, cpos = u & 7;
         const int c = cpos ^ swz(r);
         const __bf16* src = base + (int64_t)min(row0 + r, rows - 1) * ld + k0 + 8 * c;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)(lds_tile + (wave * 4 + j) * 1024), 16, 0, 0);
+                                         (__attribute__((address_space(3))) void*)(lds_tile + blk * 1024), 16, 0, 0);
     }
+}
+
+// Workgroup barrier without the fences of __syncthreads(): those make the compiler wait for *all* outstanding
+// memory operations (vmcnt(0)), which would drain the direct-to-LDS copies and register prefetches that are meant
+// to stay in flight across the barrier.  The callers wait by hand for exactly the copies the next phase needs; the
+// empty asm statements keep the compiler from moving LDS accesses across the barrier.
+__device__ __forceinline__ void barrier_keep_loads_in_flight() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 enum { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_QKV_ROPE = 2, EPI_SWIGLU = 3 };
@@ -62,68 +86,12 @@ struct GemmArgs {
     int Hq, Hkv, d;
 };
 
-// grid.x = feature tiles (fastest), grid.y = row tiles: workgroups that share an activation tile are neighbours.
+// Epilogue shared by the kernels: this wave's fp32 64 x 64 tile goes through LDS ([row][feature]), then every lane
+// handles 8 consecutive features of a row.  fw0 / rw0 = first feature / row of the wave's tile.
 template <int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
-    const int wf = wave & 1, wr = wave >> 1;           // wave position: features x rows
-    const int f0 = blockIdx.x * BF, r0 = blockIdx.y * BR;
-    const int n_kt = g.K / BK;
-
-    // fragment byte offsets inside a tile: row (32 blk + x) of this wave's half, k step ks -> chunk (2 ks + h)
-    int frag[4][2];   // [ks][blk & 1]
-    {
-        const int keyx = (x ^ (x >> 3)) & 7;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int par = 0; par < 2; ++par) frag[ks][par] = x * 128 + (((2 * ks + h) ^ keyx ^ (4 * par)) << 4);
-    }
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
-
-    auto issue = [&](int kt) {
-        unsigned char* st = smem + (kt % N_STAGE) * STAGE_BYTES;
-        dma_tile(g.w, g.K, f0, g.N, kt * BK, st, wave, lane);
-        dma_tile(g.a, g.K, r0, g.M, kt * BK, st + TILE_BYTES, wave, lane);
-    };
-#pragma unroll
-    for (int p = 0; p < N_STAGE - 1; ++p)
-        if (p < n_kt) issue(p);
-
-    for (int kt = 0; kt < n_kt; ++kt) {
-        // own copies of tile kt are the oldest outstanding: wait until at most the (N_STAGE - 2) newer tiles remain
-        if (kt + N_STAGE - 2 < n_kt) {
-            __builtin_amdgcn_s_waitcnt(0x0f70 | (8 * (N_STAGE - 2) & 15) | (((8 * (N_STAGE - 2)) >> 4) << 14));
-        } else {
-            __builtin_amdgcn_s_waitcnt(0x0f70);
-        }
-        __syncthreads();   // tile kt complete and visible; everyone is done with tile kt-1, whose stage is refilled next
-        if (kt + N_STAGE - 1 < n_kt) issue(kt + N_STAGE - 1);
-        const unsigned char* wt = smem + (kt % N_STAGE) * STAGE_BYTES + (64 * wf) * 128;
-        const unsigned char* at = smem + (kt % N_STAGE) * STAGE_BYTES + TILE_BYTES + (64 * wr) * 128;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 wfrag[2], afrag[2];
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                wfrag[b] = *reinterpret_cast<const bf16x8*>(wt + b * (32 * 128) + frag[ks][b]);
-                afrag[b] = *reinterpret_cast<const bf16x8*>(at + b * (32 * 128) + frag[ks][b]);
-            }
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[mb], afrag[nb], acc[mb][nb], 0, 0, 0);
-        }
-    }
-
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16 (&acc)[2][2], unsigned char* smem, int wave, int lane,
+                                              int fw0, int rw0) {
+    const int x = lane & 31, h = lane >> 5;
     // ---- epilogue: fp32 tile through LDS ([row][feature] per wave), then 8 consecutive features per lane ----
     __syncthreads();
     float* ep = reinterpret_cast<float*>(smem) + wave * 64 * EPI_PITCH;
@@ -142,9 +110,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int rl = 8 * i + (lane >> 3), seg = lane & 7;     // local row, group of 8 features
-        const int r = r0 + 64 * wr + rl;
-        const int f = f0 + 64 * wf + 8 * seg;
-        if (r >= g.M) continue;
+        const int r = rw0 + rl;
+        const int f = fw0 + 8 * seg;
+        if (r >= g.M || f >= g.N) continue;
         float v[8];
         {
             const f32x4 lo = *reinterpret_cast<const f32x4*>(&ep[rl * EPI_PITCH + 8 * seg]);
@@ -195,6 +163,75 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     }
 }
 
+// grid.x = feature tiles (fastest), grid.y = row tiles: workgroups that share an activation tile are neighbours.
+template <int EPI, int WF>
+__global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
+    using TL = Tiling<WF>;
+    constexpr int NW = TL::NW, BF = TL::BF, STAGE_BYTES = TL::STAGE_BYTES, N_STAGE = TL::N_STAGE;
+    constexpr int DMA_PER_TILE = TL::W_ROUNDS + TL::A_ROUNDS;   // outstanding copies per lane and K tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int wf = wave % WF, wr = wave / WF;          // wave position: features x rows
+    const int f0 = blockIdx.x * BF, r0 = blockIdx.y * BR;
+    const int n_kt = g.K / BK;
+
+    // fragment byte offsets inside a tile: row (32 blk + x) of this wave's half, k step ks -> chunk (2 ks + h)
+    int frag[4][2];   // [ks][blk & 1]
+    {
+        const int keyx = (x ^ (x >> 3)) & 7;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int par = 0; par < 2; ++par) frag[ks][par] = x * 128 + (((2 * ks + h) ^ keyx ^ (4 * par)) << 4);
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+
+    auto issue = [&](int kt) {
+        unsigned char* st = smem + (kt % N_STAGE) * STAGE_BYTES;
+        dma_tile<TL::W_ROUNDS, NW>(g.w, g.K, f0, g.N, kt * BK, st, wave, lane);
+        dma_tile<TL::A_ROUNDS, NW>(g.a, g.K, r0, g.M, kt * BK, st + TL::W_TILE_BYTES, wave, lane);
+    };
+#pragma unroll
+    for (int p = 0; p < N_STAGE - 1; ++p)
+        if (p < n_kt) issue(p);
+
+    for (int kt = 0; kt < n_kt; ++kt) {
+        // own copies of tile kt are the oldest outstanding: wait until at most the (N_STAGE - 2) newer tiles remain
+        if (kt + N_STAGE - 2 < n_kt) {
+            constexpr int newer = DMA_PER_TILE * (N_STAGE - 2);
+            __builtin_amdgcn_s_waitcnt(0x0f70 | (newer & 15) | ((newer >> 4) << 14));
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0f70);
+        }
+        barrier_keep_loads_in_flight();   // tile kt complete and visible; everyone is done with tile kt-1, whose stage is refilled next
+        if (kt + N_STAGE - 1 < n_kt) issue(kt + N_STAGE - 1);
+        const unsigned char* wt = smem + (kt % N_STAGE) * STAGE_BYTES + (64 * wf) * 128;
+        const unsigned char* at = smem + (kt % N_STAGE) * STAGE_BYTES + TL::W_TILE_BYTES + (64 * wr) * 128;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 wfrag[2], afrag[2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                wfrag[b] = *reinterpret_cast<const bf16x8*>(wt + b * (32 * 128) + frag[ks][b]);
+                afrag[b] = *reinterpret_cast<const bf16x8*>(at + b * (32 * 128) + frag[ks][b]);
+            }
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[mb], afrag[nb], acc[mb][nb], 0, 0, 0);
+        }
+    }
+
+    gemm_epilogue<EPI>(g, acc, smem, wave, lane, f0 + 64 * wf, r0 + 64 * wr);
+}
+
 // y = x * rsqrt(mean(x^2) + eps) * gain, one wave per row, fp32 statistics.
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__ x, const __bf16* __restrict__ gain, int R,
                                                       int hidden, float eps, __bf16* __restrict__ out) {
@@ -231,22 +268,34 @@ __global__ void rope_rows_table_kernel(const int32_t* __restrict__ positions, in
     table[(size_t)r * half_d + p] = make_float2((float)cs, (float)sn);
 }
 
-template <int EPI>
-hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
-    const size_t lds = (size_t)N_STAGE * STAGE_BYTES;   // 128 KB; the epilogue staging (4 x 64 x 68 x 4 B) fits inside
+int g_gemm_tile = 0;   // 0: choose; 128 / 256: features per workgroup (set through launch_gemm_set_tile, for tests)
+
+template <int EPI, int WF>
+hipError_t launch_gemm_wf(const GemmArgs& g, hipStream_t st) {
+    using TL = Tiling<WF>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI, WF>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((g.N + BF - 1) / BF, (g.M + BR - 1) / BR);
-    gemm_bf16_kernel<EPI><<<grid, dim3(256), lds, st>>>(g);
+    dim3 grid((g.N + TL::BF - 1) / TL::BF, (g.M + BR - 1) / BR);
+    gemm_bf16_kernel<EPI, WF><<<grid, dim3(64 * TL::NW), TL::LDS_BYTES, st>>>(g);
     return hipGetLastError();
 }
 
+template <int EPI>
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
+    // (Feeding the weight fragments from memory straight into registers, to halve the LDS traffic, was tried: 16-byte
+    // pieces of 32 rows per load instruction cost far more in the memory pipeline than they save: 400-500 TFLOP/s.)
+    const bool wide = (g_gemm_tile == 256) || (g_gemm_tile == 0 && g.N % 256 == 0);
+    return wide ? launch_gemm_wf<EPI, 4>(g, st) : launch_gemm_wf<EPI, 2>(g, st);
+}
+
 }  // namespace
+
+void launch_gemm_set_tile(int features_per_workgroup) { g_gemm_tile = features_per_workgroup; }
 
 hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
                          hipStream_t st) {

@@ -37,6 +37,25 @@ def test_linear(ctx, M, N, K):
     H.assert_close(H.host(res), orc.linear(a, w, r), "bf16", "linear + residual")
 
 
+@pytest.mark.parametrize("tile", [128, 256])
+@pytest.mark.parametrize("M,N,K", [(130, 256, 192), (300, 384, 1024), (129, 512, 4096)])
+def test_linear_both_tilings(ctx, M, N, K, tile):
+    """Both workgroup tilings forced (the default picks by feature count); N = 384 with 256-feature workgroups has a
+    half-empty last feature tile."""
+    rng = np.random.default_rng(M + N + K + tile)
+    a, w = bf(rng.standard_normal((M, K))), bf(rng.standard_normal((N, K)) * 0.05)
+    out = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    ctx.fr_set_option(B.FR_OPT_GEMM_TILE, tile)
+    try:
+        ctx.fr_linear(H.dev(a, "bf16"), H.dev(w, "bf16"), M, N, K, None, out)
+        torch.cuda.synchronize()
+    finally:
+        ctx.fr_set_option(B.FR_OPT_GEMM_TILE, 0)
+    H.assert_close(H.host(out), orc.linear(a, w), "bf16", f"linear, {tile}-feature workgroups")
+    with pytest.raises(B.FusionRAGError):
+        ctx.fr_set_option(B.FR_OPT_GEMM_TILE, 64)
+
+
 @pytest.mark.parametrize("M,F,K", [(70, 64, 128), (300, 192, 320)])
 def test_linear_swiglu(ctx, M, F, K):
     rng = np.random.default_rng(M + F)
