@@ -173,6 +173,26 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
                                  const void* k_new, const void* v_new, void* out, float* lse_out,
                                  void* stream);
 
+/* Sparse prefill attention over a shared chunk store (Sec. 4.3: the chunk caches are shared by the queries and never
+ * modified; the recomputed K/V of a query live in its own page).  Same result as fr_rope_shift into a per-query
+ * cache followed by fr_sparse_prefill_attn and fr_kv_scatter, without the per-query copy and without the scatter:
+ * prompt position j of chunk c (chunk_offsets[c] <= j < chunk_offsets[c+1]) reads store row
+ * chunk_store_row0[c] + j - chunk_offsets[c], its key moved from the position it was cached at
+ * (chunk_src_pos0[c] + j - chunk_offsets[c]) to j while the tile is loaded; positions listed in q_index read
+ * k_new / v_new (the page) instead, and the store's entries of those tokens are never read.
+ *   k_store, v_store   dev [n_store_rows, Hkv, d], read only
+ *   chunk_offsets      host [n_chunks + 1], prompt positions as in fr_rope_shift; L_ctx = last entry <= L
+ *   chunk_store_row0, chunk_src_pos0   host [n_chunks]
+ *   L                  prompt length; every position in [L_ctx, L) must be listed in q_index
+ *   q_rows, q_index, R, k_new, v_new (both required), out, lse_out: as in fr_sparse_prefill_attn
+ * Errors as fr_sparse_prefill_attn, plus FR_ERR_INVALID_ARG for chunk rows outside the store and
+ * FR_ERR_UNSUPPORTED unless the context is bf16 with head_dim 128. */
+fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
+                                        const void* k_store, const void* v_store, int64_t n_store_rows,
+                                        const int32_t* chunk_offsets, const int32_t* chunk_store_row0,
+                                        const int32_t* chunk_src_pos0, int32_t n_chunks, int64_t L, const void* k_new,
+                                        const void* v_new, void* out, float* lse_out, void* stream);
+
 /* Batch decoding attention over shared chunk caches and per-query exclusive pages (Sec. 4.3; decoding step of
  * Sec. 2.1).  The chunk store (k_shared, v_shared) is shared by all queries of the batch and is never written.
  * Query b's prompt consists of the store segments seg_*[seg_offsets[b] .. seg_offsets[b+1]): rows

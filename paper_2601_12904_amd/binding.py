@@ -27,7 +27,7 @@ FR_DECODE_KERNEL_AUTO, FR_DECODE_KERNEL_GENERIC = 0, 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 FR_ATTN_SPLIT_AUTO, FR_ATTN_SPLIT_OFF, FR_ATTN_SPLIT_ON = 0, 1, 2
 EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_topk_count", "fr_rope_shift",
-           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
+           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_shared", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
            "fr_linear_swiglu", "fr_qkv_rope")
 
 
@@ -79,6 +79,8 @@ def load() -> ctypes.CDLL:
     lib.fr_kv_deviation.restype = i32
     lib.fr_sparse_prefill_attn.argtypes = [vp, vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.fr_sparse_prefill_attn.restype = i32
+    lib.fr_sparse_prefill_attn_shared.argtypes = [vp, vp, vp, i32, vp, vp, i64, pi32, pi32, pi32, i32, i64, vp, vp, vp, vp, vp]
+    lib.fr_sparse_prefill_attn_shared.restype = i32
     lib.fr_decode_attn.argtypes = [vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, i32, vp, i64, vp, vp, i64, vp, vp, vp, vp]
     lib.fr_decode_attn.restype = i32
     lib.fr_mark_stale_rows.argtypes = [vp, vp, i64, vp, i32, i32, vp]
@@ -192,6 +194,17 @@ class Context:
         self._check(self._lib.fr_sparse_prefill_attn(self._h, _ptr(q_rows), _ptr(q_index), int(R), _ptr(k_cache),
                                                      _ptr(v_cache), int(L), _ptr(k_new), _ptr(v_new), _ptr(out),
                                                      _ptr(lse_out), _stream(stream)))
+
+    def fr_sparse_prefill_attn_shared(self, q_rows, q_index, R: int, k_store, v_store, n_store_rows: int, chunk_offsets,
+                                      chunk_store_row0, chunk_src_pos0, L: int, k_new, v_new, out, lse_out=None,
+                                      stream=None):
+        offs, _a = _i32_array(chunk_offsets)
+        row0, _b = _i32_array(chunk_store_row0)
+        src, _c = _i32_array(chunk_src_pos0)
+        self._check(self._lib.fr_sparse_prefill_attn_shared(self._h, _ptr(q_rows), _ptr(q_index), int(R), _ptr(k_store),
+                                                            _ptr(v_store), int(n_store_rows), offs, row0, src,
+                                                            len(_a) - 1, int(L), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                                            _ptr(lse_out), _stream(stream)))
 
     def fr_decode_attn(self, q, n_queries: int, k_shared, v_shared, n_shared_rows: int, seg_offsets, seg_row0, seg_len,
                        seg_delta, n_segments: int, stale_bits, stale_words: int, k_pages, v_pages, page_stride_rows: int,

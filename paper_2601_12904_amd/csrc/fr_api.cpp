@@ -131,6 +131,8 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_col = take((size_t)s.Hkv * max_tokens * 4);
     const size_t o_scores = take((size_t)max_tokens * 4);
     const size_t o_inv = take((size_t)max_tokens * 4);
+    const size_t o_srow = take((size_t)max_tokens * 4);
+    const size_t o_cid = take((size_t)max_tokens * 4);
     const size_t o_sel = take(4096);
     w.attn_flags_elems = (size_t)(max_tokens / 32 + 1) * s.Hkv;   // one per (row tile of >= 32 rows, KV head)
     const size_t o_flags = take(w.attn_flags_elems * 4);
@@ -152,6 +154,8 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.col_partial = (float*)(w.base + o_col);
     w.scores = (float*)(w.base + o_scores);
     w.inv_index = (int32_t*)(w.base + o_inv);
+    w.store_row_map = (int32_t*)(w.base + o_srow);
+    w.chunk_id_map = (int32_t*)(w.base + o_cid);
     w.select_tmp = (uint32_t*)(w.base + o_sel);
     w.attn_flags = (int32_t*)(w.base + o_flags);
     w.kv_images = (unsigned char*)(w.base + o_img);
@@ -372,9 +376,60 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
     hipError_t e;
     if (attn_mfma_supported(s))
         e = launch_attn_mfma(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, ctx->ws,
-                             ctx->attn_softmax_mode, ctx->attn_split_mode, hs);
+                             ctx->attn_softmax_mode, ctx->attn_split_mode, nullptr, hs);
     else
         e = launch_attn_simt(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, hs);
+    if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
+    return FR_OK;
+}
+
+fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
+                                        const void* k_store, const void* v_store, int64_t n_store_rows,
+                                        const int32_t* chunk_offsets, const int32_t* chunk_store_row0,
+                                        const int32_t* chunk_src_pos0, int32_t n_chunks, int64_t L, const void* k_new,
+                                        const void* v_new, void* out, float* lse_out, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    const Shape& s = ctx->shape;
+    fr_status st = check_rows(ctx, R, L);
+    if (st != FR_OK) return st;
+    SharedStoreArgs sh;
+    st = read_chunks(ctx, chunk_offsets, n_chunks, L, &sh.ct, nullptr);
+    if (st != FR_OK) return st;
+    if (n_store_rows < 0) return fail(ctx, FR_ERR_INVALID_ARG, "n_store_rows is negative");
+    if (n_chunks > 0 && (!chunk_store_row0 || !chunk_src_pos0))
+        return fail(ctx, FR_ERR_INVALID_ARG, "chunk_store_row0 / chunk_src_pos0 is NULL");
+    ChunkDeltas dl;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t len = (int64_t)sh.ct.off[c + 1] - sh.ct.off[c];
+        if (chunk_store_row0[c] < 0 || (int64_t)chunk_store_row0[c] + len > n_store_rows)
+            return fail(ctx, FR_ERR_INVALID_ARG, "chunk %d: store rows [%d, %lld) outside the store of %lld rows", c,
+                        chunk_store_row0[c], (long long)chunk_store_row0[c] + len, (long long)n_store_rows);
+        const int64_t delta = (int64_t)sh.ct.off[c] - (int64_t)chunk_src_pos0[c];
+        if (delta > INT32_MAX || delta < INT32_MIN) return fail(ctx, FR_ERR_INVALID_ARG, "position delta overflows");
+        dl.delta[c] = (int32_t)delta;
+    }
+    if (R == 0) return FR_OK;
+    if (!q_rows || !q_index || !out || !k_new || !v_new)
+        return fail(ctx, FR_ERR_INVALID_ARG, "q_rows / q_index / k_new / v_new / out is NULL");
+    if (sh.ct.off[sh.ct.n] > 0 && (!k_store || !v_store)) return fail(ctx, FR_ERR_INVALID_ARG, "k_store / v_store is NULL");
+    if (!aligned16(q_rows) || !aligned16(k_store) || !aligned16(v_store) || !aligned16(out) || !aligned16(k_new) ||
+        !aligned16(v_new))
+        return fail(ctx, FR_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(q_index) & 3u) || (reinterpret_cast<uintptr_t>(lse_out) & 3u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "q_index / lse_out must be 4-byte aligned");
+    if (!attn_mfma_supported(s))
+        return fail(ctx, FR_ERR_UNSUPPORTED, "the shared-store attention needs bf16, head_dim 128 and a group size of 1, 2, 4 or 8");
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    hipError_t e = launch_inv_index(q_index, R, L, ctx->ws.inv_index, hs);
+    if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
+    e = launch_rope_table(s, dl, n_chunks, ctx->ws.rope_table, hs);
+    if (e != hipSuccess) return hip_fail(ctx, "rope table launch", e);
+    sh.store_row0 = chunk_store_row0;
+    sh.table = ctx->ws.rope_table;
+    e = launch_attn_mfma(s, q_rows, q_index, R, k_store, v_store, L, k_new, v_new, ctx->ws.inv_index, out, lse_out, ctx->ws,
+                         ctx->attn_softmax_mode, ctx->attn_split_mode, &sh, hs);
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
     return FR_OK;
 }

@@ -38,6 +38,8 @@ struct Workspace {
     float* col_partial = nullptr;   // [Hkv][max_ctx] per-KV-head column sums
     float* scores = nullptr;        // [max_tokens]
     int32_t* inv_index = nullptr;   // [max_tokens] position -> row of k_new / -1
+    int32_t* store_row_map = nullptr;   // [max_tokens] prompt position -> row of the shared chunk store / -1
+    int32_t* chunk_id_map = nullptr;    // [max_tokens] prompt position -> chunk
     uint32_t* select_tmp = nullptr; // small counters for the selection kernels
     int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
     size_t attn_flags_elems = 0;
@@ -106,6 +108,15 @@ size_t decode_rot_table_bytes(const Shape& s);
 hipError_t launch_decode_attn(const Shape& s, const DecodeArgs& a, float* partials, float2* rot_table, hipStream_t st);
 hipError_t launch_mark_stale(uint32_t* bits, int64_t n_words, const int32_t* rows, int n_rows, int clear, hipStream_t st);
 
+// When given to launch_attn_mfma, k_cache / v_cache are a chunk store shared between queries: prompt position
+// j in [ct.off[c], ct.off[c+1]) reads store row store_row0[c] + j - ct.off[c], its key rotated by the chunk's
+// (cos, sin) row of `table` (device, [chunks][d/2]); store_row0 is a host array.
+struct SharedStoreArgs {
+    ChunkTable ct;
+    const int32_t* store_row0;
+    const float2* table;
+};
+
 hipError_t launch_inv_index(const int32_t* q_index, int R, int64_t L, int32_t* inv, hipStream_t st);
 hipError_t launch_attn_simt(const Shape& s, const void* q_rows, const int32_t* q_index, int R,
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
@@ -114,7 +125,8 @@ bool attn_mfma_supported(const Shape& s);
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R,
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
                             const void* v_new, const int32_t* inv, void* out, float* lse,
-                            const Workspace& ws, int softmax_mode, int split_mode, hipStream_t st);
+                            const Workspace& ws, int softmax_mode, int split_mode, const struct SharedStoreArgs* shared,
+                            hipStream_t st);
 // The attention launch splits the key range in two on its own up to ATTN_SPLIT_AUTO_ITEMS (row tile, KV head)
 // items (about 1.5 x the 256 CUs: beyond that the items alone keep the chip busy and the partial results' traffic
 // costs more than the better balance gains), and on request (FR_ATTN_SPLIT_ON) up to ATTN_SPLIT_MAX_ITEMS, which

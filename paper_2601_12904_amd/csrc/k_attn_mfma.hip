@@ -33,6 +33,8 @@
 // copies: no lookups, no pointer selects, no permutes, no address arithmetic, no staging registers.
 #include "fr_internal.hpp"
 
+#include <algorithm>
+
 #ifndef FR_SCHED_HINTS
 #define FR_SCHED_HINTS 1
 #endif
@@ -121,6 +123,39 @@ struct Geometry {
 };
 
 // ---- packing pre-pass: grid (key tiles, KV heads) ---------------------------------------------------------
+// Second half of both packing kernels: the thread's 4 key vectors and 4 value vectors (st_vec = 16-byte vector
+// within the 256-byte head row; K: keys st_key + 16 i, V: keys 4 st_key + i) go into the LDS image, which is then
+// written out as it is.
+__device__ __forceinline__ void write_image(const u32x4 (&kreg)[4], const u32x4 (&vreg)[4], unsigned char* img,
+                                            unsigned char* __restrict__ dst) {
+    const int tid = threadIdx.x;
+    const int st_vec = tid & 15, st_key = tid >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&img[(st_key + 16 * i) * K_ROW + 16 * st_vec]) = kreg[i];
+    {   // pads: K row tails, K image tail, V^T row tails (never read by the matrix operands; kept zero)
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        if (tid < KT) *reinterpret_cast<u32x4*>(&img[tid * K_ROW + 256]) = z;
+        if (tid < (K_IMG_BYTES - KT * K_ROW) / 16) *reinterpret_cast<u32x4*>(&img[KT * K_ROW + 16 * tid]) = z;
+        if (tid < D) *reinterpret_cast<u32x4*>(&img[K_IMG_BYTES + tid * V_ROW + 128]) = z;
+    }
+    const int slot = key_slot(4 * st_key);   // the 4 keys of this lane occupy slots slot .. slot + 3
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {   // dims 8 st_vec + 2c and + 2c + 1: gather the 4 keys of each
+        u32x2 lo, hi;
+        lo[0] = perm_lo(vreg[0][c], vreg[1][c]);
+        lo[1] = perm_lo(vreg[2][c], vreg[3][c]);
+        hi[0] = perm_hi(vreg[0][c], vreg[1][c]);
+        hi[1] = perm_hi(vreg[2][c], vreg[3][c]);
+        const int d0 = 8 * st_vec + 2 * c, d1 = d0 + 1;
+        *reinterpret_cast<u32x2*>(&img[K_IMG_BYTES + d0 * V_ROW + 2 * slot]) = lo;
+        *reinterpret_cast<u32x2*>(&img[K_IMG_BYTES + d1 * V_ROW + 2 * slot]) = hi;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < IMG_BYTES / 4096; ++i)
+        *reinterpret_cast<u32x4*>(dst + i * 4096 + tid * 16) = *reinterpret_cast<const u32x4*>(&img[i * 4096 + tid * 16]);
+}
+
 __global__ __launch_bounds__(256) void pack_kv_images_kernel(const __bf16* __restrict__ k_cache,
                                                              const __bf16* __restrict__ v_cache, int L,
                                                              const __bf16* __restrict__ k_new,
@@ -146,31 +181,115 @@ __global__ __launch_bounds__(256) void pack_kv_images_kernel(const __bf16* __res
         kreg[i] = *reinterpret_cast<const u32x4*>(pk + 8 * st_vec);
         vreg[i] = *reinterpret_cast<const u32x4*>(pv + 8 * st_vec);
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&img[(st_key + 16 * i) * K_ROW + 16 * st_vec]) = kreg[i];
-    {   // pads: K row tails, K image tail, V^T row tails (never read by the matrix operands; kept zero)
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        if (tid < KT) *reinterpret_cast<u32x4*>(&img[tid * K_ROW + 256]) = z;
-        if (tid < (K_IMG_BYTES - KT * K_ROW) / 16) *reinterpret_cast<u32x4*>(&img[KT * K_ROW + 16 * tid]) = z;
-        if (tid < D) *reinterpret_cast<u32x4*>(&img[K_IMG_BYTES + tid * V_ROW + 128]) = z;
+    write_image(kreg, vreg, img, images + ((size_t)g * n_img_tiles + kt) * IMG_BYTES);
+}
+
+// The same images built from a chunk store that is shared between queries and never written (Sec. 4.3): position
+// j < L_ctx of the prompt belongs to chunk c = (the chunk whose offsets contain j) and reads store row
+// row0[c] + j - off[c]; its key is moved to the prompt position on the way (Appendix A: one more rotation by
+// Delta_c, from the (cos, sin) rows of `table`, same arithmetic as the stand-alone position shift).  Positions
+// listed in the Q index (inv[j] >= 0: recomputed context tokens and all question tokens) read the query's own
+// fresh rows instead, so the store's stale entries of those tokens are never read and no per-query copy of the
+// cache exists.  Positions >= L_ctx that are not in the Q index have no data: they read as zero.
+struct ChunkRows {
+    int32_t row0[FR_MAX_CHUNKS];
+};
+
+// Prompt position -> (store row, chunk) for the packing kernel, so that it needs no search and no dependent loads:
+// grid (position tiles of the longest chunk, chunks + 1); the extra y index covers the positions behind the context
+// (no store row: -1).
+__global__ __launch_bounds__(256) void prompt_map_kernel(ChunkTable ct, ChunkRows rows, int L,
+                                                         int32_t* __restrict__ store_row, int32_t* __restrict__ chunk_id) {
+    const int c = blockIdx.y;
+    const int begin = (c < ct.n) ? ct.off[c] : ct.off[ct.n];
+    const int end = (c < ct.n) ? ct.off[c + 1] : L;
+    for (int j = begin + blockIdx.x * 256 + threadIdx.x; j < end; j += gridDim.x * 256) {
+        store_row[j] = (c < ct.n) ? rows.row0[c] + (j - begin) : -1;
+        chunk_id[j] = (c < ct.n) ? c : 0;
     }
-    const int slot = key_slot(4 * st_key);   // the 4 keys of this lane occupy slots slot .. slot + 3
+}
+
+template <int LAYOUT>
+__device__ __forceinline__ u32x4 rotate_key_vector(u32x4 own, u32x4 partner, const float2* __restrict__ trow, int st_vec) {
+    // own = elements 8 st_vec .. + 7 of the head row.  Interleaved pairs: (2p, 2p + 1) inside the vector.
+    // Half-split pairs: (p, p + 64): `partner` is the vector 64 elements away.
+    u32x4 outv;
+    if (LAYOUT == FR_ROPE_INTERLEAVED) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {   // dims 8 st_vec + 2c and + 2c + 1: gather the 4 keys of each
-        u32x2 lo, hi;
-        lo[0] = perm_lo(vreg[0][c], vreg[1][c]);
-        lo[1] = perm_lo(vreg[2][c], vreg[3][c]);
-        hi[0] = perm_hi(vreg[0][c], vreg[1][c]);
-        hi[1] = perm_hi(vreg[2][c], vreg[3][c]);
-        const int d0 = 8 * st_vec + 2 * c, d1 = d0 + 1;
-        *reinterpret_cast<u32x2*>(&img[K_IMG_BYTES + d0 * V_ROW + 2 * slot]) = lo;
-        *reinterpret_cast<u32x2*>(&img[K_IMG_BYTES + d1 * V_ROW + 2 * slot]) = hi;
+        for (int e = 0; e < 4; ++e) {
+            const float2 t = trow[4 * st_vec + e];
+            const float a = __uint_as_float(own[e] << 16), b = __uint_as_float(own[e] & 0xFFFF0000u);
+            const __bf16 ya = (__bf16)(a * t.x - b * t.y), yb = (__bf16)(b * t.x + a * t.y);
+            outv[e] = (uint32_t)__builtin_bit_cast(unsigned short, ya) | ((uint32_t)__builtin_bit_cast(unsigned short, yb) << 16);
+        }
+    } else {
+        const bool low = st_vec < 8;   // this vector holds the first elements of its pairs
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            unsigned short r2[2];
+#pragma unroll
+            for (int hlf = 0; hlf < 2; ++hlf) {
+                const float2 t = trow[(8 * st_vec + 2 * e + hlf) & 63];
+                const float mine = hlf ? __uint_as_float(own[e] & 0xFFFF0000u) : __uint_as_float(own[e] << 16);
+                const float other = hlf ? __uint_as_float(partner[e] & 0xFFFF0000u) : __uint_as_float(partner[e] << 16);
+                const float a = low ? mine : other, b = low ? other : mine;
+                const __bf16 y = low ? (__bf16)(a * t.x - b * t.y) : (__bf16)(b * t.x + a * t.y);
+                r2[hlf] = __builtin_bit_cast(unsigned short, y);
+            }
+            outv[e] = (uint32_t)r2[0] | ((uint32_t)r2[1] << 16);
+        }
     }
-    __syncthreads();
-    unsigned char* dst = images + ((size_t)g * n_img_tiles + kt) * IMG_BYTES;
+    return outv;
+}
+
+template <int LAYOUT>
+__global__ __launch_bounds__(256) void pack_kv_images_shared_kernel(const __bf16* __restrict__ k_store,
+                                                                    const __bf16* __restrict__ v_store,
+                                                                    const int32_t* __restrict__ store_row,
+                                                                    const int32_t* __restrict__ chunk_id,
+                                                                    const float2* __restrict__ table,
+                                                                    int L, const __bf16* __restrict__ k_new,
+                                                                    const __bf16* __restrict__ v_new,
+                                                                    const int32_t* __restrict__ inv, int Hkv,
+                                                                    int n_img_tiles, unsigned char* __restrict__ images) {
+    __shared__ __attribute__((aligned(16))) unsigned char img[IMG_BYTES];
+    const int tid = threadIdx.x, kt = blockIdx.x, g = blockIdx.y;
+    const int st_vec = tid & 15, st_key = tid >> 4;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    int jk[4], jv[4], rk[4], rv[4], sk[4], sv[4], ck[4];
 #pragma unroll
-    for (int i = 0; i < IMG_BYTES / 4096; ++i)
-        *reinterpret_cast<u32x4*>(dst + i * 4096 + tid * 16) = *reinterpret_cast<const u32x4*>(&img[i * 4096 + tid * 16]);
+    for (int i = 0; i < 4; ++i) {   // the maps first, all at once: no load below depends on more than one of them
+        jk[i] = min(kt * KT + st_key + 16 * i, L - 1);
+        jv[i] = min(kt * KT + 4 * st_key + i, L - 1);
+        rk[i] = inv[jk[i]];
+        rv[i] = inv[jv[i]];
+        sk[i] = store_row[jk[i]];
+        sv[i] = store_row[jv[i]];
+        ck[i] = chunk_id[jk[i]];
+    }
+    u32x4 kreg[4], vreg[4], kpart[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {   // positions that are neither fresh nor in a chunk read row 0 of the page and become zero
+        const __bf16* pk = (rk[i] >= 0 || sk[i] < 0) ? k_new + ((size_t)max(rk[i], 0) * Hkv + g) * D
+                                                      : k_store + ((size_t)sk[i] * Hkv + g) * D;
+        const __bf16* pv = (rv[i] >= 0 || sv[i] < 0) ? v_new + ((size_t)max(rv[i], 0) * Hkv + g) * D
+                                                      : v_store + ((size_t)sv[i] * Hkv + g) * D;
+        kreg[i] = *reinterpret_cast<const u32x4*>(pk + 8 * st_vec);
+        if (LAYOUT != FR_ROPE_INTERLEAVED) kpart[i] = *reinterpret_cast<const u32x4*>(pk + 8 * (st_vec ^ 8));
+        vreg[i] = *reinterpret_cast<const u32x4*>(pv + 8 * st_vec);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (rk[i] < 0) {
+            if (sk[i] >= 0)
+                kreg[i] = rotate_key_vector<LAYOUT>(kreg[i], LAYOUT != FR_ROPE_INTERLEAVED ? kpart[i] : kreg[i],
+                                                    table + (size_t)ck[i] * (D / 2), st_vec);
+            else
+                kreg[i] = zero;
+        }
+        if (rv[i] < 0 && sv[i] < 0) vreg[i] = zero;
+    }
+    write_image(kreg, vreg, img, images + ((size_t)g * n_img_tiles + kt) * IMG_BYTES);
 }
 
 // ---- staging in the fast kernel: image -> LDS directly (global_load_lds_dwordx4: lane i of a wave deposits its
@@ -668,7 +787,8 @@ __global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __r
 template <int G>
 hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                   const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
-                  float* lse, const Workspace& ws, int mode, int split_mode, hipStream_t st) {
+                  float* lse, const Workspace& ws, int mode, int split_mode, const SharedStoreArgs* shared,
+                  hipStream_t st) {
     const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
     constexpr int TR = Geometry<G>::TR;
     const int n_row_tiles = (R + TR - 1) / TR;
@@ -694,9 +814,28 @@ hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, in
     dim3 grid(n_row_tiles * s.Hkv), block(256);
     if ((size_t)grid.x > ws.attn_flags_elems) return hipErrorInvalidValue;
     if ((size_t)n_img_tiles * s.Hkv * IMG_BYTES > ws.kv_images_bytes) return hipErrorInvalidValue;
-    pack_kv_images_kernel<<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
-        (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
-        k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, ws.kv_images);
+    if (shared == nullptr) {
+        pack_kv_images_kernel<<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
+            (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
+            k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, ws.kv_images);
+    } else {   // k_cache / v_cache are the shared chunk store
+        ChunkRows rows;
+        int max_len = (int)L - shared->ct.off[shared->ct.n];
+        for (int c = 0; c < shared->ct.n; ++c) {
+            rows.row0[c] = shared->store_row0[c];
+            max_len = std::max(max_len, shared->ct.off[c + 1] - shared->ct.off[c]);
+        }
+        prompt_map_kernel<<<dim3(std::max(1, (max_len + 255) / 256), shared->ct.n + 1), block, 0, st>>>(
+            shared->ct, rows, (int)L, ws.store_row_map, ws.chunk_id_map);
+        if (s.rope_layout == FR_ROPE_INTERLEAVED)
+            pack_kv_images_shared_kernel<FR_ROPE_INTERLEAVED><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
+                (const __bf16*)k_cache, (const __bf16*)v_cache, ws.store_row_map, ws.chunk_id_map, shared->table, (int)L,
+                (const __bf16*)k_new, (const __bf16*)v_new, inv, s.Hkv, n_img_tiles, ws.kv_images);
+        else
+            pack_kv_images_shared_kernel<FR_ROPE_HALF><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
+                (const __bf16*)k_cache, (const __bf16*)v_cache, ws.store_row_map, ws.chunk_id_map, shared->table, (int)L,
+                (const __bf16*)k_new, (const __bf16*)v_new, inv, s.Hkv, n_img_tiles, ws.kv_images);
+    }
     const int32_t* flags = ws.attn_flags;
     // Few (row tile, KV head) items: the chip would idle behind the longest ones, so each is walked by two
     // workgroups.  Not worth the partial results' traffic once the items alone fill the CUs, nor for short prompts.
@@ -739,13 +878,14 @@ bool attn_mfma_supported(const Shape& s) {
 
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                             const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv,
-                            void* out, float* lse, const Workspace& ws, int mode, int split_mode, hipStream_t st) {
+                            void* out, float* lse, const Workspace& ws, int mode, int split_mode,
+                            const SharedStoreArgs* shared, hipStream_t st) {
     if (R == 0) return hipSuccess;
     switch (s.G) {
-        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, st);
-        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, st);
-        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, st);
-        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, st);
+        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, st);
+        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, st);
+        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, st);
+        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, st);
     }
 }
 

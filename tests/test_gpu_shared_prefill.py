@@ -1,0 +1,83 @@
+"""GPU parity of the sparse prefill attention over a shared chunk store (Sec. 4.3): against the oracle's
+position shift + effective cache + sparse attention, and against the library's own three-call path."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fusionrag_oracle as orc
+from paper_2601_12904_amd import binding as B
+from paper_2601_12904_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def scattered_store(w, rng, pad=7):
+    """The workload's cached chunks placed in a store in another order, with unrelated rows between them."""
+    order = rng.permutation(w.n_chunks)
+    Hkv, d = w.shape.n_kv_heads, w.shape.head_dim
+    parts_k, parts_v, row0, at = [], [], np.zeros(w.n_chunks, dtype=np.int32), 0
+    for c in order:
+        s, e = int(w.chunk_offsets[c]), int(w.chunk_offsets[c + 1])
+        junk = lambda: synth.round_to_storage((50.0 * rng.standard_normal((pad, Hkv, d))).astype(np.float32), w.shape.dtype)
+        parts_k += [junk(), w.k_cached[s:e]]
+        parts_v += [junk(), w.v_cached[s:e]]
+        row0[c] = at + pad
+        at += pad + (e - s)
+    return np.concatenate(parts_k), np.concatenate(parts_v), row0
+
+
+@pytest.mark.parametrize("layout", [B.FR_ROPE_INTERLEAVED, B.FR_ROPE_HALF])
+@pytest.mark.parametrize("ratio", [0.0, 0.15, 1.0])
+def test_shared_store_prefill_matches_oracle_and_three_call_path(ratio, layout):
+    w = synth.config_small_bf16(seed=7, ratio=ratio, chunk_lens=(200, 0, 333, 91, 256))
+    dt, tdt = "bf16", torch.bfloat16
+    Hq, Hkv, d = w.shape.n_q_heads, w.shape.n_kv_heads, w.shape.head_dim
+    rng = np.random.default_rng(3)
+    lay = "half" if layout == B.FR_ROPE_HALF else "interleaved"
+    src_pos0 = rng.integers(0, 5000, size=w.n_chunks).astype(np.int32)
+    k_store, v_store, row0 = scattered_store(w, rng)
+    k = orc.topk_count(w.L_ctx, ratio)
+    qi = np.concatenate([np.sort(rng.choice(w.L_ctx, size=k, replace=False)), w.L_ctx + np.arange(w.nq)]).astype(np.int64)
+    R = len(qi)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq, rope_layout=layout)
+    q_rows, k_new, v_new = H.dev(w.q_full[qi], dt), H.dev(w.k_full[qi], dt), H.dev(w.v_full[qi], dt)
+    qi_d = torch.from_numpy(qi.astype(np.int32)).cuda()
+    out = torch.zeros((R, Hq, d), dtype=tdt, device="cuda")
+    lse = torch.zeros((R, Hq), dtype=torch.float32, device="cuda")
+    ctx.fr_sparse_prefill_attn_shared(q_rows, qi_d, R, H.dev(k_store, dt), H.dev(v_store, dt), len(k_store), w.chunk_offsets,
+                                      row0, src_pos0, w.L, k_new, v_new, out, lse)
+    torch.cuda.synchronize()
+    # oracle: shift the chunk keys to their prompt positions, then the sparse prefill over the effective cache
+    k_ctx = synth.round_to_storage(orc.rope_shift(w.k_cached, w.chunk_offsets, src_pos0, None, w.shape.rope_base, lay), dt)
+    pad = np.zeros((w.nq, Hkv, d))
+    want, want_lse = orc.sparse_prefill_attn(w.q_full[qi], qi, np.concatenate([k_ctx, pad]),
+                                             np.concatenate([w.v_cached, pad]), w.k_full[qi], w.v_full[qi])
+    H.assert_close(H.host(out), want, dt, "shared-store attention")
+    assert np.max(np.abs(lse.cpu().numpy() - want_lse)) <= 2e-3
+    # the library's own path: shift into a per-query cache, then attend (the scatter does not change the output)
+    k_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_cache[: w.L_ctx] = H.dev(w.v_cached, dt)
+    ctx.fr_rope_shift(H.dev(w.k_cached, dt), k_cache, w.chunk_offsets, src_pos0)
+    out2 = torch.zeros_like(out)
+    ctx.fr_sparse_prefill_attn(q_rows, qi_d, R, k_cache, v_cache, w.L, k_new, v_new, out2)
+    torch.cuda.synchronize()
+    assert H.max_rel_err(H.host(out), H.host(out2)) <= 2.0 ** -7     # same inputs up to the key rotation's last bit
+    ctx.close()
+
+
+def test_shared_store_prefill_argument_errors():
+    w = synth.config_small_bf16(seed=1)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    P = 4096
+    with pytest.raises(B.FusionRAGError):      # a chunk reaches past the end of the store
+        ctx.fr_sparse_prefill_attn_shared(P, P, 5, P, P, 10, [0, 8, 16], [0, 4], [0, 0], 20, P, P, P)
+    with pytest.raises(B.FusionRAGError):      # the page is required
+        ctx.fr_sparse_prefill_attn_shared(P, P, 5, P, P, 100, [0, 8, 16], [0, 8], [0, 0], 20, None, None, P)
+    ctx.close()
+    c32 = H.make_ctx(synth.TINY_F32, 256, 4, 8)
+    with pytest.raises(B.FusionRAGError) as ei:
+        c32.fr_sparse_prefill_attn_shared(P, P, 5, P, P, 100, [0, 8, 16], [0, 8], [0, 0], 20, P, P, P)
+    assert ei.value.status == B.FR_ERR_UNSUPPORTED
+    c32.close()
