@@ -585,7 +585,23 @@ def main():
     torch.cuda.synchronize()
     dev_all_ms = a.elapsed_time(b) / reps
     dev_all_gbps = (nl * bytes_rope + 4 * nl * w.L_ctx) / (dev_all_ms * 1e-3) / 1e9
-    del big_src, big_dst, dev_all
+    # the softmax-free scores (FR_NORM_RAW) are the streaming special case of the scoring step: K is read once
+    ctx_big = H.make_ctx(w.shape, nl * w.L_ctx + w.nq, 1, w.nq)
+    raw_scores = torch.empty((nl * w.L_ctx,), dtype=torch.float32, device="cuda")
+    raw_qi = torch.empty((w.nq,), dtype=torch.int32, device="cuda")
+    big_k = big_src.reshape(nl * w.L_ctx, Hkv, d)
+    raw_call = lambda: ctx_big.fr_score_select(q_question, w.nq, big_k, [0, nl * w.L_ctx], 0, B.FR_NORM_RAW, raw_scores, raw_qi)
+    for _ in range(3):
+        raw_call()
+    a.record()
+    for _ in range(reps):
+        raw_call()
+    b.record()
+    torch.cuda.synchronize()
+    raw_all_ms = a.elapsed_time(b) / reps
+    raw_all_gbps = (nl * w.L_ctx * kv_row + 4 * nl * w.L_ctx + w.nq * Hq * d * e) / (raw_all_ms * 1e-3) / 1e9
+    ctx_big.close()
+    del big_src, big_dst, dev_all, raw_scores, big_k
 
     if args.calibrate_copy:   # 2^28 fp32 = 1 GiB read + 1 GiB written by one elementwise copy kernel
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -609,6 +625,8 @@ def main():
         "hbm_gbps": {n: round(v, 1) for n, v in hbm.items()},
         "rope_shift_all_layers": {"layers": nl, "ms": round(rope_all_ms, 4), "gbps": round(rope_all_gbps, 1),
                                   "frac_of_hbm_peak": round(rope_all_gbps / PEAK_HBM_GBPS, 4)},
+        "score_raw_all_layers": {"layers": nl, "ms": round(raw_all_ms, 4), "gbps": round(raw_all_gbps, 1),
+                                 "frac_of_hbm_peak": round(raw_all_gbps / PEAK_HBM_GBPS, 4)},
         "kv_deviation_all_layers": {"layers": nl, "ms": round(dev_all_ms, 4), "gbps": round(dev_all_gbps, 1),
                                     "frac_of_hbm_peak": round(dev_all_gbps / PEAK_HBM_GBPS, 4)},
         "roofline": {"kernel": "sparse_prefill_attn", "bound": "mfma", "achieved": round(attn_tflops, 2),

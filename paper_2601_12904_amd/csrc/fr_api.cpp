@@ -134,6 +134,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_srow = take((size_t)max_tokens * 4);
     const size_t o_cid = take((size_t)max_tokens * 4);
     const size_t o_sel = take(4096);
+    const size_t o_qsum = take(score_raw_workspace_bytes(s));
     w.attn_flags_elems = (size_t)(max_tokens / 32 + 1) * s.Hkv;   // one per (row tile of >= 32 rows, KV head)
     const size_t o_flags = take(w.attn_flags_elems * 4);
     w.kv_images_bytes = (s.dtype == FR_BF16 && s.d == 128) ? (size_t)((max_tokens + 63) / 64) * s.Hkv * 36864 : 0;
@@ -157,6 +158,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.store_row_map = (int32_t*)(w.base + o_srow);
     w.chunk_id_map = (int32_t*)(w.base + o_cid);
     w.select_tmp = (uint32_t*)(w.base + o_sel);
+    w.qsum = (float*)(w.base + o_qsum);
     w.attn_flags = (int32_t*)(w.base + o_flags);
     w.kv_images = (unsigned char*)(w.base + o_img);
     w.attn_partials = (float*)(w.base + o_part);
@@ -328,6 +330,8 @@ fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const
         hipError_t e;
         if (score_mfma_supported(s) && nq > 0 && norm != FR_NORM_RAW)
             e = launch_score_mfma(s, q_question, nq, k_ctx, ct, norm, ctx->ws, scores, hs);
+        else if (norm == FR_NORM_RAW && score_raw_supported(s))
+            e = launch_score_raw(s, q_question, nq, k_ctx, L_ctx, ctx->ws.qsum, scores, hs);
         else
             e = launch_score_simt(s, q_question, nq, k_ctx, ct, norm, ctx->ws, scores, hs);
         if (e != hipSuccess) return hip_fail(ctx, "score launch", e);

@@ -40,6 +40,7 @@ struct Workspace {
     int32_t* inv_index = nullptr;   // [max_tokens] position -> row of k_new / -1
     int32_t* store_row_map = nullptr;   // [max_tokens] prompt position -> row of the shared chunk store / -1
     int32_t* chunk_id_map = nullptr;    // [max_tokens] prompt position -> chunk
+    float* qsum = nullptr;              // [Hkv][d] question queries summed per KV head (raw scores), then partial sums
     uint32_t* select_tmp = nullptr; // small counters for the selection kernels
     int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
     size_t attn_flags_elems = 0;
@@ -81,6 +82,10 @@ hipError_t launch_kv_scatter(const Shape& s, const void* k_new, const void* v_ne
 
 hipError_t launch_score_simt(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct,
                              int norm, const Workspace& ws, float* scores, hipStream_t st);
+bool score_raw_supported(const Shape& s);
+size_t score_raw_workspace_bytes(const Shape& s);
+hipError_t launch_score_raw(const Shape& s, const void* q, int nq, const void* k_ctx, int64_t L_ctx, float* qsum,
+                            float* scores, hipStream_t st);
 bool score_mfma_supported(const Shape& s);
 hipError_t launch_score_mfma(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct,
                              int norm, const Workspace& ws, float* scores, hipStream_t st);
