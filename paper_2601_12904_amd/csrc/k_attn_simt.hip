@@ -6,19 +6,21 @@
 
 namespace fr {
 
-// inv[pos] = row of k_new/v_new holding the recomputed entry of position pos, or -1.
-__global__ void inv_fill_kernel(int32_t* __restrict__ inv, int64_t L) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < L) inv[i] = -1;
-}
-__global__ void inv_set_kernel(const int32_t* __restrict__ q_index, int R, int32_t* __restrict__ inv) {
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r < R) inv[q_index[r]] = r;
+// inv[j] = row r of k_new/v_new that holds the recomputed entry of position j (q_index[r] == j), else -1.  The Q index is strictly ascending, so every position finds its own
+// answer by a binary search (one launch, no fill-then-set ordering).
+__global__ void inv_index_kernel(const int32_t* __restrict__ q_index, int R, int64_t L, int32_t* __restrict__ inv) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= L) return;
+    int lo = 0, hi = R;   // first r with q_index[r] >= j
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (q_index[mid] < j) lo = mid + 1; else hi = mid;
+    }
+    inv[j] = (lo < R && q_index[lo] == j) ? lo : -1;
 }
 
 hipError_t launch_inv_index(const int32_t* q_index, int R, int64_t L, int32_t* inv, hipStream_t st) {
-    if (L > 0) inv_fill_kernel<<<dim3((unsigned)((L + 255) / 256)), dim3(256), 0, st>>>(inv, L);
-    if (R > 0) inv_set_kernel<<<dim3((R + 255) / 256), dim3(256), 0, st>>>(q_index, R, inv);
+    if (L > 0) inv_index_kernel<<<dim3((unsigned)((L + 255) / 256)), dim3(256), 0, st>>>(q_index, R, L, inv);
     return hipGetLastError();
 }
 
