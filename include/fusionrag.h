@@ -97,12 +97,21 @@ int64_t fr_workspace_bytes(const fr_ctx* ctx);
  * FR_OPT_DECODE_KERNEL: AUTO (default) lets fr_decode_attn form the logits on the matrix cores where it can (bf16,
  * head_dim 128); GENERIC forces the all-vector-ALU kernel that every other shape uses (so that tests reach both).
  * FR_OPT_GEMM_TILE: output features per workgroup of the projection kernels, 0 (default: 256 where the feature count
- * is a multiple of 256, else 128), 128 or 256; process-wide, for tests and tuning. */
-typedef enum { FR_OPT_ATTN_SOFTMAX = 1, FR_OPT_ATTN_SPLIT = 2, FR_OPT_DECODE_KERNEL = 3, FR_OPT_GEMM_TILE = 4 } fr_option;
+ * is a multiple of 256, else 128), 128 or 256; process-wide, for tests and tuning.
+ * FR_OPT_ATTN_KERNEL_TIMER: value n in [0, 256]: the tiled attention launch records an event pair on its stream around
+ * its dominant kernel (the key-tile loop) and keeps the last n pairs; 0 (default) switches the timer off.  Read
+ * with fr_attn_kernel_times.  For benchmarks: the events see one kernel, not the whole call. */
+typedef enum { FR_OPT_ATTN_SOFTMAX = 1, FR_OPT_ATTN_SPLIT = 2, FR_OPT_DECODE_KERNEL = 3, FR_OPT_GEMM_TILE = 4,
+               FR_OPT_ATTN_KERNEL_TIMER = 5 } fr_option;
 typedef enum { FR_DECODE_KERNEL_AUTO = 0, FR_DECODE_KERNEL_GENERIC = 1 } fr_decode_kernel;
 typedef enum { FR_ATTN_SOFTMAX_AUTO = 0, FR_ATTN_SOFTMAX_RUNNING_MAX = 1 } fr_attn_softmax;
 typedef enum { FR_ATTN_SPLIT_AUTO = 0, FR_ATTN_SPLIT_OFF = 1, FR_ATTN_SPLIT_ON = 2 } fr_attn_split;
 fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value);
+
+/* Durations (ms) of the dominant attention kernel of the most recent launches recorded under
+ * FR_OPT_ATTN_KERNEL_TIMER, oldest first: at most `capacity` values into the host array ms_out, their number into
+ * *n_out.  Waits for the recorded launches to finish. */
+fr_status fr_attn_kernel_times(fr_ctx* ctx, float* ms_out, int32_t capacity, int32_t* n_out);
 
 /* Number of context tokens a recompute ratio selects: floor(ratio * L_ctx + 0.5) clamped to
  * [0, L_ctx].  The ratio counts context tokens; question tokens are always computed (Sec. 4.3).

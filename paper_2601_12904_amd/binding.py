@@ -23,10 +23,11 @@ FR_OPT_ATTN_SOFTMAX = 1
 FR_OPT_ATTN_SPLIT = 2
 FR_OPT_DECODE_KERNEL = 3
 FR_OPT_GEMM_TILE = 4
+FR_OPT_ATTN_KERNEL_TIMER = 5
 FR_DECODE_KERNEL_AUTO, FR_DECODE_KERNEL_GENERIC = 0, 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 FR_ATTN_SPLIT_AUTO, FR_ATTN_SPLIT_OFF, FR_ATTN_SPLIT_ON = 0, 1, 2
-EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_topk_count", "fr_rope_shift",
+EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_attn_kernel_times", "fr_topk_count", "fr_rope_shift",
            "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_shared", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
            "fr_linear_swiglu", "fr_qkv_rope")
 
@@ -67,6 +68,8 @@ def load() -> ctypes.CDLL:
     lib.fr_workspace_bytes.restype = i64
     lib.fr_set_option.argtypes = [vp, i32, i64]
     lib.fr_set_option.restype = i32
+    lib.fr_attn_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
+    lib.fr_attn_kernel_times.restype = i32
     lib.fr_topk_count.argtypes = [i64, f64]
     lib.fr_topk_count.restype = i64
     lib.fr_rope_shift.argtypes = [vp, vp, vp, pi32, pi32, pi32, i32, i32, i32, i64, i64, vp]
@@ -161,6 +164,12 @@ class Context:
 
     def workspace_bytes(self) -> int:
         return int(self._lib.fr_workspace_bytes(self._h))
+
+    def fr_attn_kernel_times(self, capacity: int = 256):
+        buf = (ctypes.c_float * capacity)()
+        n = ctypes.c_int32(0)
+        self._check(self._lib.fr_attn_kernel_times(self._h, buf, int(capacity), ctypes.byref(n)))
+        return [float(buf[i]) for i in range(n.value)]
 
     def fr_set_option(self, option: int, value: int):
         self._check(self._lib.fr_set_option(self._h, int(option), int(value)))

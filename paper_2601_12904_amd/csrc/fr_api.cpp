@@ -172,6 +172,10 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
 
 void fr_destroy(fr_ctx* ctx) {
     if (!ctx) return;
+    for (int i = 0; i < KernelTimer::MAX_SLOTS; ++i) {
+        if (ctx->attn_timer.start[i]) (void)hipEventDestroy(ctx->attn_timer.start[i]);
+        if (ctx->attn_timer.stop[i]) (void)hipEventDestroy(ctx->attn_timer.stop[i]);
+    }
     if (ctx->ws.base) (void)hipFree(ctx->ws.base);
     delete ctx;
 }
@@ -194,6 +198,21 @@ fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value) {
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_DECODE_KERNEL: unknown value %lld", (long long)value);
             ctx->decode_generic = (value == FR_DECODE_KERNEL_GENERIC) ? 1 : 0;
             return FR_OK;
+        case FR_OPT_ATTN_KERNEL_TIMER: {
+            if (value < 0 || value > KernelTimer::MAX_SLOTS)
+                return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_ATTN_KERNEL_TIMER: %lld slots outside [0, %d]", (long long)value,
+                            KernelTimer::MAX_SLOTS);
+            fr_status st = need_device(ctx);
+            if (st != FR_OK) return st;
+            KernelTimer& t = ctx->attn_timer;
+            for (int i = 0; i < (int)value; ++i) {   // events are created once and kept until fr_destroy
+                if (!t.start[i] && (hipEventCreate(&t.start[i]) != hipSuccess || hipEventCreate(&t.stop[i]) != hipSuccess))
+                    return hip_fail(ctx, "event creation", hipGetLastError());
+            }
+            t.n_slots = (int)value;
+            t.n_recorded = 0;
+            return FR_OK;
+        }
         case FR_OPT_GEMM_TILE:
             if (value != 0 && value != 128 && value != 256)
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_GEMM_TILE: %lld is not 0, 128 or 256", (long long)value);
@@ -207,6 +226,23 @@ fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value) {
         default:
             return fail(ctx, FR_ERR_INVALID_ARG, "unknown option %d", option);
     }
+}
+
+fr_status fr_attn_kernel_times(fr_ctx* ctx, float* ms_out, int32_t capacity, int32_t* n_out) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    if (!ms_out || !n_out || capacity < 0) return fail(ctx, FR_ERR_INVALID_ARG, "ms_out / n_out is NULL or capacity < 0");
+    KernelTimer& t = ctx->attn_timer;
+    const int64_t have = t.n_recorded < t.n_slots ? t.n_recorded : t.n_slots;
+    const int n = (int)(have < capacity ? have : capacity);
+    for (int i = 0; i < n; ++i) {   // oldest of the kept launches first
+        const int slot = (int)((t.n_recorded - have + i) % t.n_slots);
+        if (hipEventSynchronize(t.stop[slot]) != hipSuccess ||
+            hipEventElapsedTime(&ms_out[i], t.start[slot], t.stop[slot]) != hipSuccess)
+            return hip_fail(ctx, "reading kernel timer events", hipGetLastError());
+    }
+    *n_out = n;
+    return FR_OK;
 }
 
 fr_status fr_rope_shift(fr_ctx* ctx, const void* k_src, void* k_dst, const int32_t* chunk_offsets,
@@ -380,7 +416,7 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
     hipError_t e;
     if (attn_mfma_supported(s))
         e = launch_attn_mfma(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, ctx->ws,
-                             ctx->attn_softmax_mode, ctx->attn_split_mode, nullptr, hs);
+                             ctx->attn_softmax_mode, ctx->attn_split_mode, nullptr, &ctx->attn_timer, hs);
     else
         e = launch_attn_simt(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, hs);
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
@@ -433,7 +469,7 @@ fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const i
     sh.store_row0 = chunk_store_row0;
     sh.table = ctx->ws.rope_table;
     e = launch_attn_mfma(s, q_rows, q_index, R, k_store, v_store, L, k_new, v_new, ctx->ws.inv_index, out, lse_out, ctx->ws,
-                         ctx->attn_softmax_mode, ctx->attn_split_mode, &sh, hs);
+                         ctx->attn_softmax_mode, ctx->attn_split_mode, &sh, &ctx->attn_timer, hs);
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
     return FR_OK;
 }

@@ -55,6 +55,17 @@ struct Workspace {
 
 }  // namespace fr
 
+namespace fr {
+// Optional timing of the dominant attention kernel: a ring of event pairs recorded on the launch stream around it.
+struct KernelTimer {
+    static constexpr int MAX_SLOTS = 256;
+    int n_slots = 0;            // 0 = off
+    int64_t n_recorded = 0;     // launches recorded since it was switched on
+    hipEvent_t start[MAX_SLOTS] = {};
+    hipEvent_t stop[MAX_SLOTS] = {};
+};
+}  // namespace fr
+
 struct fr_ctx {
     fr::Shape shape;
     int64_t max_tokens = 0;
@@ -66,6 +77,7 @@ struct fr_ctx {
     int attn_softmax_mode = FR_ATTN_SOFTMAX_AUTO;
     int attn_split_mode = FR_ATTN_SPLIT_AUTO;
     int decode_generic = 0;
+    fr::KernelTimer attn_timer;
     std::string err;
 };
 
@@ -131,7 +143,7 @@ hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
                             const void* v_new, const int32_t* inv, void* out, float* lse,
                             const Workspace& ws, int softmax_mode, int split_mode, const struct SharedStoreArgs* shared,
-                            hipStream_t st);
+                            struct KernelTimer* timer, hipStream_t st);
 // The attention launch splits the key range in two on its own up to ATTN_SPLIT_AUTO_ITEMS (row tile, KV head)
 // items (about 1.5 x the 256 CUs: beyond that the items alone keep the chip busy and the partial results' traffic
 // costs more than the better balance gains), and on request (FR_ATTN_SPLIT_ON) up to ATTN_SPLIT_MAX_ITEMS, which

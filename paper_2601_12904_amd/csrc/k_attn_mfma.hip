@@ -788,7 +788,7 @@ template <int G>
 hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                   const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
                   float* lse, const Workspace& ws, int mode, int split_mode, const SharedStoreArgs* shared,
-                  hipStream_t st) {
+                  KernelTimer* timer, hipStream_t st) {
     const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
     constexpr int TR = Geometry<G>::TR;
     const int n_row_tiles = (R + TR - 1) / TR;
@@ -844,18 +844,23 @@ hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, in
     const bool fits = (size_t)grid.x * 2 * PART_FLOATS * sizeof(float) <= ws.attn_partials_bytes;
     const bool split = fits && (split_mode == FR_ATTN_SPLIT_ON ||
                                 (split_mode == FR_ATTN_SPLIT_AUTO && (int)grid.x <= ATTN_SPLIT_AUTO_ITEMS && n_img_tiles >= 32));
+    const bool timed = timer != nullptr && timer->n_slots > 0 && mode != FR_ATTN_SOFTMAX_RUNNING_MAX;
+    const int slot = timed ? (int)(timer->n_recorded % timer->n_slots) : 0;
+    if (timed && hipEventRecord(timer->start[slot], st) != hipSuccess) return hipGetLastError();
     if (mode == FR_ATTN_SOFTMAX_RUNNING_MAX) {
         flags = nullptr;   // recompute every workgroup with the running maximum
     } else if (split) {
         attn_fixed_ref_kernel<G, 2><<<dim3(grid.x * 2), block, lds_fast, st>>>(
             (const __bf16*)q_rows, q_index, R, ws.kv_images, n_img_tiles, (__bf16*)out, lse, ws.attn_flags,
             ws.attn_partials, s.Hq, s.Hkv, n_row_tiles, scale_log2e);
+        if (timed) { (void)hipEventRecord(timer->stop[slot], st); ++timer->n_recorded; }
         attn_combine_kernel<G><<<grid, block, EPILOGUE_LDS, st>>>(q_index, R, ws.attn_partials, (__bf16*)out, lse,
                                                                   ws.attn_flags, s.Hq, s.Hkv, n_row_tiles);
     } else {
         attn_fixed_ref_kernel<G, 1><<<grid, block, lds_fast, st>>>((const __bf16*)q_rows, q_index, R, ws.kv_images,
                                                                    n_img_tiles, (__bf16*)out, lse, ws.attn_flags, nullptr,
                                                                    s.Hq, s.Hkv, n_row_tiles, scale_log2e);
+        if (timed) { (void)hipEventRecord(timer->stop[slot], st); ++timer->n_recorded; }
     }
     attn_running_max_kernel<G><<<grid, block, lds_safe, st>>>((const __bf16*)q_rows, q_index, R, ws.kv_images,
                                                               n_img_tiles, (__bf16*)out, lse, flags, s.Hq, s.Hkv,
@@ -879,13 +884,13 @@ bool attn_mfma_supported(const Shape& s) {
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                             const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv,
                             void* out, float* lse, const Workspace& ws, int mode, int split_mode,
-                            const SharedStoreArgs* shared, hipStream_t st) {
+                            const SharedStoreArgs* shared, KernelTimer* timer, hipStream_t st) {
     if (R == 0) return hipSuccess;
     switch (s.G) {
-        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, st);
-        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, st);
-        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, st);
-        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, st);
+        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, st);
+        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, st);
+        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, st);
+        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, st);
     }
 }
 

@@ -408,6 +408,26 @@ def test_attention_split_key_range(seed, ratio):
     ctx.close()
 
 
+def test_attention_kernel_timer():
+    """The optional event pairs around the dominant attention kernel: one duration per launch, the most recent kept."""
+    w = synth.config_small_bf16(seed=2)
+    k_ctx, _, _, qi = staged(w)
+    k_cache, v_cache = assembled_cache(w, k_ctx)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    assert ctx.fr_attn_kernel_times() == []
+    ctx.fr_set_option(B.FR_OPT_ATTN_KERNEL_TIMER, 3)
+    for _ in range(5):
+        got, _ = run_attention(ctx, w, qi, k_cache, v_cache)
+    ms = ctx.fr_attn_kernel_times()
+    assert len(ms) == 3 and all(0.0 < t < 50.0 for t in ms)
+    ctx.fr_set_option(B.FR_OPT_ATTN_KERNEL_TIMER, 0)
+    got2, _ = run_attention(ctx, w, qi, k_cache, v_cache)
+    assert np.array_equal(got, got2) and ctx.fr_attn_kernel_times() == []
+    with pytest.raises(B.FusionRAGError):
+        ctx.fr_set_option(B.FR_OPT_ATTN_KERNEL_TIMER, 1000)
+    ctx.close()
+
+
 def test_attention_split_with_runaway_logits():
     """Split launch + overflow of the fixed exponent reference: the combine step must flag the workgroups and the
     running-maximum kernel recompute them."""
