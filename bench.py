@@ -548,6 +548,19 @@ def main():
     if timer_on:
         ctx.fr_set_option(B.FR_OPT_ATTN_KERNEL_TIMER, 0)
     ms_per_step = wall * 1e3 / args.steps
+    # the same step with the write-back fused into the attention call (three calls instead of four)
+    def step_fused():
+        ctx.fr_rope_shift(k_cached, k_cache, w.chunk_offsets, w.src_pos0)
+        ctx.fr_score_select(q_question, w.nq, k_cache, w.chunk_offsets, k, B.FR_NORM_PER_CHUNK, None, qi)
+        ctx.fr_sparse_prefill_attn_writeback(rows[0], qi, R, k_cache, v_cache, w.L, rows[1], rows[2], out)
+    for _ in range(2):
+        step_fused()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_fused()
+    torch.cuda.synchronize()
+    ms_fused = (time.perf_counter() - t0) * 1e3 / args.steps
     names = ["rope_shift", "score_select", "sparse_prefill_attn", "kv_scatter"]
     call_ms = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
                for i, n in enumerate(names)}
@@ -631,6 +644,7 @@ def main():
                    "question_tokens": w.nq, "chunks": w.n_chunks, "recompute_ratio": w.ratio, "selected": k,
                    "rows": R, "seed": args.seed},
         "call_ms": {n: round(v, 4) for n, v in call_ms.items()},
+        "ms_per_step_with_fused_writeback": round(ms_fused, 4),
         "attn_tflops": round(attn_tflops, 2),
         "attn_flops": attn_flops,
         "hbm_gbps": {n: round(v, 1) for n, v in hbm.items()},

@@ -182,6 +182,13 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
                                  const void* k_new, const void* v_new, void* out, float* lse_out,
                                  void* stream);
 
+/* fr_sparse_prefill_attn followed by fr_kv_scatter in one call (the write-back fused into the attention's tile
+ * packing pass): same output, and afterwards k_cache[q_index[r]] = k_new[r], v_cache[q_index[r]] = v_new[r].
+ * k_new / v_new are required; k_cache / v_cache are read and written. */
+fr_status fr_sparse_prefill_attn_writeback(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
+                                           void* k_cache, void* v_cache, int64_t L, const void* k_new,
+                                           const void* v_new, void* out, float* lse_out, void* stream);
+
 /* Sparse prefill attention over a shared chunk store (Sec. 4.3: the chunk caches are shared by the queries and never
  * modified; the recomputed K/V of a query live in its own page).  Same result as fr_rope_shift into a per-query
  * cache followed by fr_sparse_prefill_attn and fr_kv_scatter, without the per-query copy and without the scatter:

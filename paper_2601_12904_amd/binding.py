@@ -28,7 +28,7 @@ FR_DECODE_KERNEL_AUTO, FR_DECODE_KERNEL_GENERIC = 0, 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 FR_ATTN_SPLIT_AUTO, FR_ATTN_SPLIT_OFF, FR_ATTN_SPLIT_ON = 0, 1, 2
 EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_attn_kernel_times", "fr_topk_count", "fr_rope_shift",
-           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_shared", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
+           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_writeback", "fr_sparse_prefill_attn_shared", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
            "fr_linear_swiglu", "fr_qkv_rope")
 
 
@@ -82,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.fr_kv_deviation.restype = i32
     lib.fr_sparse_prefill_attn.argtypes = [vp, vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.fr_sparse_prefill_attn.restype = i32
+    lib.fr_sparse_prefill_attn_writeback.argtypes = [vp, vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, vp]
+    lib.fr_sparse_prefill_attn_writeback.restype = i32
     lib.fr_sparse_prefill_attn_shared.argtypes = [vp, vp, vp, i32, vp, vp, i64, pi32, pi32, pi32, i32, i64, vp, vp, vp, vp, vp]
     lib.fr_sparse_prefill_attn_shared.restype = i32
     lib.fr_decode_attn.argtypes = [vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, i32, vp, i64, vp, vp, i64, vp, vp, vp, vp]
@@ -203,6 +205,12 @@ class Context:
         self._check(self._lib.fr_sparse_prefill_attn(self._h, _ptr(q_rows), _ptr(q_index), int(R), _ptr(k_cache),
                                                      _ptr(v_cache), int(L), _ptr(k_new), _ptr(v_new), _ptr(out),
                                                      _ptr(lse_out), _stream(stream)))
+
+    def fr_sparse_prefill_attn_writeback(self, q_rows, q_index, R: int, k_cache, v_cache, L: int, k_new, v_new, out,
+                                         lse_out=None, stream=None):
+        self._check(self._lib.fr_sparse_prefill_attn_writeback(self._h, _ptr(q_rows), _ptr(q_index), int(R),
+                                                               _ptr(k_cache), _ptr(v_cache), int(L), _ptr(k_new),
+                                                               _ptr(v_new), _ptr(out), _ptr(lse_out), _stream(stream)))
 
     def fr_sparse_prefill_attn_shared(self, q_rows, q_index, R: int, k_store, v_store, n_store_rows: int, chunk_offsets,
                                       chunk_store_row0, chunk_src_pos0, L: int, k_new, v_new, out, lse_out=None,

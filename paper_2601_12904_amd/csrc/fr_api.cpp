@@ -387,9 +387,9 @@ static fr_status check_rows(fr_ctx* ctx, int32_t R, int64_t L) {
     return FR_OK;
 }
 
-fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
-                                 const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
-                                 const void* v_new, void* out, float* lse_out, void* stream) {
+static fr_status prefill_attn_impl(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
+                                   const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
+                                   const void* v_new, void* out, float* lse_out, bool writeback, void* stream) {
     if (!ctx) return FR_ERR_INVALID_ARG;
     ctx->err.clear();
     const Shape& s = ctx->shape;
@@ -413,14 +413,30 @@ fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t*
         if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
         inv = ctx->ws.inv_index;
     }
+    if (writeback && !k_new) return fail(ctx, FR_ERR_INVALID_ARG, "the write-back needs k_new / v_new");
     hipError_t e;
-    if (attn_mfma_supported(s))
+    if (attn_mfma_supported(s)) {
         e = launch_attn_mfma(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, ctx->ws,
-                             ctx->attn_softmax_mode, ctx->attn_split_mode, nullptr, &ctx->attn_timer, hs);
-    else
+                             ctx->attn_softmax_mode, ctx->attn_split_mode, nullptr, &ctx->attn_timer, writeback, hs);
+    } else {
         e = launch_attn_simt(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, hs);
+        if (e == hipSuccess && writeback)   // the generic kernel has no packing pass to fuse it into
+            e = launch_kv_scatter(s, k_new, v_new, q_index, R, const_cast<void*>(k_cache), const_cast<void*>(v_cache), hs);
+    }
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
     return FR_OK;
+}
+
+fr_status fr_sparse_prefill_attn(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
+                                 const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
+                                 const void* v_new, void* out, float* lse_out, void* stream) {
+    return prefill_attn_impl(ctx, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, out, lse_out, false, stream);
+}
+
+fr_status fr_sparse_prefill_attn_writeback(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
+                                           void* k_cache, void* v_cache, int64_t L, const void* k_new,
+                                           const void* v_new, void* out, float* lse_out, void* stream) {
+    return prefill_attn_impl(ctx, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, out, lse_out, true, stream);
 }
 
 fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
@@ -469,7 +485,7 @@ fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const i
     sh.store_row0 = chunk_store_row0;
     sh.table = ctx->ws.rope_table;
     e = launch_attn_mfma(s, q_rows, q_index, R, k_store, v_store, L, k_new, v_new, ctx->ws.inv_index, out, lse_out, ctx->ws,
-                         ctx->attn_softmax_mode, ctx->attn_split_mode, &sh, &ctx->attn_timer, hs);
+                         ctx->attn_softmax_mode, ctx->attn_split_mode, &sh, &ctx->attn_timer, false, hs);
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
     return FR_OK;
 }

@@ -143,7 +143,7 @@ hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
                             const void* v_new, const int32_t* inv, void* out, float* lse,
                             const Workspace& ws, int softmax_mode, int split_mode, const struct SharedStoreArgs* shared,
-                            struct KernelTimer* timer, hipStream_t st);
+                            struct KernelTimer* timer, bool writeback, hipStream_t st);
 // The attention launch splits the key range in two on its own up to ATTN_SPLIT_AUTO_ITEMS (row tile, KV head)
 // items (about 1.5 x the 256 CUs: beyond that the items alone keep the chip busy and the partial results' traffic
 // costs more than the better balance gains), and on request (FR_ATTN_SPLIT_ON) up to ATTN_SPLIT_MAX_ITEMS, which

@@ -156,8 +156,11 @@ __device__ __forceinline__ void write_image(const u32x4 (&kreg)[4], const u32x4 
         *reinterpret_cast<u32x4*>(dst + i * 4096 + tid * 16) = *reinterpret_cast<const u32x4*>(&img[i * 4096 + tid * 16]);
 }
 
-__global__ __launch_bounds__(256) void pack_kv_images_kernel(const __bf16* __restrict__ k_cache,
-                                                             const __bf16* __restrict__ v_cache, int L,
+// WRITEBACK: the fresh rows are also stored at their positions of the cache (the write-back of Sec. 4.3 fused into
+// this pass: the row is in registers anyway).  No workgroup reads a cache row that another one writes: a position
+// with a fresh row is never read from the cache.
+template <bool WRITEBACK>
+__global__ __launch_bounds__(256) void pack_kv_images_kernel(const __bf16* k_cache, const __bf16* v_cache, int L,
                                                              const __bf16* __restrict__ k_new,
                                                              const __bf16* __restrict__ v_new,
                                                              const int32_t* __restrict__ inv, int Hkv, int n_img_tiles,
@@ -180,6 +183,12 @@ __global__ __launch_bounds__(256) void pack_kv_images_kernel(const __bf16* __res
         }
         kreg[i] = *reinterpret_cast<const u32x4*>(pk + 8 * st_vec);
         vreg[i] = *reinterpret_cast<const u32x4*>(pv + 8 * st_vec);
+        if (WRITEBACK && inv != nullptr) {   // (a clamped key past the end repeats key L-1: the same bytes again)
+            if (inv[jk] >= 0)
+                *reinterpret_cast<u32x4*>(const_cast<__bf16*>(k_cache) + ((size_t)jk * Hkv + g) * D + 8 * st_vec) = kreg[i];
+            if (inv[jv] >= 0)
+                *reinterpret_cast<u32x4*>(const_cast<__bf16*>(v_cache) + ((size_t)jv * Hkv + g) * D + 8 * st_vec) = vreg[i];
+        }
     }
     write_image(kreg, vreg, img, images + ((size_t)g * n_img_tiles + kt) * IMG_BYTES);
 }
@@ -788,7 +797,7 @@ template <int G>
 hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                   const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
                   float* lse, const Workspace& ws, int mode, int split_mode, const SharedStoreArgs* shared,
-                  KernelTimer* timer, hipStream_t st) {
+                  KernelTimer* timer, bool writeback, hipStream_t st) {
     const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
     constexpr int TR = Geometry<G>::TR;
     const int n_row_tiles = (R + TR - 1) / TR;
@@ -815,9 +824,14 @@ hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, in
     if ((size_t)grid.x > ws.attn_flags_elems) return hipErrorInvalidValue;
     if ((size_t)n_img_tiles * s.Hkv * IMG_BYTES > ws.kv_images_bytes) return hipErrorInvalidValue;
     if (shared == nullptr) {
-        pack_kv_images_kernel<<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
-            (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
-            k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, ws.kv_images);
+        if (writeback)
+            pack_kv_images_kernel<true><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
+                (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
+                k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, ws.kv_images);
+        else
+            pack_kv_images_kernel<false><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
+                (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
+                k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, ws.kv_images);
     } else {   // k_cache / v_cache are the shared chunk store
         ChunkRows rows;
         int max_len = (int)L - shared->ct.off[shared->ct.n];
@@ -884,13 +898,13 @@ bool attn_mfma_supported(const Shape& s) {
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
                             const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv,
                             void* out, float* lse, const Workspace& ws, int mode, int split_mode,
-                            const SharedStoreArgs* shared, KernelTimer* timer, hipStream_t st) {
+                            const SharedStoreArgs* shared, KernelTimer* timer, bool writeback, hipStream_t st) {
     if (R == 0) return hipSuccess;
     switch (s.G) {
-        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, st);
-        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, st);
-        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, st);
-        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, st);
+        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
+        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
+        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
+        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
     }
 }
 

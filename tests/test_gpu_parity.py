@@ -408,6 +408,34 @@ def test_attention_split_key_range(seed, ratio):
     ctx.close()
 
 
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
+def test_attention_with_fused_writeback(name):
+    """fr_sparse_prefill_attn_writeback = attention + write-back in one call: output and caches equal the two-call path
+    bit for bit (the tiled path fuses the copy into its packing pass, the generic path runs the scatter kernel)."""
+    w = workloads()[name](6)
+    dt, tdt = w.shape.dtype, H.TORCH_DTYPE[w.shape.dtype]
+    k_ctx, _, _, qi = staged(w)
+    k_cache, v_cache = assembled_cache(w, k_ctx)
+    R = len(qi)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    q_rows, k_new, v_new = H.dev(w.q_full[qi], dt), H.dev(w.k_full[qi], dt), H.dev(w.v_full[qi], dt)
+    qi_d = torch.from_numpy(qi.astype(np.int32)).cuda()
+    kc1, vc1 = H.dev(k_cache, dt), H.dev(v_cache, dt)
+    kc2, vc2 = kc1.clone(), vc1.clone()
+    out1 = torch.zeros((R, w.shape.n_q_heads, w.shape.head_dim), dtype=tdt, device="cuda")
+    out2 = torch.zeros_like(out1)
+    ctx.fr_sparse_prefill_attn(q_rows, qi_d, R, kc1, vc1, w.L, k_new, v_new, out1)
+    ctx.fr_kv_scatter(k_new, v_new, qi_d, R, kc1, vc1, w.L)
+    ctx.fr_sparse_prefill_attn_writeback(q_rows, qi_d, R, kc2, vc2, w.L, k_new, v_new, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2) and torch.equal(kc1, kc2) and torch.equal(vc1, vc2)
+    want_k, want_v = orc.kv_scatter(qi, w.k_full[qi], w.v_full[qi], k_cache, v_cache)
+    assert np.array_equal(H.host(kc2), want_k) and np.array_equal(H.host(vc2), want_v)
+    with pytest.raises(B.FusionRAGError):
+        ctx.fr_sparse_prefill_attn_writeback(q_rows, qi_d, R, kc2, vc2, w.L, None, None, out2)
+    ctx.close()
+
+
 def test_attention_kernel_timer():
     """The optional event pairs around the dominant attention kernel: one duration per launch, the most recent kept."""
     w = synth.config_small_bf16(seed=2)
