@@ -305,12 +305,19 @@ __global__ __launch_bounds__(256) void pack_kv_images_shared_kernel(const __bf16
 //      16 bytes at the wave's LDS base + 16 i), no registers involved.  An image is 18 chunks of 1 KB; wave w
 //      moves chunks w, w + 4, ...  Completion: the issuing wave's vmcnt, then a workgroup barrier. ----------
 __device__ __forceinline__ void dma_image(const unsigned char* src, unsigned char* lds_dst, int wave, int lane) {
+    // Written out rather than left to the builtin: the compiler treats a pending direct-to-LDS load as an access
+    // that may complete out of order with the LDS reads, and from then on waits for *all* outstanding fragment
+    // reads before every use (lgkmcnt(0)), which puts a full LDS round trip in front of the matrix pipe every few
+    // fragments.  Completion is waited for explicitly anyway (wait_dma + workgroup barrier), so nothing is lost.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_dst;
 #pragma unroll
     for (int c = 0; c < 5; ++c) {
         const int chunk = wave + 4 * c;
-        if (chunk < K_IMG_BYTES / 1024)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + chunk * 1024 + lane * 16),
-                                             (__attribute__((address_space(3))) void*)(lds_dst + chunk * 1024), 16, 0, 0);
+        if (chunk < K_IMG_BYTES / 1024) {
+            const unsigned char* g = src + chunk * 1024 + lane * 16;
+            const uint32_t l = __builtin_amdgcn_readfirstlane(lds_base + chunk * 1024);
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory");
+        }
     }
 }
 __device__ __forceinline__ void wait_dma() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0)
@@ -408,7 +415,7 @@ __device__ __forceinline__ void pipeline_step(const unsigned char* k_next, int m
     }
     // Operand fragments are requested from LDS PF matrix steps before their use (rotating register buffer), so the
     // LDS latency overlaps the matrix and vector work already in flight.
-    constexpr int PF = 3;
+    constexpr int PF = 4;
     bf16x8 fr[PF + 1];
     auto frag = [&](int i) -> bf16x8 {   // i < 8: K fragment ks = i of the next half;  i >= 8: V fragment (kk, md)
         if (i < 8) return *reinterpret_cast<const bf16x8*>(k_next + fo.k + 32 * i + mb_next * (32 * K_ROW));
@@ -454,12 +461,17 @@ __device__ __forceinline__ void pipeline_step(const unsigned char* k_next, int m
     lsum[0] += psum0;
     lsum[1] += psum1;
 #if FR_SCHED_HINTS
-    // Ask the scheduler to alternate matrix and transcendental instructions (the two long-latency strands);
-    // measured: a few per cent over its own order, while fuller patterns (LDS reads, other vector work) lose.
+    // Ask the scheduler for: every fragment read PF matrix steps ahead of its use, and matrix and transcendental
+    // instructions (the two long-latency strands) alternating.  Measured: several per cent over its own order;
+    // patterns that also place the remaining vector work lose.
+    __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);       // the first PF fragment reads
 #pragma unroll
-    for (int i = 0; i < (DO_QK ? 32 : 16); ++i) {
+    for (int i = first; i < 16; ++i) {
+        if (i + PF < 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // fragment i + PF
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // matrix
         __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);   // transcendental
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
     }
 #endif
 }
