@@ -57,8 +57,11 @@ __device__ __forceinline__ void dma_tile(const __bf16* __restrict__ base, int64_
         const int r = u >> 3, cpos = u & 7;
         const int c = cpos ^ swz(r);
         const __bf16* src = base + (int64_t)min(row0 + r, rows - 1) * ld + k0 + 8 * c;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)(lds_tile + blk * 1024), 16, 0, 0);
+        // (written out: with the builtin the compiler takes the pending copy for an access that may complete out
+        // of order with the LDS reads, and waits for all outstanding fragment reads before every matrix instruction)
+        const uint32_t l = __builtin_amdgcn_readfirstlane(
+            (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)(lds_tile + blk * 1024));
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
     }
 }
 
@@ -213,19 +216,30 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
         if (kt + N_STAGE - 1 < n_kt) issue(kt + N_STAGE - 1);
         const unsigned char* wt = smem + (kt % N_STAGE) * STAGE_BYTES + (64 * wf) * 128;
         const unsigned char* at = smem + (kt % N_STAGE) * STAGE_BYTES + TL::W_TILE_BYTES + (64 * wr) * 128;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 wfrag[2], afrag[2];
+        // fragments of K step ks + 1 are requested before the matrix instructions of step ks are issued
+        bf16x8 wfrag[2][2], afrag[2][2];
+        auto request = [&](int ks, int buf) {
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
-                wfrag[b] = *reinterpret_cast<const bf16x8*>(wt + b * (32 * 128) + frag[ks][b]);
-                afrag[b] = *reinterpret_cast<const bf16x8*>(at + b * (32 * 128) + frag[ks][b]);
+                wfrag[buf][b] = *reinterpret_cast<const bf16x8*>(wt + b * (32 * 128) + frag[ks][b]);
+                afrag[buf][b] = *reinterpret_cast<const bf16x8*>(at + b * (32 * 128) + frag[ks][b]);
             }
+        };
+        request(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks + 1 < 4) request(ks + 1, (ks + 1) & 1);
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[mb], afrag[nb], acc[mb][nb], 0, 0, 0);
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag[ks & 1][mb], afrag[ks & 1][nb], acc[mb][nb], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // LDS reads of step 0
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks + 1 < 4) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);   // matrix
         }
     }
 
