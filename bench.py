@@ -627,6 +627,22 @@ def main():
     ctx_big.close()
     del big_src, big_dst, dev_all, raw_scores, big_k
 
+    # selection at a stress size where it is bound by reading the scores (2^24 scores = 64 MB, top 15 %)
+    n_sel = 1 << 24
+    k_sel = B.fr_topk_count(n_sel, 0.15)
+    sel_scores = torch.empty(n_sel, dtype=torch.float32, device="cuda").log_normal_(mean=2.77, std=0.6,
+                                                                                   generator=torch.Generator(device="cuda").manual_seed(args.seed))
+    sel_out = torch.empty(k_sel, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        ctx.fr_select_topk(sel_scores, n_sel, k_sel, 0, sel_out)
+    a.record()
+    for _ in range(reps):
+        ctx.fr_select_topk(sel_scores, n_sel, k_sel, 0, sel_out)
+    b.record()
+    torch.cuda.synchronize()
+    sel_ms = a.elapsed_time(b) / reps
+    del sel_scores, sel_out
+
     if args.calibrate_copy:   # 2^28 fp32 = 1 GiB read + 1 GiB written by one elementwise copy kernel
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
@@ -654,6 +670,9 @@ def main():
                                  "frac_of_hbm_peak": round(raw_all_gbps / PEAK_HBM_GBPS, 4)},
         "kv_deviation_all_layers": {"layers": nl, "ms": round(dev_all_ms, 4), "gbps": round(dev_all_gbps, 1),
                                     "frac_of_hbm_peak": round(dev_all_gbps / PEAK_HBM_GBPS, 4)},
+        "select_stress": {"scores": n_sel, "selected": k_sel, "ms": round(sel_ms, 4),
+                          "passes_over_the_scores": 5, "ms_of_one_read_at_hbm_peak": round(4 * n_sel / PEAK_HBM_GBPS / 1e6, 4),
+                          "gbps_of_five_reads_and_the_output": round((5 * 4 * n_sel + 4 * k_sel) / (sel_ms * 1e-3) / 1e9, 1)},
         "roofline": {"kernel": "attn_fixed_ref_kernel (key-tile loop of fr_sparse_prefill_attn)" if kernel_ms
                      else "sparse_prefill_attn", "bound": "mfma", "achieved": round(kernel_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS if dt == "bf16" else 157.3, "unit": "TFLOP/s",

@@ -133,7 +133,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_inv = take((size_t)max_tokens * 4);
     const size_t o_srow = take((size_t)max_tokens * 4);
     const size_t o_cid = take((size_t)max_tokens * 4);
-    const size_t o_sel = take(4096);
+    const size_t o_sel = take(select_workspace_bytes());
     const size_t o_qsum = take(score_raw_workspace_bytes(s));
     w.attn_flags_elems = (size_t)(max_tokens / 32 + 1) * s.Hkv;   // one per (row tile of >= 32 rows, KV head)
     const size_t o_flags = take(w.attn_flags_elems * 4);

@@ -41,7 +41,7 @@ struct Workspace {
     int32_t* store_row_map = nullptr;   // [max_tokens] prompt position -> row of the shared chunk store / -1
     int32_t* chunk_id_map = nullptr;    // [max_tokens] prompt position -> chunk
     float* qsum = nullptr;              // [Hkv][d] question queries summed per KV head (raw scores), then partial sums
-    uint32_t* select_tmp = nullptr; // small counters for the selection kernels
+    uint32_t* select_tmp = nullptr; // state, histogram, per-wave counts and candidate list of the selection kernels
     int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
     size_t attn_flags_elems = 0;
     float2* rope_rows = nullptr;    // [max_tokens][d/2] (cos, sin) of the recomputed rows' positions
@@ -104,6 +104,9 @@ hipError_t launch_score_mfma(const Shape& s, const void* q, int nq, const void* 
 
 hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index,
                          uint32_t* tmp, hipStream_t st);
+size_t select_workspace_bytes();   // what `tmp` must hold
+hipError_t launch_select_large(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index, uint32_t* tmp,
+                               hipStream_t st);   // n beyond one workgroup's registers
 
 hipError_t launch_kv_deviation(const Shape& s, const void* kv_a, const void* kv_b, int64_t n_tokens, float* out,
                                hipStream_t st);

@@ -6,7 +6,7 @@
 // ordered compaction then emits, in index order, every token above that key plus the first
 // (lowest-index) tokens equal to it that are still needed.  The result is unique, so it does not
 // depend on scheduling.  One workgroup: the 64 KB of scores of a 17k-token prompt fit its registers, and the
-// whole selection is latency- rather than bandwidth-sized.  Scores of one prompt are clustered (their sign and
+// whole selection is latency- rather than bandwidth-sized (longer score vectors: k_select_large.hip).  Scores of one prompt are clustered (their sign and
 // most exponent bits agree), which would pile a plain histogram onto one or two bins; the digits are therefore
 // taken from key - min(key), starting at the highest bit in which the largest and the smallest key differ.
 #include "fr_internal.hpp"
@@ -55,8 +55,7 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot) {   // set bits
 
 // Wave w owns the contiguous index range [w * 64 * per, (w + 1) * 64 * per); its i-th load covers the 64
 // consecutive tokens base + 64 i + lane, so loads and stores are coalesced and (i, lane) order is index order.
-// PER > 0: every thread keeps its PER keys in registers (n <= SEL_THREADS * PER);
-// PER == 0: any n, the scores are re-read from memory in every pass.
+// Every thread keeps its PER keys in registers (n <= SEL_THREADS * PER).
 template <int PER>
 __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* __restrict__ scores, int64_t n,
                                                                   int64_t k, int nq, int32_t* __restrict__ out) {
@@ -71,19 +70,17 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
     for (int i = tid; i < nq; i += SEL_THREADS) out[k + i] = (int32_t)(n + i);
     if (k <= 0 || n <= 0) return;
 
-    const int per = (PER > 0) ? PER : (int)((n + SEL_THREADS - 1) / SEL_THREADS);
-    const int64_t first = (int64_t)wave * 64 * per + lane;     // this lane's tokens: first + 64 i
-    const int cnt = (int)max((int64_t)0, min((int64_t)per, (n - first + 63) / 64));
-    uint32_t keys[PER > 0 ? PER : 1];
-    if (PER > 0) {
+    const int64_t first = (int64_t)wave * 64 * PER + lane;     // this lane's tokens: first + 64 i
+    const int cnt = (int)max((int64_t)0, min((int64_t)PER, (n - first + 63) / 64));
+    uint32_t keys[PER];
+    {
         // branch-free: every load is issued (index clamped into the array) before the first one is waited for
-        float raw[PER > 0 ? PER : 1];
+        float raw[PER];
 #pragma unroll
         for (int i = 0; i < PER; ++i) raw[i] = scores[min(first + 64 * i, n - 1)];
 #pragma unroll
         for (int i = 0; i < PER; ++i) keys[i] = (i < cnt) ? score_key(raw[i]) : 0u;
     }
-    auto key_at = [&](int i) -> uint32_t { return (PER > 0) ? keys[i] : score_key(scores[first + 64 * (int64_t)i]); };
 
     uint32_t thr_key = 0u;     // key of the k-th largest score
     uint32_t need_eq = 0u;     // how many tokens equal to it are taken
@@ -91,13 +88,9 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
     if (!take_all) {
         // range of the keys: block-wide minimum and maximum
         uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-        if (PER > 0) {
 #pragma unroll
-            for (int i = 0; i < PER; ++i)
-                if (i < cnt) { kmin = min(kmin, keys[i]); kmax = max(kmax, keys[i]); }
-        } else {
-            for (int i = 0; i < cnt; ++i) { const uint32_t key = key_at(i); kmin = min(kmin, key); kmax = max(kmax, key); }
-        }
+        for (int i = 0; i < PER; ++i)
+            if (i < cnt) { kmin = min(kmin, keys[i]); kmax = max(kmax, keys[i]); }
         for (int o = 32; o > 0; o >>= 1) {
             kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
             kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
@@ -119,17 +112,10 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
             if (tid < 256) hist[tid] = 0u;
             __syncthreads();
             const uint32_t prefix = s_prefix;
-            if (PER > 0) {
 #pragma unroll
-                for (int i = 0; i < PER; ++i) {
-                    const uint32_t rk = keys[i] - kmin;
-                    if (i < cnt && (rk & mask) == prefix) atomicAdd(&hist[(rk >> shift) & digit_mask], 1u);
-                }
-            } else {
-                for (int i = 0; i < cnt; ++i) {
-                    const uint32_t rk = key_at(i) - kmin;
-                    if ((rk & mask) == prefix) atomicAdd(&hist[(rk >> shift) & digit_mask], 1u);
-                }
+            for (int i = 0; i < PER; ++i) {
+                const uint32_t rk = keys[i] - kmin;
+                if (i < cnt && (rk & mask) == prefix) atomicAdd(&hist[(rk >> shift) & digit_mask], 1u);
             }
             __syncthreads();
             pick_digit(hist, wave_tot, &s_prefix, &s_remaining, shift);
@@ -145,18 +131,10 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
     auto is_gt = [&](int i, uint32_t key) { return i < cnt && (take_all || key > thr_key); };
     auto is_eq = [&](int i, uint32_t key) { return i < cnt && !take_all && key == thr_key; };
     uint32_t w_gt = 0u, w_eq = 0u;
-    if (PER > 0) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            w_gt += (uint32_t)__popcll(__ballot(is_gt(i, keys[i])));
-            w_eq += (uint32_t)__popcll(__ballot(is_eq(i, keys[i])));
-        }
-    } else {
-        for (int i = 0; i < per; ++i) {
-            const uint32_t key = (i < cnt) ? key_at(i) : 0u;
-            w_gt += (uint32_t)__popcll(__ballot(is_gt(i, key)));
-            w_eq += (uint32_t)__popcll(__ballot(is_eq(i, key)));
-        }
+    for (int i = 0; i < PER; ++i) {
+        w_gt += (uint32_t)__popcll(__ballot(is_gt(i, keys[i])));
+        w_eq += (uint32_t)__popcll(__ballot(is_eq(i, keys[i])));
     }
     __syncthreads();   // wave_a / wave_b are free again
     if (lane == 0) { wave_a[wave] = w_gt; wave_b[wave] = w_eq; }
@@ -176,17 +154,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
         pos += (uint32_t)__popcll(bsel);
         eq_seen += (uint32_t)__popcll(beq);
     };
-    if (PER > 0) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) emit(i, keys[i]);
-    } else {
-        for (int i = 0; i < per; ++i) emit(i, (i < cnt) ? key_at(i) : 0u);
-    }
+    for (int i = 0; i < PER; ++i) emit(i, keys[i]);
 }
 
 hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index, uint32_t* tmp,
                          hipStream_t st) {
-    (void)tmp;
     if (k + nq == 0) return hipSuccess;
     if (n <= (int64_t)SEL_THREADS * 8)
         select_topk_kernel<8><<<dim3(1), dim3(SEL_THREADS), 0, st>>>(scores, n, k, nq, q_index);
@@ -195,7 +168,7 @@ hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int3
     else if (n <= (int64_t)SEL_THREADS * 32)
         select_topk_kernel<32><<<dim3(1), dim3(SEL_THREADS), 0, st>>>(scores, n, k, nq, q_index);
     else
-        select_topk_kernel<0><<<dim3(1), dim3(SEL_THREADS), 0, st>>>(scores, n, k, nq, q_index);
+        return launch_select_large(scores, n, k, nq, q_index, tmp, st);
     return hipGetLastError();
 }
 

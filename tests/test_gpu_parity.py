@@ -163,6 +163,37 @@ def test_select_topk_exact(n, k, nq):
     ctx.close()
 
 
+@pytest.mark.parametrize("n,k,nq", [(32769, 4915, 3), (40000, 40000, 2), (33000, 1, 0), (300000, 45000, 9),
+                                    (1 << 20, 157286, 0), (1234567, 1234, 1)])
+def test_select_topk_many_workgroups(n, k, nq):
+    """Score vectors beyond one workgroup's registers take the multi-pass selection: same definition, same oracle.
+    `narrow_cluster` puts more keys into one 24-bit prefix than the candidate list holds (the last level then re-reads
+    the scores); `ties` and `constant` exercise the equal-key budget across waves."""
+    ctx = H.make_ctx(synth.TINY_F32, 4096, 4, 16)
+    rng = np.random.default_rng(n ^ k)
+    for kind in ("signed", "ties", "clustered", "full_range", "constant", "narrow_cluster"):
+        if kind == "signed":
+            s = rng.standard_normal(n).astype(np.float32)
+        elif kind == "ties":
+            s = rng.integers(0, 8, size=n).astype(np.float32)
+        elif kind == "clustered":
+            s = (16.0 * np.exp(0.6 * rng.standard_normal(n))).astype(np.float32)
+        elif kind == "full_range":
+            s = (16.0 * np.exp(0.6 * rng.standard_normal(n))).astype(np.float32)
+            s[n // 2] = -3.0e38
+            s[n // 3] = 3.0e38
+        elif kind == "constant":
+            s = np.full(n, 0.25, dtype=np.float32)
+        else:
+            s = (np.float32(1.0) + rng.integers(0, 256, size=n).astype(np.float32) * np.float32(2.0 ** -23)).astype(np.float32)
+            s[n // 5] = 1.0e30
+        out = torch.full((k + nq,), -7, dtype=torch.int32, device="cuda")
+        ctx.fr_select_topk(torch.from_numpy(s).cuda(), n, k, nq, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), orc.select_q_index(s, k, nq)), kind
+    ctx.close()
+
+
 @pytest.mark.parametrize("name", ["tiny_f32", "offline_bf16"])
 def test_offline_preprocess_attention(name):
     """eq. 10, the offline stage's attention: the retrieved chunks' cached keys are moved to their positions in
