@@ -209,6 +209,37 @@ fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const i
                                         const int32_t* chunk_src_pos0, int32_t n_chunks, int64_t L, const void* k_new,
                                         const void* v_new, void* out, float* lse_out, void* stream);
 
+/* The same for several queries in one call (Sec. 4.3: queries that retrieve chunks of one store are served
+ * together; each has its own chunk list, Q index, page of fresh rows and output).  All queries of the call share one
+ * attention launch (groups of 16), which fills the chip where a single sparse query cannot; results equal those of
+ * fr_sparse_prefill_attn_shared query by query.
+ *   queries    host [n_queries]: the per-query arguments of fr_sparse_prefill_attn_shared (host and device pointers
+ *              as there); a query with R = 0 is skipped
+ *   workspace  dev, 256-byte aligned, at least fr_shared_batch_workspace_bytes(ctx, n_queries, max over queries of L)
+ *              bytes: tile images, index maps and rotation tables of the queries in flight (78 MB per 17k-token
+ *              query); owned by the caller, contents undefined afterwards, must stay untouched until the call's
+ *              work on the stream has finished
+ * Every query is validated before the first launch.  Errors as fr_sparse_prefill_attn_shared (the message names
+ * the query), plus FR_ERR_WORKSPACE when workspace_bytes is too small. */
+typedef struct {
+    const void* q_rows;                /* dev [R, Hq, d] */
+    const int32_t* q_index;            /* dev [R] */
+    int32_t R;
+    const int32_t* chunk_offsets;      /* host [n_chunks + 1] */
+    const int32_t* chunk_store_row0;   /* host [n_chunks] */
+    const int32_t* chunk_src_pos0;     /* host [n_chunks] */
+    int32_t n_chunks;
+    int64_t L;
+    const void* k_new;                 /* dev [R, Hkv, d] */
+    const void* v_new;                 /* dev [R, Hkv, d] */
+    void* out;                         /* dev [R, Hq, d] */
+    float* lse_out;                    /* dev [R, Hq] or NULL */
+} fr_shared_query;
+int64_t fr_shared_batch_workspace_bytes(const fr_ctx* ctx, int32_t n_queries, int64_t max_L);
+fr_status fr_sparse_prefill_attn_shared_batch(fr_ctx* ctx, const fr_shared_query* queries, int32_t n_queries,
+                                              const void* k_store, const void* v_store, int64_t n_store_rows,
+                                              void* workspace, int64_t workspace_bytes, void* stream);
+
 /* Batch decoding attention over shared chunk caches and per-query exclusive pages (Sec. 4.3; decoding step of
  * Sec. 2.1).  The chunk store (k_shared, v_shared) is shared by all queries of the batch and is never written.
  * Query b's prompt consists of the store segments seg_*[seg_offsets[b] .. seg_offsets[b+1]): rows

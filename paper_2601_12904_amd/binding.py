@@ -28,7 +28,7 @@ FR_DECODE_KERNEL_AUTO, FR_DECODE_KERNEL_GENERIC = 0, 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 FR_ATTN_SPLIT_AUTO, FR_ATTN_SPLIT_OFF, FR_ATTN_SPLIT_ON = 0, 1, 2
 EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_attn_kernel_times", "fr_topk_count", "fr_rope_shift",
-           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_writeback", "fr_sparse_prefill_attn_shared", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
+           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_writeback", "fr_sparse_prefill_attn_shared", "fr_shared_batch_workspace_bytes", "fr_sparse_prefill_attn_shared_batch", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
            "fr_linear_swiglu", "fr_qkv_rope")
 
 
@@ -36,6 +36,14 @@ class fr_layer_desc(ctypes.Structure):
     _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("rope_base", ctypes.c_double), ("rope_layout", ctypes.c_int32),
                 ("rope_index_base", ctypes.c_int32)]
+
+
+class fr_shared_query(ctypes.Structure):
+    _fields_ = [("q_rows", ctypes.c_void_p), ("q_index", ctypes.c_void_p), ("R", ctypes.c_int32),
+                ("chunk_offsets", ctypes.POINTER(ctypes.c_int32)), ("chunk_store_row0", ctypes.POINTER(ctypes.c_int32)),
+                ("chunk_src_pos0", ctypes.POINTER(ctypes.c_int32)), ("n_chunks", ctypes.c_int32), ("L", ctypes.c_int64),
+                ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("out", ctypes.c_void_p),
+                ("lse_out", ctypes.c_void_p)]
 
 
 class FusionRAGError(RuntimeError):
@@ -86,6 +94,10 @@ def load() -> ctypes.CDLL:
     lib.fr_sparse_prefill_attn_writeback.restype = i32
     lib.fr_sparse_prefill_attn_shared.argtypes = [vp, vp, vp, i32, vp, vp, i64, pi32, pi32, pi32, i32, i64, vp, vp, vp, vp, vp]
     lib.fr_sparse_prefill_attn_shared.restype = i32
+    lib.fr_shared_batch_workspace_bytes.argtypes = [vp, i32, i64]
+    lib.fr_shared_batch_workspace_bytes.restype = i64
+    lib.fr_sparse_prefill_attn_shared_batch.argtypes = [vp, ctypes.POINTER(fr_shared_query), i32, vp, vp, i64, vp, i64, vp]
+    lib.fr_sparse_prefill_attn_shared_batch.restype = i32
     lib.fr_decode_attn.argtypes = [vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, i32, vp, i64, vp, vp, i64, vp, vp, vp, vp]
     lib.fr_decode_attn.restype = i32
     lib.fr_mark_stale_rows.argtypes = [vp, vp, i64, vp, i32, i32, vp]
@@ -222,6 +234,29 @@ class Context:
                                                             _ptr(v_store), int(n_store_rows), offs, row0, src,
                                                             len(_a) - 1, int(L), _ptr(k_new), _ptr(v_new), _ptr(out),
                                                             _ptr(lse_out), _stream(stream)))
+
+    def fr_shared_batch_workspace_bytes(self, n_queries: int, max_L: int) -> int:
+        return int(self._lib.fr_shared_batch_workspace_bytes(self._h, int(n_queries), int(max_L)))
+
+    def fr_sparse_prefill_attn_shared_batch(self, queries, k_store, v_store, n_store_rows: int, workspace,
+                                            workspace_bytes: Optional[int] = None, stream=None):
+        """queries: sequence of dicts with the keys q_rows, q_index, R, chunk_offsets, chunk_store_row0, chunk_src_pos0,
+        L, k_new, v_new, out and optionally lse_out (the per-query arguments of fr_sparse_prefill_attn_shared)."""
+        arr = (fr_shared_query * max(1, len(queries)))()
+        keep = []
+        for i, q in enumerate(queries):
+            offs, a = _i32_array(q["chunk_offsets"])
+            row0, b = _i32_array(q["chunk_store_row0"])
+            src, c = _i32_array(q["chunk_src_pos0"])
+            keep += [a, b, c]
+            arr[i] = fr_shared_query(_ptr(q["q_rows"]), _ptr(q["q_index"]), int(q["R"]), offs, row0, src, len(a) - 1,
+                                     int(q["L"]), _ptr(q["k_new"]), _ptr(q["v_new"]), _ptr(q["out"]),
+                                     _ptr(q.get("lse_out")))
+        if workspace_bytes is None:
+            workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self._check(self._lib.fr_sparse_prefill_attn_shared_batch(self._h, arr, len(queries), _ptr(k_store), _ptr(v_store),
+                                                                  int(n_store_rows), _ptr(workspace), int(workspace_bytes),
+                                                                  _stream(stream)))
 
     def fr_decode_attn(self, q, n_queries: int, k_shared, v_shared, n_shared_rows: int, seg_offsets, seg_row0, seg_len,
                        seg_delta, n_segments: int, stale_bits, stale_words: int, k_pages, v_pages, page_stride_rows: int,

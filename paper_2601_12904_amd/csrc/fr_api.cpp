@@ -7,6 +7,9 @@
 
 #include "fr_internal.hpp"
 
+#include <string>
+#include <vector>
+
 using namespace fr;
 
 namespace {
@@ -439,6 +442,44 @@ fr_status fr_sparse_prefill_attn_writeback(fr_ctx* ctx, const void* q_rows, cons
     return prefill_attn_impl(ctx, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, out, lse_out, true, stream);
 }
 
+// Host-side checks of one query over the shared chunk store; fills the chunk table and the position deltas.
+static fr_status check_shared_query(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
+                                    const void* k_store, const void* v_store, int64_t n_store_rows,
+                                    const int32_t* chunk_offsets, const int32_t* chunk_store_row0,
+                                    const int32_t* chunk_src_pos0, int32_t n_chunks, int64_t L, const void* k_new,
+                                    const void* v_new, const void* out, const float* lse_out, SharedStoreArgs* sh,
+                                    ChunkDeltas* dl) {
+    fr_status st = check_rows(ctx, R, L);
+    if (st != FR_OK) return st;
+    st = read_chunks(ctx, chunk_offsets, n_chunks, L, &sh->ct, nullptr);
+    if (st != FR_OK) return st;
+    if (n_store_rows < 0) return fail(ctx, FR_ERR_INVALID_ARG, "n_store_rows is negative");
+    if (n_chunks > 0 && (!chunk_store_row0 || !chunk_src_pos0))
+        return fail(ctx, FR_ERR_INVALID_ARG, "chunk_store_row0 / chunk_src_pos0 is NULL");
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t len = (int64_t)sh->ct.off[c + 1] - sh->ct.off[c];
+        if (chunk_store_row0[c] < 0 || (int64_t)chunk_store_row0[c] + len > n_store_rows)
+            return fail(ctx, FR_ERR_INVALID_ARG, "chunk %d: store rows [%d, %lld) outside the store of %lld rows", c,
+                        chunk_store_row0[c], (long long)chunk_store_row0[c] + len, (long long)n_store_rows);
+        const int64_t delta = (int64_t)sh->ct.off[c] - (int64_t)chunk_src_pos0[c];
+        if (delta > INT32_MAX || delta < INT32_MIN) return fail(ctx, FR_ERR_INVALID_ARG, "position delta overflows");
+        dl->delta[c] = (int32_t)delta;
+    }
+    if (R == 0) return FR_OK;
+    if (!q_rows || !q_index || !out || !k_new || !v_new)
+        return fail(ctx, FR_ERR_INVALID_ARG, "q_rows / q_index / k_new / v_new / out is NULL");
+    if (sh->ct.off[sh->ct.n] > 0 && (!k_store || !v_store)) return fail(ctx, FR_ERR_INVALID_ARG, "k_store / v_store is NULL");
+    if (!aligned16(q_rows) || !aligned16(k_store) || !aligned16(v_store) || !aligned16(out) || !aligned16(k_new) ||
+        !aligned16(v_new))
+        return fail(ctx, FR_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(q_index) & 3u) || (reinterpret_cast<uintptr_t>(lse_out) & 3u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "q_index / lse_out must be 4-byte aligned");
+    if (!attn_mfma_supported(ctx->shape))
+        return fail(ctx, FR_ERR_UNSUPPORTED, "the shared-store attention needs bf16, head_dim 128 and a group size of 1, 2, 4 or 8");
+    sh->store_row0 = chunk_store_row0;
+    return FR_OK;
+}
+
 fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
                                         const void* k_store, const void* v_store, int64_t n_store_rows,
                                         const int32_t* chunk_offsets, const int32_t* chunk_store_row0,
@@ -447,46 +488,132 @@ fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const i
     if (!ctx) return FR_ERR_INVALID_ARG;
     ctx->err.clear();
     const Shape& s = ctx->shape;
-    fr_status st = check_rows(ctx, R, L);
-    if (st != FR_OK) return st;
     SharedStoreArgs sh;
-    st = read_chunks(ctx, chunk_offsets, n_chunks, L, &sh.ct, nullptr);
-    if (st != FR_OK) return st;
-    if (n_store_rows < 0) return fail(ctx, FR_ERR_INVALID_ARG, "n_store_rows is negative");
-    if (n_chunks > 0 && (!chunk_store_row0 || !chunk_src_pos0))
-        return fail(ctx, FR_ERR_INVALID_ARG, "chunk_store_row0 / chunk_src_pos0 is NULL");
     ChunkDeltas dl;
-    for (int c = 0; c < n_chunks; ++c) {
-        const int64_t len = (int64_t)sh.ct.off[c + 1] - sh.ct.off[c];
-        if (chunk_store_row0[c] < 0 || (int64_t)chunk_store_row0[c] + len > n_store_rows)
-            return fail(ctx, FR_ERR_INVALID_ARG, "chunk %d: store rows [%d, %lld) outside the store of %lld rows", c,
-                        chunk_store_row0[c], (long long)chunk_store_row0[c] + len, (long long)n_store_rows);
-        const int64_t delta = (int64_t)sh.ct.off[c] - (int64_t)chunk_src_pos0[c];
-        if (delta > INT32_MAX || delta < INT32_MIN) return fail(ctx, FR_ERR_INVALID_ARG, "position delta overflows");
-        dl.delta[c] = (int32_t)delta;
-    }
+    fr_status st = check_shared_query(ctx, q_rows, q_index, R, k_store, v_store, n_store_rows, chunk_offsets,
+                                      chunk_store_row0, chunk_src_pos0, n_chunks, L, k_new, v_new, out, lse_out, &sh, &dl);
+    if (st != FR_OK) return st;
     if (R == 0) return FR_OK;
-    if (!q_rows || !q_index || !out || !k_new || !v_new)
-        return fail(ctx, FR_ERR_INVALID_ARG, "q_rows / q_index / k_new / v_new / out is NULL");
-    if (sh.ct.off[sh.ct.n] > 0 && (!k_store || !v_store)) return fail(ctx, FR_ERR_INVALID_ARG, "k_store / v_store is NULL");
-    if (!aligned16(q_rows) || !aligned16(k_store) || !aligned16(v_store) || !aligned16(out) || !aligned16(k_new) ||
-        !aligned16(v_new))
-        return fail(ctx, FR_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    if ((reinterpret_cast<uintptr_t>(q_index) & 3u) || (reinterpret_cast<uintptr_t>(lse_out) & 3u))
-        return fail(ctx, FR_ERR_INVALID_ARG, "q_index / lse_out must be 4-byte aligned");
-    if (!attn_mfma_supported(s))
-        return fail(ctx, FR_ERR_UNSUPPORTED, "the shared-store attention needs bf16, head_dim 128 and a group size of 1, 2, 4 or 8");
     if ((st = need_device(ctx)) != FR_OK) return st;
     hipStream_t hs = (hipStream_t)stream;
     hipError_t e = launch_inv_index(q_index, R, L, ctx->ws.inv_index, hs);
     if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
     e = launch_rope_table(s, dl, n_chunks, ctx->ws.rope_table, hs);
     if (e != hipSuccess) return hip_fail(ctx, "rope table launch", e);
-    sh.store_row0 = chunk_store_row0;
     sh.table = ctx->ws.rope_table;
     e = launch_attn_mfma(s, q_rows, q_index, R, k_store, v_store, L, k_new, v_new, ctx->ws.inv_index, out, lse_out, ctx->ws,
                          ctx->attn_softmax_mode, ctx->attn_split_mode, &sh, &ctx->attn_timer, false, hs);
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
+    return FR_OK;
+}
+
+// Scratch of one query of a batch inside the caller's workspace, every part 256-byte aligned.
+namespace {
+struct BatchScratch {
+    size_t inv, srow, cid, table, images, flags, end;
+    size_t images_bytes, flags_elems;
+};
+BatchScratch batch_scratch(const Shape& s, int64_t L, int64_t R, size_t base) {
+    BatchScratch b{};
+    size_t off = base;
+    auto take = [&](size_t bytes) {
+        const size_t o = off;
+        off += round_up(bytes, 256);
+        return o;
+    };
+    b.inv = take((size_t)L * 4);
+    b.srow = take((size_t)L * 4);
+    b.cid = take((size_t)L * 4);
+    b.table = take((size_t)FR_MAX_CHUNKS * (s.d / 2) * sizeof(float2));
+    b.images_bytes = attn_mfma_images_bytes(s, L);
+    b.images = take(b.images_bytes);
+    b.flags_elems = attn_mfma_flags_elems(s, R);
+    b.flags = take(b.flags_elems * 4);
+    b.end = off;
+    return b;
+}
+}  // namespace
+
+int64_t fr_shared_batch_workspace_bytes(const fr_ctx* ctx, int32_t n_queries, int64_t max_L) {
+    if (!ctx || n_queries <= 0 || max_L <= 0) return 0;
+    const int64_t group = n_queries < ATTN_MAX_BATCH ? n_queries : ATTN_MAX_BATCH;
+    return group * (int64_t)batch_scratch(ctx->shape, max_L, max_L, 0).end;
+}
+
+fr_status fr_sparse_prefill_attn_shared_batch(fr_ctx* ctx, const fr_shared_query* queries, int32_t n_queries,
+                                              const void* k_store, const void* v_store, int64_t n_store_rows,
+                                              void* workspace, int64_t workspace_bytes, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    const Shape& s = ctx->shape;
+    if (n_queries < 0) return fail(ctx, FR_ERR_INVALID_ARG, "n_queries = %d is negative", n_queries);
+    if (n_queries == 0) return FR_OK;
+    if (!queries) return fail(ctx, FR_ERR_INVALID_ARG, "queries is NULL");
+    if (workspace_bytes < 0 || (workspace_bytes > 0 && !workspace) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "workspace is NULL or not 256-byte aligned");
+    // every query is checked before anything is launched
+    std::vector<SharedBatchQuery> work;
+    std::vector<ChunkDeltas> deltas;
+    work.reserve(n_queries);
+    deltas.reserve(n_queries);
+    for (int i = 0; i < n_queries; ++i) {
+        const fr_shared_query& q = queries[i];
+        SharedBatchQuery w{};
+        ChunkDeltas dl;
+        fr_status st = check_shared_query(ctx, q.q_rows, q.q_index, q.R, k_store, v_store, n_store_rows, q.chunk_offsets,
+                                          q.chunk_store_row0, q.chunk_src_pos0, q.n_chunks, q.L, q.k_new, q.v_new, q.out,
+                                          q.lse_out, &w.shared, &dl);
+        if (st != FR_OK) {
+            ctx->err = "query " + std::to_string(i) + ": " + ctx->err;
+            return st;
+        }
+        if (q.R == 0) continue;   // nothing to compute for this query
+        w.q_rows = q.q_rows; w.q_index = q.q_index; w.R = q.R; w.L = q.L;
+        w.k_new = q.k_new; w.v_new = q.v_new; w.out = q.out; w.lse = q.lse_out;
+        work.push_back(w);
+        deltas.push_back(dl);
+    }
+    if (work.empty()) return FR_OK;
+    // groups of at most ATTN_MAX_BATCH queries share one attention launch; the groups reuse the workspace (the
+    // stream orders them)
+    for (size_t g0 = 0; g0 < work.size(); g0 += ATTN_MAX_BATCH) {
+        const size_t g1 = std::min(work.size(), g0 + (size_t)ATTN_MAX_BATCH);
+        size_t off = 0;
+        for (size_t i = g0; i < g1; ++i) off = batch_scratch(s, work[i].L, work[i].R, off).end;
+        if ((int64_t)off > workspace_bytes)
+            return fail(ctx, FR_ERR_WORKSPACE, "the batch needs %lld bytes of workspace, %lld given "
+                        "(fr_shared_batch_workspace_bytes gives a sufficient size)", (long long)off, (long long)workspace_bytes);
+    }
+    fr_status st = need_device(ctx);
+    if (st != FR_OK) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    unsigned char* base = static_cast<unsigned char*>(workspace);
+    for (size_t g0 = 0; g0 < work.size(); g0 += ATTN_MAX_BATCH) {
+        const size_t g1 = std::min(work.size(), g0 + (size_t)ATTN_MAX_BATCH);
+        size_t off = 0;
+        for (size_t i = g0; i < g1; ++i) {
+            SharedBatchQuery& w = work[i];
+            const BatchScratch b = batch_scratch(s, w.L, w.R, off);
+            off = b.end;
+            int32_t* inv = reinterpret_cast<int32_t*>(base + b.inv);
+            float2* table = reinterpret_cast<float2*>(base + b.table);
+            hipError_t e = launch_inv_index(w.q_index, w.R, w.L, inv, hs);
+            if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
+            e = launch_rope_table(s, deltas[i], w.shared.ct.n, table, hs);
+            if (e != hipSuccess) return hip_fail(ctx, "rope table launch", e);
+            w.inv = inv;
+            w.shared.table = table;
+            w.store_row_map = reinterpret_cast<int32_t*>(base + b.srow);
+            w.chunk_id_map = reinterpret_cast<int32_t*>(base + b.cid);
+            w.images = base + b.images;
+            w.images_bytes = b.images_bytes;
+            w.flags = reinterpret_cast<int32_t*>(base + b.flags);
+            w.flags_elems = b.flags_elems;
+        }
+        hipError_t e = launch_attn_mfma_shared_batch(s, (int)(g1 - g0), &work[g0], k_store, v_store, ctx->attn_softmax_mode,
+                                                     &ctx->attn_timer, hs);
+        if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
+    }
     return FR_OK;
 }
 

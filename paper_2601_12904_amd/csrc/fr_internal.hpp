@@ -147,6 +147,23 @@ hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q
                             const void* v_new, const int32_t* inv, void* out, float* lse,
                             const Workspace& ws, int softmax_mode, int split_mode, const struct SharedStoreArgs* shared,
                             struct KernelTimer* timer, bool writeback, hipStream_t st);
+// Several queries over one shared chunk store in one attention launch (Sec. 4.3).  Each query brings its scratch:
+// inverse index map, prompt maps, rotation table, tile images and recompute flags (sizes: attn_mfma_images_bytes,
+// attn_mfma_flags_elems).  R > 0 for every query.
+constexpr int ATTN_MAX_BATCH = 16;
+struct SharedBatchQuery {
+    const void* q_rows; const int32_t* q_index; int R; int64_t L;
+    const void* k_new; const void* v_new; void* out; float* lse;
+    SharedStoreArgs shared;          // chunk table, store rows (host), rotation table (device)
+    const int32_t* inv;              // device [L], already built
+    int32_t* store_row_map; int32_t* chunk_id_map;   // device [L] each
+    unsigned char* images; size_t images_bytes;
+    int32_t* flags; size_t flags_elems;
+};
+size_t attn_mfma_images_bytes(const Shape& s, int64_t L);
+size_t attn_mfma_flags_elems(const Shape& s, int64_t R);
+hipError_t launch_attn_mfma_shared_batch(const Shape& s, int n, const SharedBatchQuery* qs, const void* k_store,
+                                         const void* v_store, int softmax_mode, struct KernelTimer* timer, hipStream_t st);
 // The attention launch splits the key range in two on its own up to ATTN_SPLIT_AUTO_ITEMS (row tile, KV head)
 // items (about 1.5 x the 256 CUs: beyond that the items alone keep the chip busy and the partial results' traffic
 // costs more than the better balance gains), and on request (FR_ATTN_SPLIT_ON) up to ATTN_SPLIT_MAX_ITEMS, which

@@ -94,15 +94,15 @@ struct Geometry {
     int n_kt;      // key tiles the workgroup walks
     int n_plain;   // leading tiles whose keys are visible to every row of the workgroup
 
+    // ordinal counts the row tiles of a query from the longest one; ordinal < n_row_tiles
     __device__ __forceinline__ void init(const int32_t* __restrict__ q_index, int R, int Hkv, int n_row_tiles,
-                                         int n_split = 1) {
+                                         int g_, int split_, int ordinal) {
         const int tid = threadIdx.x, lane = tid & 63;
         wave = tid >> 6;
         x = lane & 31;
         h = lane >> 5;
-        g = blockIdx.x % Hkv;                               // consecutive blocks land on different XCDs
-        split = (int)(blockIdx.x / Hkv) % n_split;
-        const int ordinal = (int)(blockIdx.x / (Hkv * n_split));
+        g = g_;
+        split = split_;
         tile = n_row_tiles - 1 - ordinal;                   // longest tiles first
         item = ordinal * Hkv + g;
         row0 = tile * TR;
@@ -518,22 +518,62 @@ __device__ __forceinline__ void store_output(const Geometry<G>& ge, f32x16 (&o)[
 constexpr int PART_REGS = 132;
 constexpr int PART_FLOATS = PART_REGS * 256;
 
+// One launch serves up to ATTN_MAX_BATCH queries with their own rows, index sets, tile images and outputs (Sec. 4.3:
+// queries of a batch share nothing but the chunk store the images were built from).  The table travels as a kernel
+// argument.  blockIdx.x = ((query * max_row_tiles + ordinal) * NS + part) * Hkv + KV head: consecutive blocks land on
+// different XCDs, so with 8 KV heads each XCD's L2 serves the images of one head; the queries follow one another, each
+// with its row tiles longest first, so that the short tiles at the end of one query run beside the long ones of the
+// next and no more than about two queries' images are in use at a time (interleaving the queries was measured: their
+// images then compete for the caches and the batch gains nothing over one launch per query).  A query with fewer row
+// tiles than the longest one leaves its surplus blocks empty.
+struct AttnQuery {
+    const __bf16* q_rows;
+    const int32_t* q_index;
+    const unsigned char* images;
+    __bf16* out;
+    float* lse;
+    int32_t* flags;        // per (row tile, KV head): 1 = redo with a running maximum
+    int R, n_row_tiles, n_img_tiles, pad;
+};
+struct AttnBatch {
+    AttnQuery q[ATTN_MAX_BATCH];
+    int n, max_row_tiles;
+};
+struct BlockWork {
+    int g, split, ordinal, query;
+    __device__ __forceinline__ void init(int max_row_tiles, int n_split, int Hkv) {
+        int t = (int)blockIdx.x;
+        g = t % Hkv; t /= Hkv;
+        split = t % n_split; t /= n_split;
+        ordinal = t % max_row_tiles;
+        query = t / max_row_tiles;
+    }
+};
+
 // ---- fast kernel ---------------------------------------------------------------------------------
 // grid.x = n_row_tiles * Hkv * NS.  Dynamic LDS: the larger of the K/V rings and the epilogue's staging.
 // NS = 1: the workgroup walks all key tiles of its rows and writes the output.  NS = 2 (few row tiles, CUs
 // would idle): it walks one half of them and leaves a partial result; every part uses the same exponent
 // reference (each derives it from the first 32 keys), so the parts simply add up in attn_combine_kernel.
 template <int G, int NS>
-__global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __restrict__ q_rows,
-                                                             const int32_t* __restrict__ q_index, int R,
-                                                             const unsigned char* __restrict__ images, int n_img_tiles,
-                                                             __bf16* __restrict__ out, float* __restrict__ lse_out,
-                                                             int32_t* __restrict__ redo_flags, float* __restrict__ partials,
-                                                             int Hq, int Hkv, int n_row_tiles, float scale_log2e) {
+__global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch batch, float* __restrict__ partials,
+                                                             int Hq, int Hkv, float scale_log2e) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Rings& rg = *reinterpret_cast<Rings*>(smem_raw);
+    BlockWork bw;
+    bw.init(batch.max_row_tiles, NS, Hkv);
+    const AttnQuery& aq = batch.q[bw.query];
+    const int n_row_tiles = aq.n_row_tiles;
+    if (bw.ordinal >= n_row_tiles) return;
+    const __bf16* __restrict__ q_rows = aq.q_rows;
+    const int32_t* __restrict__ q_index = aq.q_index;
+    const unsigned char* __restrict__ images = aq.images;
+    __bf16* __restrict__ out = aq.out;
+    float* __restrict__ lse_out = aq.lse;
+    int32_t* __restrict__ redo_flags = aq.flags;
+    const int R = aq.R, n_img_tiles = aq.n_img_tiles;
     Geometry<G> ge;
-    ge.init(q_index, R, Hkv, n_row_tiles, NS);
+    ge.init(q_index, R, Hkv, n_row_tiles, bw.g, bw.split, bw.ordinal);
     const int x = ge.x, h = ge.h;
     // this workgroup's key tiles [kb, ke)
     const int per_split = (ge.n_kt + NS - 1) / NS;
@@ -678,7 +718,7 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const __bf16* __res
         bad = bad || !(chk < INFINITY) || !(l[nb] > 0.f);
     }
     const int any_bad = __syncthreads_or(bad ? 1 : 0);   // also: every wave is done with the rings
-    if (threadIdx.x == 0) redo_flags[blockIdx.x] = any_bad;
+    if (threadIdx.x == 0) redo_flags[ge.item] = any_bad;
     if (any_bad) return;
     store_output<G>(ge, o, l, mref, R, Hq, smem_raw, out, lse_out);
 }
@@ -692,7 +732,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const int32_t* __rest
                                                            int Hq, int Hkv, int n_row_tiles) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     Geometry<G> ge;
-    ge.init(q_index, R, Hkv, n_row_tiles);
+    ge.init(q_index, R, Hkv, n_row_tiles, (int)blockIdx.x % Hkv, 0, (int)blockIdx.x / Hkv);
     const float* p0 = partials + (size_t)ge.item * 2 * PART_FLOATS + threadIdx.x;
     const float* p1 = p0 + PART_FLOATS;
     f32x16 o[4][2];
@@ -727,19 +767,25 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const int32_t* __rest
 
 // ---- safe kernel: classic online softmax, runs only where the fast kernel raised its flag ----------
 template <int G>
-__global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __restrict__ q_rows,
-                                                               const int32_t* __restrict__ q_index, int R,
-                                                               const unsigned char* __restrict__ images,
-                                                               int n_img_tiles, __bf16* __restrict__ out,
-                                                               float* __restrict__ lse_out,
-                                                               const int32_t* __restrict__ redo_flags, int Hq, int Hkv,
-                                                               int n_row_tiles, float scale_log2e) {
-    if (redo_flags != nullptr && redo_flags[blockIdx.x] == 0) return;
+__global__ __launch_bounds__(256) void attn_running_max_kernel(const AttnBatch batch, int use_flags, int Hq, int Hkv,
+                                                               float scale_log2e) {
+    BlockWork bw;
+    bw.init(batch.max_row_tiles, 1, Hkv);
+    const AttnQuery& aq = batch.q[bw.query];
+    const int n_row_tiles = aq.n_row_tiles;
+    if (bw.ordinal >= n_row_tiles) return;
+    if (use_flags && aq.flags[bw.ordinal * Hkv + bw.g] == 0) return;
+    const __bf16* __restrict__ q_rows = aq.q_rows;
+    const int32_t* __restrict__ q_index = aq.q_index;
+    const unsigned char* __restrict__ images = aq.images;
+    __bf16* __restrict__ out = aq.out;
+    float* __restrict__ lse_out = aq.lse;
+    const int R = aq.R, n_img_tiles = aq.n_img_tiles;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     unsigned char* k_img = smem_raw;
     unsigned char* v_img = smem_raw + K_IMG_BYTES;
     Geometry<G> ge;
-    ge.init(q_index, R, Hkv, n_row_tiles);
+    ge.init(q_index, R, Hkv, n_row_tiles, bw.g, 0, bw.ordinal);
     const int x = ge.x, h = ge.h;
     FragOffsets fo;
     fo.init(x, h);
@@ -805,45 +851,59 @@ __global__ __launch_bounds__(256) void attn_running_max_kernel(const __bf16* __r
     store_output<G>(ge, o, l, m2, R, Hq, smem_raw, out, lse_out);
 }
 
+// Where one query's packing pass leaves its results.
+struct QueryScratch {
+    int32_t* store_row_map;   // [L], shared-store queries only
+    int32_t* chunk_id_map;    // [L], shared-store queries only
+    unsigned char* images;
+    size_t images_bytes;
+    int32_t* flags;
+    size_t flags_elems;
+};
+
 template <int G>
-hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
-                  const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
-                  float* lse, const Workspace& ws, int mode, int split_mode, const SharedStoreArgs* shared,
-                  KernelTimer* timer, bool writeback, hipStream_t st) {
-    const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
-    constexpr int TR = Geometry<G>::TR;
-    const int n_row_tiles = (R + TR - 1) / TR;
-    const int n_img_tiles = (int)((L + KT - 1) / KT);
+hipError_t set_kernel_attributes() {
     const size_t lds_fast = sizeof(Rings) > EPILOGUE_LDS ? sizeof(Rings) : EPILOGUE_LDS;
     const size_t lds_safe = (size_t)IMG_BYTES > EPILOGUE_LDS ? (size_t)IMG_BYTES : EPILOGUE_LDS;
     static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 1>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_combine_kernel<G>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)EPILOGUE_LDS);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_running_max_kernel<G>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_safe);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    dim3 grid(n_row_tiles * s.Hkv), block(256);
-    if ((size_t)grid.x > ws.attn_flags_elems) return hipErrorInvalidValue;
-    if ((size_t)n_img_tiles * s.Hkv * IMG_BYTES > ws.kv_images_bytes) return hipErrorInvalidValue;
+    if (attr_set) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_combine_kernel<G>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)EPILOGUE_LDS);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_running_max_kernel<G>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_safe);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+    return hipSuccess;
+}
+
+// Packing pass of one query: tile images of its effective K/V into sc.images; fills the query's line of the table.
+template <int G>
+hipError_t pack_query(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
+                      const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
+                      float* lse, const QueryScratch& sc, const SharedStoreArgs* shared, bool writeback, AttnQuery* aq,
+                      hipStream_t st) {
+    constexpr int TR = Geometry<G>::TR;
+    const int n_row_tiles = (R + TR - 1) / TR;
+    const int n_img_tiles = (int)((L + KT - 1) / KT);
+    const dim3 block(256);
+    if ((size_t)n_row_tiles * s.Hkv > sc.flags_elems) return hipErrorInvalidValue;
+    if ((size_t)n_img_tiles * s.Hkv * IMG_BYTES > sc.images_bytes) return hipErrorInvalidValue;
     if (shared == nullptr) {
         if (writeback)
             pack_kv_images_kernel<true><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
                 (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
-                k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, ws.kv_images);
+                k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, sc.images);
         else
             pack_kv_images_kernel<false><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
                 (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
-                k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, ws.kv_images);
+                k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, sc.images);
     } else {   // k_cache / v_cache are the shared chunk store
         ChunkRows rows;
         int max_len = (int)L - shared->ct.off[shared->ct.n];
@@ -852,46 +912,103 @@ hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, in
             max_len = std::max(max_len, shared->ct.off[c + 1] - shared->ct.off[c]);
         }
         prompt_map_kernel<<<dim3(std::max(1, (max_len + 255) / 256), shared->ct.n + 1), block, 0, st>>>(
-            shared->ct, rows, (int)L, ws.store_row_map, ws.chunk_id_map);
+            shared->ct, rows, (int)L, sc.store_row_map, sc.chunk_id_map);
         if (s.rope_layout == FR_ROPE_INTERLEAVED)
             pack_kv_images_shared_kernel<FR_ROPE_INTERLEAVED><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
-                (const __bf16*)k_cache, (const __bf16*)v_cache, ws.store_row_map, ws.chunk_id_map, shared->table, (int)L,
-                (const __bf16*)k_new, (const __bf16*)v_new, inv, s.Hkv, n_img_tiles, ws.kv_images);
+                (const __bf16*)k_cache, (const __bf16*)v_cache, sc.store_row_map, sc.chunk_id_map, shared->table, (int)L,
+                (const __bf16*)k_new, (const __bf16*)v_new, inv, s.Hkv, n_img_tiles, sc.images);
         else
             pack_kv_images_shared_kernel<FR_ROPE_HALF><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
-                (const __bf16*)k_cache, (const __bf16*)v_cache, ws.store_row_map, ws.chunk_id_map, shared->table, (int)L,
-                (const __bf16*)k_new, (const __bf16*)v_new, inv, s.Hkv, n_img_tiles, ws.kv_images);
+                (const __bf16*)k_cache, (const __bf16*)v_cache, sc.store_row_map, sc.chunk_id_map, shared->table, (int)L,
+                (const __bf16*)k_new, (const __bf16*)v_new, inv, s.Hkv, n_img_tiles, sc.images);
     }
-    const int32_t* flags = ws.attn_flags;
+    aq->q_rows = (const __bf16*)q_rows;
+    aq->q_index = q_index;
+    aq->images = sc.images;
+    aq->out = (__bf16*)out;
+    aq->lse = lse;
+    aq->flags = sc.flags;
+    aq->R = R;
+    aq->n_row_tiles = n_row_tiles;
+    aq->n_img_tiles = n_img_tiles;
+    aq->pad = 0;
+    return hipGetLastError();
+}
+
+// The attention launches over the packed queries of `batch`.
+template <int G>
+hipError_t run_batch(const Shape& s, AttnBatch& batch, float* partials, size_t partials_bytes, int mode,
+                     int split_mode, KernelTimer* timer, hipStream_t st) {
+    const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
+    const size_t lds_fast = sizeof(Rings) > EPILOGUE_LDS ? sizeof(Rings) : EPILOGUE_LDS;
+    const size_t lds_safe = (size_t)IMG_BYTES > EPILOGUE_LDS ? (size_t)IMG_BYTES : EPILOGUE_LDS;
+    int max_row_tiles = 0, max_img_tiles = 0;
+    for (int i = 0; i < batch.n; ++i) {
+        max_row_tiles = std::max(max_row_tiles, batch.q[i].n_row_tiles);
+        max_img_tiles = std::max(max_img_tiles, batch.q[i].n_img_tiles);
+    }
+    batch.max_row_tiles = max_row_tiles;
+    const dim3 grid(max_row_tiles * batch.n * s.Hkv), block(256);
     // Few (row tile, KV head) items: the chip would idle behind the longest ones, so each is walked by two
-    // workgroups.  Not worth the partial results' traffic once the items alone fill the CUs, nor for short prompts.
+    // workgroups.  Not worth the partial results' traffic once the items alone fill the CUs, nor for short prompts;
+    // a batch of queries fills the chip by itself.
     // (Letting the part that finishes last add the other's sums inside the same kernel was measured too: the
     // device-scope fences it needs write back and invalidate the whole L2 at every arrival and cost 110 us.)
-    const bool fits = (size_t)grid.x * 2 * PART_FLOATS * sizeof(float) <= ws.attn_partials_bytes;
+    const bool fits = batch.n == 1 && (size_t)grid.x * 2 * PART_FLOATS * sizeof(float) <= partials_bytes;
     const bool split = fits && (split_mode == FR_ATTN_SPLIT_ON ||
-                                (split_mode == FR_ATTN_SPLIT_AUTO && (int)grid.x <= ATTN_SPLIT_AUTO_ITEMS && n_img_tiles >= 32));
+                                (split_mode == FR_ATTN_SPLIT_AUTO && (int)grid.x <= ATTN_SPLIT_AUTO_ITEMS && max_img_tiles >= 32));
     const bool timed = timer != nullptr && timer->n_slots > 0 && mode != FR_ATTN_SOFTMAX_RUNNING_MAX;
     const int slot = timed ? (int)(timer->n_recorded % timer->n_slots) : 0;
     if (timed && hipEventRecord(timer->start[slot], st) != hipSuccess) return hipGetLastError();
+    int use_flags = 1;
     if (mode == FR_ATTN_SOFTMAX_RUNNING_MAX) {
-        flags = nullptr;   // recompute every workgroup with the running maximum
+        use_flags = 0;   // recompute every workgroup with the running maximum
     } else if (split) {
-        attn_fixed_ref_kernel<G, 2><<<dim3(grid.x * 2), block, lds_fast, st>>>(
-            (const __bf16*)q_rows, q_index, R, ws.kv_images, n_img_tiles, (__bf16*)out, lse, ws.attn_flags,
-            ws.attn_partials, s.Hq, s.Hkv, n_row_tiles, scale_log2e);
+        attn_fixed_ref_kernel<G, 2><<<dim3(grid.x * 2), block, lds_fast, st>>>(batch, partials, s.Hq, s.Hkv, scale_log2e);
         if (timed) { (void)hipEventRecord(timer->stop[slot], st); ++timer->n_recorded; }
-        attn_combine_kernel<G><<<grid, block, EPILOGUE_LDS, st>>>(q_index, R, ws.attn_partials, (__bf16*)out, lse,
-                                                                  ws.attn_flags, s.Hq, s.Hkv, n_row_tiles);
+        const AttnQuery& q0 = batch.q[0];
+        attn_combine_kernel<G><<<grid, block, EPILOGUE_LDS, st>>>(q0.q_index, q0.R, partials, q0.out, q0.lse, q0.flags,
+                                                                  s.Hq, s.Hkv, q0.n_row_tiles);
     } else {
-        attn_fixed_ref_kernel<G, 1><<<grid, block, lds_fast, st>>>((const __bf16*)q_rows, q_index, R, ws.kv_images,
-                                                                   n_img_tiles, (__bf16*)out, lse, ws.attn_flags, nullptr,
-                                                                   s.Hq, s.Hkv, n_row_tiles, scale_log2e);
+        attn_fixed_ref_kernel<G, 1><<<grid, block, lds_fast, st>>>(batch, nullptr, s.Hq, s.Hkv, scale_log2e);
         if (timed) { (void)hipEventRecord(timer->stop[slot], st); ++timer->n_recorded; }
     }
-    attn_running_max_kernel<G><<<grid, block, lds_safe, st>>>((const __bf16*)q_rows, q_index, R, ws.kv_images,
-                                                              n_img_tiles, (__bf16*)out, lse, flags, s.Hq, s.Hkv,
-                                                              n_row_tiles, scale_log2e);
+    attn_running_max_kernel<G><<<grid, block, lds_safe, st>>>(batch, use_flags, s.Hq, s.Hkv, scale_log2e);
     return hipGetLastError();
+}
+
+template <int G>
+hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
+                  const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
+                  float* lse, const Workspace& ws, int mode, int split_mode, const SharedStoreArgs* shared,
+                  KernelTimer* timer, bool writeback, hipStream_t st) {
+    hipError_t e = set_kernel_attributes<G>();
+    if (e != hipSuccess) return e;
+    const QueryScratch sc{ws.store_row_map, ws.chunk_id_map, ws.kv_images, ws.kv_images_bytes, ws.attn_flags,
+                          ws.attn_flags_elems};
+    AttnBatch batch;
+    batch.n = 1;
+    e = pack_query<G>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, sc, shared, writeback,
+                      &batch.q[0], st);
+    if (e != hipSuccess) return e;
+    return run_batch<G>(s, batch, ws.attn_partials, ws.attn_partials_bytes, mode, split_mode, timer, st);
+}
+
+template <int G>
+hipError_t launch_shared_batch(const Shape& s, int n, const SharedBatchQuery* qs, const void* k_store,
+                               const void* v_store, int mode, KernelTimer* timer, hipStream_t st) {
+    hipError_t e = set_kernel_attributes<G>();
+    if (e != hipSuccess) return e;
+    AttnBatch batch;
+    batch.n = n;
+    for (int i = 0; i < n; ++i) {
+        const SharedBatchQuery& q = qs[i];
+        const QueryScratch sc{q.store_row_map, q.chunk_id_map, q.images, q.images_bytes, q.flags, q.flags_elems};
+        e = pack_query<G>(s, q.q_rows, q.q_index, q.R, k_store, v_store, q.L, q.k_new, q.v_new, q.inv, q.out, q.lse, sc,
+                          &q.shared, false, &batch.q[i], st);
+        if (e != hipSuccess) return e;
+    }
+    return run_batch<G>(s, batch, nullptr, 0, mode, FR_ATTN_SPLIT_OFF, timer, st);
 }
 
 }  // namespace
@@ -917,6 +1034,21 @@ hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q
         case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
         case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
         default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
+    }
+}
+
+size_t attn_mfma_images_bytes(const Shape& s, int64_t L) { return (size_t)((L + KT - 1) / KT) * s.Hkv * IMG_BYTES; }
+size_t attn_mfma_flags_elems(const Shape& s, int64_t R) { return (size_t)(R / 32 + 1) * s.Hkv; }
+
+hipError_t launch_attn_mfma_shared_batch(const Shape& s, int n, const SharedBatchQuery* qs, const void* k_store,
+                                         const void* v_store, int mode, KernelTimer* timer, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    if (n > ATTN_MAX_BATCH) return hipErrorInvalidValue;
+    switch (s.G) {
+        case 1: return launch_shared_batch<1>(s, n, qs, k_store, v_store, mode, timer, st);
+        case 2: return launch_shared_batch<2>(s, n, qs, k_store, v_store, mode, timer, st);
+        case 4: return launch_shared_batch<4>(s, n, qs, k_store, v_store, mode, timer, st);
+        default: return launch_shared_batch<8>(s, n, qs, k_store, v_store, mode, timer, st);
     }
 }
 

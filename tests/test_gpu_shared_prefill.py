@@ -81,3 +81,69 @@ def test_shared_store_prefill_argument_errors():
         c32.fr_sparse_prefill_attn_shared(P, P, 5, P, P, 100, [0, 8, 16], [0, 8], [0, 0], 20, P, P, P)
     assert ei.value.status == B.FR_ERR_UNSUPPORTED
     c32.close()
+
+
+def test_shared_store_prefill_batch_of_queries():
+    """Several queries over one chunk store in one call (Sec. 4.3): different chunk subsets and orders, lengths, ratios
+    and index sets (one query recomputes nothing, one has no rows at all).  Each query's output equals the one-query
+    entry point's bit for bit (same kernels, same summation order with the key-range split off) and the oracle's
+    within the bf16 tolerance."""
+    dt, tdt = "bf16", torch.bfloat16
+    rng = np.random.default_rng(11)
+    base = synth.config_small_bf16(seed=5, chunk_lens=(200, 64, 333, 91, 256, 130))
+    Hq, Hkv, d = base.shape.n_q_heads, base.shape.n_kv_heads, base.shape.head_dim
+    k_store, v_store, row0_all = scattered_store(base, rng)
+    ks_d, vs_d = H.dev(k_store, dt), H.dev(v_store, dt)
+    chunk_len = np.diff(base.chunk_offsets)
+    ctx = H.make_ctx(base.shape, base.L + 64, base.n_chunks, base.nq)
+    ctx.fr_set_option(B.FR_OPT_ATTN_SPLIT, B.FR_ATTN_SPLIT_OFF)
+    plans = [((0, 2, 4), 0.15, base.nq), ((5, 1), 0.0, 7), ((3, 0, 1, 2, 4, 5), 0.4, 33), ((2,), 1.0, 1), ((4, 3), 0.15, 0)]
+    queries, keep = [], []
+    for chunks, ratio, nq in plans:
+        lens = [int(chunk_len[c]) for c in chunks]
+        offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        L_ctx = int(offs[-1]); L = L_ctx + nq
+        src_pos0 = rng.integers(0, 3000, size=len(chunks)).astype(np.int32)
+        k = orc.topk_count(L_ctx, ratio) if nq > 0 else 0
+        qi = np.concatenate([np.sort(rng.choice(L_ctx, size=k, replace=False)), L_ctx + np.arange(nq)]).astype(np.int64)
+        R = len(qi)
+        mk = lambda n, heads, scale: synth.round_to_storage((scale * rng.standard_normal((n, heads, d))).astype(np.float32), dt)
+        q_rows, k_new, v_new = mk(R, Hq, 1.0), mk(R, Hkv, 1.0), mk(R, Hkv, 1.0)
+        k_cached = np.concatenate([base.k_cached[base.chunk_offsets[c]:base.chunk_offsets[c + 1]] for c in chunks])
+        v_cached = np.concatenate([base.v_cached[base.chunk_offsets[c]:base.chunk_offsets[c + 1]] for c in chunks])
+        q = dict(q_rows=H.dev(q_rows, dt), q_index=torch.from_numpy(qi.astype(np.int32)).cuda(), R=R, chunk_offsets=offs,
+                 chunk_store_row0=row0_all[list(chunks)], chunk_src_pos0=src_pos0, L=L, k_new=H.dev(k_new, dt),
+                 v_new=H.dev(v_new, dt), out=torch.zeros((R, Hq, d), dtype=tdt, device="cuda"),
+                 lse_out=torch.zeros((R, Hq), dtype=torch.float32, device="cuda"))
+        queries.append(q)
+        keep.append((qi, q_rows, k_new, v_new, k_cached, v_cached, offs, src_pos0, nq))
+    n_ws = ctx.fr_shared_batch_workspace_bytes(len(queries), max(q["L"] for q in queries))
+    assert n_ws > 0
+    ws = torch.empty(n_ws, dtype=torch.uint8, device="cuda")
+    ctx.fr_sparse_prefill_attn_shared_batch(queries, ks_d, vs_d, len(k_store), ws)
+    torch.cuda.synchronize()
+    for q, (qi, q_rows, k_new, v_new, k_cached, v_cached, offs, src_pos0, nq) in zip(queries, keep):
+        R = q["R"]
+        if R == 0:
+            continue
+        single = torch.zeros_like(q["out"])
+        single_lse = torch.zeros_like(q["lse_out"])
+        ctx.fr_sparse_prefill_attn_shared(q["q_rows"], q["q_index"], R, ks_d, vs_d, len(k_store), offs, q["chunk_store_row0"],
+                                          src_pos0, q["L"], q["k_new"], q["v_new"], single, single_lse)
+        torch.cuda.synchronize()
+        assert torch.equal(single, q["out"]) and torch.equal(single_lse, q["lse_out"])
+        k_ctx = synth.round_to_storage(orc.rope_shift(k_cached, offs, src_pos0, None, base.shape.rope_base, "interleaved"), dt)
+        pad = np.zeros((nq, Hkv, d))
+        want, want_lse = orc.sparse_prefill_attn(q_rows, qi, np.concatenate([k_ctx, pad]), np.concatenate([v_cached, pad]),
+                                                 k_new, v_new)
+        H.assert_close(H.host(q["out"]), want, dt, "batched shared-store attention")
+        assert np.max(np.abs(q["lse_out"].cpu().numpy() - want_lse)) <= 2e-3
+    # too small a workspace, and a bad query, are refused before anything runs
+    with pytest.raises(B.FusionRAGError) as ei:
+        ctx.fr_sparse_prefill_attn_shared_batch(queries, ks_d, vs_d, len(k_store), ws, workspace_bytes=4096)
+    assert ei.value.status == B.FR_ERR_WORKSPACE
+    bad = dict(queries[0]); bad["chunk_store_row0"] = np.array([len(k_store)] * 3, dtype=np.int32)
+    with pytest.raises(B.FusionRAGError) as ei:
+        ctx.fr_sparse_prefill_attn_shared_batch([queries[1], bad], ks_d, vs_d, len(k_store), ws)
+    assert "query 1" in str(ei.value)
+    ctx.close()
