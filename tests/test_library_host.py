@@ -151,3 +151,30 @@ def test_valid_call_without_gpu_reports_device_error(ctx):
     expect(B.FR_ERR_DEVICE, ctx.fr_decode_attn, P, 2, P, P, 100, P, P, P, P, 3, P, 4, P, P, 64, P, P)
     expect(B.FR_ERR_DEVICE, ctx.fr_mark_stale_rows, P, 4, P, 3)
     assert ctx.workspace_bytes() == 0
+
+
+def test_shared_batch_argument_errors():
+    """fr_sparse_prefill_attn_shared_batch validates every query on the host before the first launch."""
+    import torch
+    c = B.Context(32, 8, 128, B.FR_BF16, 5e5, max_tokens=600, max_chunks=4, max_question_tokens=32)
+    P = 4096
+    q = dict(q_rows=P, q_index=P, R=5, chunk_offsets=[0, 8, 16], chunk_store_row0=[0, 8], chunk_src_pos0=[0, 0], L=20,
+             k_new=P, v_new=P, out=P)
+    need = c.fr_shared_batch_workspace_bytes(2, 20)
+    assert need > 0 and need % 256 == 0
+    assert c.fr_shared_batch_workspace_bytes(0, 20) == 0
+    assert c.fr_shared_batch_workspace_bytes(40, 20) == 8 * need      # groups of 16 reuse the workspace
+    c.fr_sparse_prefill_attn_shared_batch([], P, P, 100, None, 0)     # no queries: nothing to do
+    expect(B.FR_ERR_WORKSPACE, c.fr_sparse_prefill_attn_shared_batch, [q, q], P, P, 100, P, 512)
+    expect(B.FR_ERR_INVALID_ARG, c.fr_sparse_prefill_attn_shared_batch, [q], P, P, 100, P + 16, need)   # workspace alignment
+    bad = dict(q, chunk_store_row0=[0, 96])                            # second chunk reaches past the store
+    with pytest.raises(B.FusionRAGError) as ei:
+        c.fr_sparse_prefill_attn_shared_batch([q, bad], P, P, 100, P, need)
+    assert ei.value.status == B.FR_ERR_INVALID_ARG and "query 1" in str(ei.value)
+    expect(B.FR_ERR_WORKSPACE, c.fr_sparse_prefill_attn_shared_batch, [dict(q, L=601)], P, P, 100, P, need)
+    expect(B.FR_ERR_INVALID_ARG, c.fr_sparse_prefill_attn_shared_batch, [dict(q, k_new=None)], P, P, 100, P, need)
+    empty = dict(q, R=0)
+    c.fr_sparse_prefill_attn_shared_batch([empty, empty], P, P, 100, None, 0)   # no rows anywhere: nothing to do
+    if not torch.cuda.is_available():
+        expect(B.FR_ERR_DEVICE, c.fr_sparse_prefill_attn_shared_batch, [q, q], P, P, 100, P, need)
+    c.close()
