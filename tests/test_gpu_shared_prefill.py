@@ -147,3 +147,47 @@ def test_shared_store_prefill_batch_of_queries():
         ctx.fr_sparse_prefill_attn_shared_batch([queries[1], bad], ks_d, vs_d, len(k_store), ws)
     assert "query 1" in str(ei.value)
     ctx.close()
+
+
+def test_shared_store_batch_full_size_sampled():
+    """The launch configuration `bench.py --config 8` times (Llama-3-8B layer shape, queries of 16 chunks x 1024 tokens
+    drawn from a 32-chunk store, 512 question tokens, 15 %), three queries per call: sampled output rows against the
+    oracle, which forms each sampled row over the query's effective K/V."""
+    shape = synth.LLAMA3_8B_BF16
+    Hq, Hkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    dt, tdt = "bf16", torch.bfloat16
+    nb, n_store_chunks, cpq, clen, nq, ratio = 3, 32, 16, 1024, 512, 0.15
+    L_ctx, L = cpq * clen, cpq * clen + nq
+    rng = np.random.default_rng(21)
+    sig = 1.0 / np.sqrt(d)
+    N = n_store_chunks * clen
+    mk = lambda n, heads, scale: synth.round_to_storage((scale * rng.standard_normal((n, heads, d))).astype(np.float32), dt)
+    k_store, v_store = mk(N, Hkv, sig), mk(N, Hkv, sig)
+    ks_d, vs_d = H.dev(k_store, dt), H.dev(v_store, dt)
+    k_sel = orc.topk_count(L_ctx, ratio)
+    R = k_sel + nq
+    offs = np.arange(0, L_ctx + 1, clen, dtype=np.int32)
+    ctx = H.make_ctx(shape, L, cpq, nq)
+    queries, keep = [], []
+    for b in range(nb):
+        ids = rng.choice(n_store_chunks, size=cpq, replace=False)
+        row0 = (ids * clen).astype(np.int32)
+        src = rng.integers(0, 4096, size=cpq).astype(np.int32)
+        qi = np.concatenate([np.sort(rng.choice(L_ctx, size=k_sel, replace=False)), L_ctx + np.arange(nq)]).astype(np.int64)
+        q_rows, k_new, v_new = mk(R, Hq, np.sqrt(d)), mk(R, Hkv, sig), mk(R, Hkv, sig)
+        queries.append(dict(q_rows=H.dev(q_rows, dt), q_index=torch.from_numpy(qi.astype(np.int32)).cuda(), R=R,
+                            chunk_offsets=offs, chunk_store_row0=row0, chunk_src_pos0=src, L=L, k_new=H.dev(k_new, dt),
+                            v_new=H.dev(v_new, dt), out=torch.zeros((R, Hq, d), dtype=tdt, device="cuda")))
+        keep.append((ids, src, qi, q_rows, k_new, v_new))
+    ws = torch.empty(ctx.fr_shared_batch_workspace_bytes(nb, L), dtype=torch.uint8, device="cuda")
+    ctx.fr_sparse_prefill_attn_shared_batch(queries, ks_d, vs_d, N, ws)
+    torch.cuda.synchronize()
+    for q, (ids, src, qi, q_rows, k_new, v_new) in zip(queries, keep):
+        gather = np.concatenate([np.arange(i * clen, (i + 1) * clen) for i in ids])
+        k_ctx = synth.round_to_storage(orc.rope_shift(k_store[gather], offs, src, None, shape.rope_base, "interleaved"), dt)
+        pad = np.zeros((nq, Hkv, d))
+        rows = np.unique(np.concatenate([[0, R - 1], rng.choice(R, size=30, replace=False)]))
+        want, _ = orc.sparse_prefill_attn(q_rows, qi, np.concatenate([k_ctx, pad]), np.concatenate([v_store[gather], pad]),
+                                          k_new, v_new, rows=rows)
+        H.assert_close(H.host(q["out"][torch.from_numpy(rows).cuda()]), want, dt, "sampled rows of the batched launch")
+    ctx.close()
