@@ -98,11 +98,14 @@ int64_t fr_workspace_bytes(const fr_ctx* ctx);
  * head_dim 128); GENERIC forces the all-vector-ALU kernel that every other shape uses (so that tests reach both).
  * FR_OPT_GEMM_TILE: output features per workgroup of the projection kernels, 0 (default: 256 where the feature count
  * is a multiple of 256, else 128), 128 or 256; process-wide, for tests and tuning.
+ * FR_OPT_GEMM_TAIL_SPLIT: 1 (default): when the output tiles of a projection do not fill the last round of
+ * workgroups (one per CU), the tiles of that round are split along K over several workgroups each and a second small
+ * kernel adds the parts; 0: never.  Same results up to fp32 summation order; process-wide, for tests and tuning.
  * FR_OPT_ATTN_KERNEL_TIMER: value n in [0, 256]: the tiled attention launch records an event pair on its stream around
  * its dominant kernel (the key-tile loop) and keeps the last n pairs; 0 (default) switches the timer off.  Read
  * with fr_attn_kernel_times.  For benchmarks: the events see one kernel, not the whole call. */
 typedef enum { FR_OPT_ATTN_SOFTMAX = 1, FR_OPT_ATTN_SPLIT = 2, FR_OPT_DECODE_KERNEL = 3, FR_OPT_GEMM_TILE = 4,
-               FR_OPT_ATTN_KERNEL_TIMER = 5 } fr_option;
+               FR_OPT_ATTN_KERNEL_TIMER = 5, FR_OPT_GEMM_TAIL_SPLIT = 6 } fr_option;
 typedef enum { FR_DECODE_KERNEL_AUTO = 0, FR_DECODE_KERNEL_GENERIC = 1 } fr_decode_kernel;
 typedef enum { FR_ATTN_SOFTMAX_AUTO = 0, FR_ATTN_SOFTMAX_RUNNING_MAX = 1 } fr_attn_softmax;
 typedef enum { FR_ATTN_SPLIT_AUTO = 0, FR_ATTN_SPLIT_OFF = 1, FR_ATTN_SPLIT_ON = 2 } fr_attn_split;

@@ -23,6 +23,7 @@ FR_OPT_ATTN_SOFTMAX = 1
 FR_OPT_ATTN_SPLIT = 2
 FR_OPT_DECODE_KERNEL = 3
 FR_OPT_GEMM_TILE = 4
+FR_OPT_GEMM_TAIL_SPLIT = 6
 FR_OPT_ATTN_KERNEL_TIMER = 5
 FR_DECODE_KERNEL_AUTO, FR_DECODE_KERNEL_GENERIC = 0, 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1

@@ -147,6 +147,8 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_dpart = take(decode_partials_bytes(s));
     const size_t o_drot = take(decode_rot_table_bytes(s));
     const size_t o_rr = take((size_t)max_tokens * (s.d / 2) * sizeof(float2));
+    w.gemm_partials_bytes = (s.dtype == FR_BF16) ? gemm_partials_bytes() : 0;
+    const size_t o_gp = take(w.gemm_partials_bytes);
     w.bytes = off;
     hipError_t e = hipMalloc((void**)&w.base, w.bytes);
     if (e != hipSuccess) {
@@ -168,6 +170,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.decode_partials = (float*)(w.base + o_dpart);
     w.decode_rot = (float2*)(w.base + o_drot);
     w.rope_rows = (float2*)(w.base + o_rr);
+    w.gemm_partials = w.gemm_partials_bytes ? (float*)(w.base + o_gp) : nullptr;
     ctx->has_device = true;
     *out = ctx;
     return FR_OK;
@@ -220,6 +223,11 @@ fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value) {
             if (value != 0 && value != 128 && value != 256)
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_GEMM_TILE: %lld is not 0, 128 or 256", (long long)value);
             launch_gemm_set_tile((int)value);
+            return FR_OK;
+        case FR_OPT_GEMM_TAIL_SPLIT:
+            if (value != 0 && value != 1)
+                return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_GEMM_TAIL_SPLIT: %lld is not 0 or 1", (long long)value);
+            launch_gemm_set_split((int)value);
             return FR_OK;
         case FR_OPT_ATTN_SPLIT:
             if (value != FR_ATTN_SPLIT_AUTO && value != FR_ATTN_SPLIT_OFF && value != FR_ATTN_SPLIT_ON)
@@ -736,7 +744,7 @@ fr_status fr_linear(fr_ctx* ctx, const void* a, const void* w, int32_t M, int32_
     if (!out || !aligned16(out) || !aligned16(residual))
         return fail(ctx, FR_ERR_INVALID_ARG, "fr_linear: out is NULL or out / residual not 16-byte aligned");
     if ((st = need_device(ctx)) != FR_OK) return st;
-    hipError_t e = launch_linear(a, w, M, N, K, residual, out, (hipStream_t)stream);
+    hipError_t e = launch_linear(a, w, M, N, K, residual, out, ctx->ws.gemm_partials, ctx->ws.gemm_partials_bytes, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "linear launch", e);
     return FR_OK;
 }
@@ -751,7 +759,7 @@ fr_status fr_linear_swiglu(fr_ctx* ctx, const void* a, const void* w_gate_up, in
     if (M == 0) return FR_OK;
     if (!out || !aligned16(out)) return fail(ctx, FR_ERR_INVALID_ARG, "fr_linear_swiglu: out is NULL or misaligned");
     if ((st = need_device(ctx)) != FR_OK) return st;
-    hipError_t e = launch_linear_swiglu(a, w_gate_up, M, F, K, out, (hipStream_t)stream);
+    hipError_t e = launch_linear_swiglu(a, w_gate_up, M, F, K, out, ctx->ws.gemm_partials, ctx->ws.gemm_partials_bytes, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "swiglu launch", e);
     return FR_OK;
 }
@@ -771,7 +779,8 @@ fr_status fr_qkv_rope(fr_ctx* ctx, const void* a, const void* w_qkv, int32_t M, 
         (reinterpret_cast<uintptr_t>(positions) & 3u))
         return fail(ctx, FR_ERR_INVALID_ARG, "fr_qkv_rope: positions / q_out / k_out / v_out is NULL or misaligned");
     if ((st = need_device(ctx)) != FR_OK) return st;
-    hipError_t e = launch_qkv_rope(s, a, w_qkv, M, K, positions, ctx->ws.rope_rows, q_out, k_out, v_out, (hipStream_t)stream);
+    hipError_t e = launch_qkv_rope(s, a, w_qkv, M, K, positions, ctx->ws.rope_rows, q_out, k_out, v_out, ctx->ws.gemm_partials,
+                                   ctx->ws.gemm_partials_bytes, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "qkv launch", e);
     return FR_OK;
 }

@@ -43,6 +43,8 @@ struct Workspace {
     float* qsum = nullptr;              // [Hkv][d] question queries summed per KV head (raw scores), then partial sums
     uint32_t* select_tmp = nullptr; // state, histogram, per-wave counts and candidate list of the selection kernels
     int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
+    float* gemm_partials = nullptr; // partial sums of the GEMM tiles that are split along K
+    size_t gemm_partials_bytes = 0;
     size_t attn_flags_elems = 0;
     float2* rope_rows = nullptr;    // [max_tokens][d/2] (cos, sin) of the recomputed rows' positions
     float* decode_partials = nullptr;    // [DECODE_MAX_UNITS][Hq][d + 2] partial softmax results of fr_decode_attn
@@ -173,11 +175,17 @@ constexpr int ATTN_SPLIT_MAX_ITEMS = 768;
 size_t attn_mfma_partials_bytes(const Shape& s, int64_t max_tokens);
 
 void launch_gemm_set_tile(int features_per_workgroup);   // 0 = choose, 128, 256
+void launch_gemm_set_split(int on);                      // 0 = the last round's tiles are never split along K
+// `partials` (gemm_partials_bytes() bytes, or NULL: no split) holds the partial sums of the tiles of a launch's last,
+// partly filled round, which are computed by several workgroups each.
+size_t gemm_partials_bytes();
 hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
-                         hipStream_t st);
-hipError_t launch_linear_swiglu(const void* a, const void* w_gate_up, int M, int F, int K, void* out, hipStream_t st);
+                         float* partials, size_t partials_bytes, hipStream_t st);
+hipError_t launch_linear_swiglu(const void* a, const void* w_gate_up, int M, int F, int K, void* out, float* partials,
+                                size_t partials_bytes, hipStream_t st);
 hipError_t launch_qkv_rope(const Shape& s, const void* a, const void* w_qkv, int M, int K, const int32_t* positions,
-                           float2* rope_rows, void* q_out, void* k_out, void* v_out, hipStream_t st);
+                           float2* rope_rows, void* q_out, void* k_out, void* v_out, float* partials,
+                           size_t partials_bytes, hipStream_t st);
 hipError_t launch_rmsnorm(const void* x, const void* gain, int R, int hidden, float eps, void* out, hipStream_t st);
 
 // ---- element helpers (device) ------------------------------------------------------------

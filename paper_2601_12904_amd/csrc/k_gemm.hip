@@ -15,6 +15,8 @@
 // of any 16 consecutive rows then fall into 16 distinct bank groups.
 #include "fr_internal.hpp"
 
+#include <algorithm>
+
 namespace fr {
 
 namespace {
@@ -87,7 +89,15 @@ struct GemmArgs {
     __bf16 *q_out, *k_out, *v_out;
     const float2* rope;     // [M][d / 2] (cos, sin) of each row's position
     int Hq, Hkv, d;
+    // Tail split.  Tiles [0, n_whole) are computed by one workgroup each; every later tile by n_parts workgroups that
+    // walk 1 / n_parts of K each and leave their fp32 accumulators in `partials` (gemm_fixup_kernel adds them and
+    // runs the epilogue).  n_parts = 1: no tile is split.
+    int n_whole, n_parts;
+    float* partials;        // [(tile - n_whole) * n_parts + part][wave][64 registers][64 lanes]
+    size_t partials_bytes;  // (host side: what the buffer holds)
 };
+constexpr int PARTIAL_FLOATS_PER_WAVE = 64 * 64;
+constexpr int MIN_K_TILES_PER_PART = 96;
 
 // Epilogue shared by the kernels: this wave's fp32 64 x 64 tile goes through LDS ([row][feature]), then every lane
 // handles 8 consecutive features of a row.  fw0 / rw0 = first feature / row of the wave's tile.
@@ -166,7 +176,6 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, f32x16 (&acc)[2
     }
 }
 
-// grid.x = feature tiles (fastest), grid.y = row tiles: workgroups that share an activation tile are neighbours.
 template <int EPI, int WF>
 __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
     using TL = Tiling<WF>;
@@ -175,8 +184,20 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int wf = wave % WF, wr = wave / WF;          // wave position: features x rows
-    const int f0 = blockIdx.x * BF, r0 = blockIdx.y * BR;
-    const int n_kt = g.K / BK;
+    // tile order: feature tiles fastest, so that workgroups that share an activation tile are neighbours
+    const int n_ftiles = (g.N + BF - 1) / BF;
+    int tile = (int)blockIdx.x, part = 0;
+    if (tile >= g.n_whole) {
+        const int j = tile - g.n_whole;
+        tile = g.n_whole + j / g.n_parts;
+        part = j % g.n_parts;
+    }
+    const bool split_tile = (int)blockIdx.x >= g.n_whole && g.n_parts > 1;
+    const int f0 = (tile % n_ftiles) * BF, r0 = (tile / n_ftiles) * BR;
+    const int n_kt_all = g.K / BK;
+    const int kt_begin = split_tile ? (int)((int64_t)n_kt_all * part / g.n_parts) : 0;
+    const int kt_end = split_tile ? (int)((int64_t)n_kt_all * (part + 1) / g.n_parts) : n_kt_all;
+    const int n_kt = kt_end - kt_begin;   // K tiles of this workgroup: kt below counts from kt_begin
 
     // fragment byte offsets inside a tile: row (32 blk + x) of this wave's half, k step ks -> chunk (2 ks + h)
     int frag[4][2];   // [ks][blk & 1]
@@ -197,8 +218,8 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
 
     auto issue = [&](int kt) {
         unsigned char* st = smem + (kt % N_STAGE) * STAGE_BYTES;
-        dma_tile<TL::W_ROUNDS, NW>(g.w, g.K, f0, g.N, kt * BK, st, wave, lane);
-        dma_tile<TL::A_ROUNDS, NW>(g.a, g.K, r0, g.M, kt * BK, st + TL::W_TILE_BYTES, wave, lane);
+        dma_tile<TL::W_ROUNDS, NW>(g.w, g.K, f0, g.N, (kt_begin + kt) * BK, st, wave, lane);
+        dma_tile<TL::A_ROUNDS, NW>(g.a, g.K, r0, g.M, (kt_begin + kt) * BK, st + TL::W_TILE_BYTES, wave, lane);
     };
 #pragma unroll
     for (int p = 0; p < N_STAGE - 1; ++p)
@@ -243,6 +264,46 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
         }
     }
 
+    if (split_tile) {   // leave the partial sums: register-major, one coalesced 256-byte line per wave and register
+        float* dst = g.partials + ((size_t)(((int)blockIdx.x - g.n_whole) * NW + wave)) * PARTIAL_FLOATS_PER_WAVE + lane;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) dst[((2 * mb + nb) * 16 + v) * 64] = acc[mb][nb][v];
+        return;
+    }
+    gemm_epilogue<EPI>(g, acc, smem, wave, lane, f0 + 64 * wf, r0 + 64 * wr);
+}
+
+// Adds the n_parts partial sums of every split tile and runs the epilogue on the result.  grid.x = split tiles.
+template <int EPI, int WF>
+__global__ __launch_bounds__(128 * WF) void gemm_fixup_kernel(GemmArgs g) {
+    using TL = Tiling<WF>;
+    constexpr int NW = TL::NW, BF = TL::BF;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wf = wave % WF, wr = wave / WF;
+    const int n_ftiles = (g.N + BF - 1) / BF;
+    const int tile = g.n_whole + (int)blockIdx.x;
+    const int f0 = (tile % n_ftiles) * BF, r0 = (tile / n_ftiles) * BR;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+    for (int p = 0; p < g.n_parts; ++p) {
+        const float* src = g.partials + ((size_t)(((int)blockIdx.x * g.n_parts + p) * NW + wave)) * PARTIAL_FLOATS_PER_WAVE + lane;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mb][nb][v] += src[((2 * mb + nb) * 16 + v) * 64];
+    }
     gemm_epilogue<EPI>(g, acc, smem, wave, lane, f0 + 64 * wf, r0 + 64 * wr);
 }
 
@@ -284,18 +345,44 @@ __global__ void rope_rows_table_kernel(const int32_t* __restrict__ positions, in
 
 int g_gemm_tile = 0;   // 0: choose; 128 / 256: features per workgroup (set through launch_gemm_set_tile, for tests)
 
+int g_gemm_split = 1;               // 0: never split the tail (for tests)
+
 template <int EPI, int WF>
-hipError_t launch_gemm_wf(const GemmArgs& g, hipStream_t st) {
+hipError_t launch_gemm_wf(GemmArgs g, hipStream_t st) {
     using TL = Tiling<WF>;
     static bool attr_set = false;
+    static int n_cu = 0;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI, WF>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_fixup_kernel<EPI, WF>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+            return hipErrorInvalidDevice;
         attr_set = true;
     }
-    dim3 grid((g.N + TL::BF - 1) / TL::BF, (g.M + BR - 1) / BR);
-    gemm_bf16_kernel<EPI, WF><<<grid, dim3(64 * TL::NW), TL::LDS_BYTES, st>>>(g);
+    // One workgroup per CU at a time (the LDS ring fills it), so a launch runs in rounds of n_cu tiles and a last round
+    // of `rest` tiles leaves CUs idle.  The tiles of that round are split along K over n_cu / rest workgroups each: the
+    // round then takes 1 / n_parts of a tile's time, and the launch rest / n_cu rounds less.
+    const int n_tiles = ((g.N + TL::BF - 1) / TL::BF) * ((g.M + BR - 1) / BR);
+    const int rest = n_tiles % n_cu;
+    int n_parts = (rest == 0 || g_gemm_split == 0) ? 1 : std::min(n_cu / rest, 8);
+    // A part pays its own pipeline fill, a 128 KB dump of partial sums and its share of the second kernel: measured,
+    // parts of 112 K tiles gain 9 % (K = 14336, 384 tiles), parts of 32 or 16 lose 10 - 15 % (K = 4096).
+    n_parts = std::min(n_parts, (g.K / BK) / MIN_K_TILES_PER_PART);
+    if (n_parts > 1 &&
+        (g.partials == nullptr || (size_t)rest * n_parts * TL::NW * PARTIAL_FLOATS_PER_WAVE * sizeof(float) > g.partials_bytes))
+        n_parts = 1;
+    g.n_parts = std::max(n_parts, 1);
+    g.n_whole = g.n_parts > 1 ? n_tiles - rest : n_tiles;
+    const int grid = g.n_whole + (n_tiles - g.n_whole) * g.n_parts;
+    gemm_bf16_kernel<EPI, WF><<<dim3(grid), dim3(64 * TL::NW), TL::LDS_BYTES, st>>>(g);
+    if (g.n_parts > 1)
+        gemm_fixup_kernel<EPI, WF><<<dim3(n_tiles - g.n_whole), dim3(64 * TL::NW), TL::LDS_BYTES, st>>>(g);
     return hipGetLastError();
 }
 
@@ -310,26 +397,33 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
 }  // namespace
 
 void launch_gemm_set_tile(int features_per_workgroup) { g_gemm_tile = features_per_workgroup; }
+void launch_gemm_set_split(int on) { g_gemm_split = on; }
+size_t gemm_partials_bytes() { return (size_t)256 * 8 * PARTIAL_FLOATS_PER_WAVE * sizeof(float); }   // 256 parts of 8 waves
 
 hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
-                         hipStream_t st) {
+                         float* partials, size_t partials_bytes, hipStream_t st) {
     GemmArgs g{};
+    g.partials = partials; g.partials_bytes = partials_bytes;
     g.a = (const __bf16*)a; g.w = (const __bf16*)w; g.M = M; g.N = N; g.K = K;
     g.out = (__bf16*)out; g.residual = (const __bf16*)residual;
     return residual ? launch_gemm<EPI_RESIDUAL>(g, st) : launch_gemm<EPI_STORE>(g, st);
 }
 
-hipError_t launch_linear_swiglu(const void* a, const void* w_gate_up, int M, int F, int K, void* out, hipStream_t st) {
+hipError_t launch_linear_swiglu(const void* a, const void* w_gate_up, int M, int F, int K, void* out, float* partials,
+                                size_t partials_bytes, hipStream_t st) {
     GemmArgs g{};
+    g.partials = partials; g.partials_bytes = partials_bytes;
     g.a = (const __bf16*)a; g.w = (const __bf16*)w_gate_up; g.M = M; g.N = 2 * F; g.K = K; g.out = (__bf16*)out;
     return launch_gemm<EPI_SWIGLU>(g, st);
 }
 
 hipError_t launch_qkv_rope(const Shape& s, const void* a, const void* w_qkv, int M, int K, const int32_t* positions,
-                           float2* rope_rows, void* q_out, void* k_out, void* v_out, hipStream_t st) {
+                           float2* rope_rows, void* q_out, void* k_out, void* v_out, float* partials,
+                           size_t partials_bytes, hipStream_t st) {
     rope_rows_table_kernel<<<dim3(M), dim3(64), 0, st>>>(positions, M, s.d / 2, s.d, s.rope_base, s.rope_index_base,
                                                           rope_rows);
     GemmArgs g{};
+    g.partials = partials; g.partials_bytes = partials_bytes;
     g.a = (const __bf16*)a; g.w = (const __bf16*)w_qkv; g.M = M; g.N = (s.Hq + 2 * s.Hkv) * s.d; g.K = K;
     g.q_out = (__bf16*)q_out; g.k_out = (__bf16*)k_out; g.v_out = (__bf16*)v_out; g.rope = rope_rows;
     g.Hq = s.Hq; g.Hkv = s.Hkv; g.d = s.d;

@@ -56,6 +56,45 @@ def test_linear_both_tilings(ctx, M, N, K, tile):
         ctx.fr_set_option(B.FR_OPT_GEMM_TILE, 64)
 
 
+@pytest.mark.parametrize("split", [0, 1])
+@pytest.mark.parametrize("tile", [128, 256])
+def test_epilogues_with_and_without_tail_split(ctx, tile, split):
+    """Few output tiles and a long K: every tile belongs to the launch's last round and is computed by several
+    workgroups along K, whose partial sums a second kernel adds before the epilogue (residual, SwiGLU, rotary Q/K/V).
+    Forced off for comparison: same oracle, same tolerance."""
+    rng = np.random.default_rng(40 + tile + split)
+    Hq, Hkv, d = SHAPE.n_q_heads, SHAPE.n_kv_heads, SHAPE.head_dim
+    M, K = 300, 2 * 96 * 64          # two parts of 96 K tiles each is the shortest split the launcher makes
+    a = bf(rng.standard_normal((M, K)))
+    ctx.fr_set_option(B.FR_OPT_GEMM_TILE, tile)
+    ctx.fr_set_option(B.FR_OPT_GEMM_TAIL_SPLIT, split)
+    try:
+        w, r = bf(rng.standard_normal((384, K)) * 0.05), bf(rng.standard_normal((M, 384)))
+        res = H.dev(r, "bf16")
+        ctx.fr_linear(H.dev(a, "bf16"), H.dev(w, "bf16"), M, 384, K, res, res)
+        wg = bf(rng.standard_normal((2 * 192, K)) * 0.05)
+        sw = torch.zeros((M, 192), dtype=torch.bfloat16, device="cuda")
+        ctx.fr_linear_swiglu(H.dev(a, "bf16"), H.dev(wg, "bf16"), M, 192, K, sw)
+        wq = bf(rng.standard_normal(((Hq + 2 * Hkv) * d, K)) * 0.05)
+        pos = np.sort(rng.choice(4000, size=M, replace=False)).astype(np.int32)
+        q = torch.zeros((M, Hq, d), dtype=torch.bfloat16, device="cuda")
+        k = torch.zeros((M, Hkv, d), dtype=torch.bfloat16, device="cuda")
+        v = torch.zeros((M, Hkv, d), dtype=torch.bfloat16, device="cuda")
+        ctx.fr_qkv_rope(H.dev(a, "bf16"), H.dev(wq, "bf16"), M, K, torch.from_numpy(pos).cuda(), q, k, v)
+        torch.cuda.synchronize()
+    finally:
+        ctx.fr_set_option(B.FR_OPT_GEMM_TILE, 0)
+        ctx.fr_set_option(B.FR_OPT_GEMM_TAIL_SPLIT, 1)
+    H.assert_close(H.host(res), orc.linear(a, w, r), "bf16", "linear + residual")
+    H.assert_close(H.host(sw), orc.linear_swiglu(a, wg), "bf16", "swiglu")
+    qo, ko, vo = orc.qkv_rope(a, wq, pos, Hq, Hkv, d, SHAPE.rope_base)
+    H.assert_close(H.host(q), qo, "bf16", "q")
+    H.assert_close(H.host(k), ko, "bf16", "k")
+    H.assert_close(H.host(v), vo, "bf16", "v")
+    with pytest.raises(B.FusionRAGError):
+        ctx.fr_set_option(B.FR_OPT_GEMM_TAIL_SPLIT, 2)
+
+
 @pytest.mark.parametrize("M,F,K", [(70, 64, 128), (300, 192, 320)])
 def test_linear_swiglu(ctx, M, F, K):
     rng = np.random.default_rng(M + F)
