@@ -309,14 +309,19 @@ __device__ __forceinline__ void dma_image(const unsigned char* src, unsigned cha
     // that may complete out of order with the LDS reads, and from then on waits for *all* outstanding fragment
     // reads before every use (lgkmcnt(0)), which puts a full LDS round trip in front of the matrix pipe every few
     // fragments.  Completion is waited for explicitly anyway (wait_dma + workgroup barrier), so nothing is lost.
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_dst;
+    // The image address is the same for the whole workgroup, so it travels in scalar registers (base + 16 lane):
+    // the copies cost the vector ALU nothing.  `wave` must be wave-uniform in the compiler's eyes (readfirstlane).
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_dst);
+    const uint32_t lane_off = (uint32_t)lane * 16u;
+    static_assert(K_IMG_BYTES / 1024 == 18, "chunks 0..15 by all four waves, 16 and 17 by waves 0 and 1");
 #pragma unroll
     for (int c = 0; c < 5; ++c) {
         const int chunk = wave + 4 * c;
-        if (chunk < K_IMG_BYTES / 1024) {
-            const unsigned char* g = src + chunk * 1024 + lane * 16;
-            const uint32_t l = __builtin_amdgcn_readfirstlane(lds_base + chunk * 1024);
-            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory");
+        if (c < 4 || wave < 2) {
+            const unsigned char* g = src + chunk * 1024;
+            const uint32_t l = lds_base + (uint32_t)chunk * 1024u;
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(g), "s"(l) : "memory");
         }
     }
 }
@@ -605,7 +610,7 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
 
     // ---- prologue: K images 0 and 1 and V image 0 land in LDS ---------------------------------------------
     const unsigned char* head_images = images + (size_t)ge.g * n_img_tiles * IMG_BYTES;
-    const int wave = ge.wave, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(ge.wave), lane = threadIdx.x & 63;
     const int n_kt = ge.n_kt;
     const unsigned char* first_image = head_images + (size_t)kb * IMG_BYTES;
     dma_image(first_image, rg.k[0], wave, lane);
