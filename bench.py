@@ -130,8 +130,12 @@ def bench_stack(args):
     for _ in range(max(1, args.warmup // 3)):
         run(True)
     steps = max(1, args.steps // 10)
-    ms_every = float(np.mean([run(True) for _ in range(steps)]))
-    ms_once = float(np.mean([run(False) for _ in range(steps)]))
+    # the two schedules alternate, so that clock and temperature drift of a 70 ms step under full load hits both alike
+    t_every, t_once = [], []
+    for _ in range(steps):
+        t_every.append(run(True))
+        t_once.append(run(False))
+    ms_every, ms_once = float(np.mean(t_every)), float(np.mean(t_once))
     gemm_flops = 2.0 * R * n_layers * (hidden * (Hq + 2 * Hkv) * d + Hq * d * hidden + 3 * hidden * ffn)
     attn_flops = 4.0 * d * Hq * attention_pairs(qi.cpu().numpy()) * n_layers
     print(json.dumps({

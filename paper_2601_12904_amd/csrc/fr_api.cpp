@@ -729,6 +729,8 @@ static fr_status check_gemm(fr_ctx* ctx, const char* what, const void* a, const 
     if (M < 0 || N <= 0 || K <= 0) return fail(ctx, FR_ERR_INVALID_ARG, "%s: bad M = %d, N = %d, K = %d", what, M, N, K);
     if (N % 128 != 0 || K % 64 != 0)
         return fail(ctx, FR_ERR_UNSUPPORTED, "%s: N = %d must be a multiple of 128 and K = %d of 64", what, N, K);
+    if (K > (1 << 22))   // the kernel addresses a tile's rows with 32-bit byte offsets: 256 rows of K elements
+        return fail(ctx, FR_ERR_UNSUPPORTED, "%s: K = %d exceeds 2^22", what, K);
     if (M > 0 && (!a || !w || !aligned16(a) || !aligned16(w)))
         return fail(ctx, FR_ERR_INVALID_ARG, "%s: a / w is NULL or not 16-byte aligned", what);
     return FR_OK;

@@ -48,22 +48,32 @@ struct Tiling {
 __device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
 
 // Copy one operand tile (rows of 128 bytes) into LDS.  Chunk u (16 bytes) of the tile sits at byte 16 u; every wave
-// moves 1 KB per round.  `rows` bounds the operand (rows past the end are clamped and never stored).
+// moves 1 KB per round.  The per-lane part of a copy's source address does not change from K tile to K tile (which
+// row, which 16-byte chunk of its 128 bytes: `lane_off`, set up once by dma_offsets; rows past the end of the operand
+// are clamped and never stored), the rest is the same for the whole workgroup and travels in scalar registers, as
+// does the LDS address: a copy costs the vector ALU nothing.
+// (The copies are written out rather than left to the builtin: with it the compiler takes the pending copy for an
+// access that may complete out of order with the LDS reads, and waits for all outstanding fragment reads before
+// every matrix instruction.)
 template <int ROUNDS, int NW>
-__device__ __forceinline__ void dma_tile(const __bf16* __restrict__ base, int64_t ld, int row0, int rows, int k0,
-                                         unsigned char* lds_tile, int wave, int lane) {
+__device__ __forceinline__ void dma_offsets(int64_t ld, int row0, int rows, int wave, int lane, uint32_t (&lane_off)[ROUNDS]) {
 #pragma unroll
     for (int j = 0; j < ROUNDS; ++j) {
-        const int blk = j * NW + wave;
-        const int u = blk * 64 + lane;
+        const int u = (j * NW + wave) * 64 + lane;
         const int r = u >> 3, cpos = u & 7;
         const int c = cpos ^ swz(r);
-        const __bf16* src = base + (int64_t)min(row0 + r, rows - 1) * ld + k0 + 8 * c;
-        // (written out: with the builtin the compiler takes the pending copy for an access that may complete out
-        // of order with the LDS reads, and waits for all outstanding fragment reads before every matrix instruction)
-        const uint32_t l = __builtin_amdgcn_readfirstlane(
-            (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)(lds_tile + blk * 1024));
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(l) : "memory");
+        // relative to the operand's row row0 and the current K tile; fits 32 bits: at most 256 rows of at most 2^22
+        // elements (checked by the caller)
+        lane_off[j] = (uint32_t)(((int64_t)(min(row0 + r, rows - 1) - row0) * ld + 8 * c) * 2);
+    }
+}
+template <int ROUNDS, int NW>
+__device__ __forceinline__ void dma_tile(const unsigned char* tile_src /* uniform: row row0, current K tile */,
+                                         const uint32_t (&lane_off)[ROUNDS], uint32_t lds_tile /* uniform */, int wave_u) {
+#pragma unroll
+    for (int j = 0; j < ROUNDS; ++j) {
+        const uint32_t l = lds_tile + (uint32_t)(j * NW + wave_u) * 1024u;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off[j]), "s"(tile_src), "s"(l) : "memory");
     }
 }
 
@@ -216,10 +226,18 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
+    uint32_t w_off[TL::W_ROUNDS], a_off[TL::A_ROUNDS];
+    dma_offsets<TL::W_ROUNDS, NW>(g.K, f0, g.N, wave, lane, w_off);
+    dma_offsets<TL::A_ROUNDS, NW>(g.K, r0, g.M, wave, lane, a_off);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem);
+    const unsigned char* w_row0 = reinterpret_cast<const unsigned char*>(g.w + (int64_t)f0 * g.K);
+    const unsigned char* a_row0 = reinterpret_cast<const unsigned char*>(g.a + (int64_t)r0 * g.K);
     auto issue = [&](int kt) {
-        unsigned char* st = smem + (kt % N_STAGE) * STAGE_BYTES;
-        dma_tile<TL::W_ROUNDS, NW>(g.w, g.K, f0, g.N, (kt_begin + kt) * BK, st, wave, lane);
-        dma_tile<TL::A_ROUNDS, NW>(g.a, g.K, r0, g.M, (kt_begin + kt) * BK, st + TL::W_TILE_BYTES, wave, lane);
+        const uint32_t st = lds0 + (uint32_t)(kt % N_STAGE) * STAGE_BYTES;
+        const int64_t k_bytes = (int64_t)(kt_begin + kt) * BK * 2;
+        dma_tile<TL::W_ROUNDS, NW>(w_row0 + k_bytes, w_off, st, wave_u);
+        dma_tile<TL::A_ROUNDS, NW>(a_row0 + k_bytes, a_off, st + TL::W_TILE_BYTES, wave_u);
     };
 #pragma unroll
     for (int p = 0; p < N_STAGE - 1; ++p)
