@@ -364,6 +364,17 @@ def bench_shared_prefill(args):
     ms_batch = timeit(lambda: ctx.fr_sparse_prefill_attn_shared_batch(batch, k_store, v_store, N, ws))
     ms_shared = timeit(lambda: [shared(qd) for qd in queries])
     ms_three = timeit(lambda: [three_call(qd, gi) for qd, gi in zip(queries, gather_idx)])
+    # Query-Guided Selection of the same queries: straight from the store against copy + fr_rope_shift + fr_score_select
+    qq = (torch.randn((nq, Hq, d), generator=gen, device="cuda") * np.sqrt(d)).to(bf)
+    qi_sel = torch.empty(R, dtype=torch.int32, device="cuda")
+    k_shift = torch.empty((L_ctx, Hkv, d), dtype=bf, device="cuda")
+    def select_shared(qd):
+        ctx.fr_score_select_shared(qq, nq, k_store, N, offs, qd["row0"], qd["src"], k_sel, B.FR_NORM_PER_CHUNK, None, qi_sel)
+    def select_two_call(qd, gi):
+        ctx.fr_rope_shift(k_store[gi], k_shift, offs, qd["src"])
+        ctx.fr_score_select(qq, nq, k_shift, offs, k_sel, B.FR_NORM_PER_CHUNK, None, qi_sel)
+    ms_sel_shared = timeit(lambda: [select_shared(qd) for qd in queries])
+    ms_sel_two = timeit(lambda: [select_two_call(qd, gi) for qd, gi in zip(queries, gather_idx)])
     shared(queries[0]); three_call(queries[0], gather_idx[0]); torch.cuda.synchronize()
     agree = float((out.float() - out2.float()).abs().max() / out2.float().abs().max())
     agree_batch = float((outs[0].float() - out.float()).abs().max() / out.float().abs().max())
@@ -380,6 +391,8 @@ def bench_shared_prefill(args):
         "ms_three_call_path_incl_cache_copy": round(ms_three, 4),
         "max_rel_diff_between_paths": agree, "max_rel_diff_batch_vs_one_call_per_query": agree_batch,
         "workspace_bytes": int(ws.numel()),
+        "score_select_shared_ms_per_batch": round(ms_sel_shared, 4),
+        "score_select_copy_shift_score_ms_per_batch": round(ms_sel_two, 4),
         "attn_tflops": round(tf, 2),
         "roofline": {"kernel": "sparse_prefill_attn_shared_batch", "bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None},

@@ -154,6 +154,20 @@ fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const
                           const int32_t* chunk_offsets, int32_t n_chunks, int64_t k, int32_t norm,
                           float* scores_out, int32_t* q_index_out, void* stream);
 
+/* Query-Guided Selection over a chunk store that is shared between queries and never written (Sec. 4.3): the
+ * same scores and Q index as fr_rope_shift followed by fr_score_select, without the per-query copy of the keys.
+ * Chunk c of the prompt (positions chunk_offsets[c] .. chunk_offsets[c+1] - 1) is read from store rows
+ * chunk_store_row0[c] .., and its keys are moved from the positions they were cached at (chunk_src_pos0[c] ..) to
+ * their prompt positions on the way into the kernels (Appendix A; same arithmetic as fr_rope_shift).
+ *   k_store  dev [n_store_rows, Hkv, d], read only
+ *   chunk_offsets, chunk_store_row0, chunk_src_pos0  host, as in fr_sparse_prefill_attn_shared
+ *   norm     FR_NORM_PER_CHUNK or FR_NORM_GLOBAL
+ * Everything else as in fr_score_select.  FR_ERR_UNSUPPORTED unless the context is bf16 with head_dim 128. */
+fr_status fr_score_select_shared(fr_ctx* ctx, const void* q_question, int32_t nq, const void* k_store,
+                                 int64_t n_store_rows, const int32_t* chunk_offsets, const int32_t* chunk_store_row0,
+                                 const int32_t* chunk_src_pos0, int32_t n_chunks, int64_t k, int32_t norm,
+                                 float* scores_out, int32_t* q_index_out, void* stream);
+
 /* Only the selection half of the call above, over scores the caller already has (any selector:
  * for example the KV deviation of eq. 7-8).  scores dev [n] fp32 (finite), q_index_out dev [k + nq]. */
 fr_status fr_select_topk(fr_ctx* ctx, const float* scores, int64_t n, int64_t k, int32_t nq,

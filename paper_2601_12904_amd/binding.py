@@ -29,7 +29,7 @@ FR_DECODE_KERNEL_AUTO, FR_DECODE_KERNEL_GENERIC = 0, 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 FR_ATTN_SPLIT_AUTO, FR_ATTN_SPLIT_OFF, FR_ATTN_SPLIT_ON = 0, 1, 2
 EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_attn_kernel_times", "fr_topk_count", "fr_rope_shift",
-           "fr_score_select", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_writeback", "fr_sparse_prefill_attn_shared", "fr_shared_batch_workspace_bytes", "fr_sparse_prefill_attn_shared_batch", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
+           "fr_score_select", "fr_score_select_shared", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_writeback", "fr_sparse_prefill_attn_shared", "fr_shared_batch_workspace_bytes", "fr_sparse_prefill_attn_shared_batch", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
            "fr_linear_swiglu", "fr_qkv_rope")
 
 
@@ -85,6 +85,8 @@ def load() -> ctypes.CDLL:
     lib.fr_rope_shift.restype = i32
     lib.fr_score_select.argtypes = [vp, vp, i32, vp, pi32, i32, i64, i32, vp, vp, vp]
     lib.fr_score_select.restype = i32
+    lib.fr_score_select_shared.argtypes = [vp, vp, i32, vp, i64, pi32, pi32, pi32, i32, i64, i32, vp, vp, vp]
+    lib.fr_score_select_shared.restype = i32
     lib.fr_select_topk.argtypes = [vp, vp, i64, i64, i32, vp, vp]
     lib.fr_select_topk.restype = i32
     lib.fr_kv_deviation.argtypes = [vp, vp, vp, i64, vp, vp]
@@ -204,6 +206,16 @@ class Context:
         self._check(self._lib.fr_score_select(self._h, _ptr(q_question), int(nq), _ptr(k_ctx), offs, len(_a) - 1,
                                               int(k), int(norm), _ptr(scores_out), _ptr(q_index_out),
                                               _stream(stream)))
+
+    def fr_score_select_shared(self, q_question, nq: int, k_store, n_store_rows: int, chunk_offsets, chunk_store_row0,
+                               chunk_src_pos0, k: int, norm: int = FR_NORM_PER_CHUNK, scores_out=None, q_index_out=None,
+                               stream=None):
+        offs, _a = _i32_array(chunk_offsets)
+        row0, _b = _i32_array(chunk_store_row0)
+        src, _c = _i32_array(chunk_src_pos0)
+        self._check(self._lib.fr_score_select_shared(self._h, _ptr(q_question), int(nq), _ptr(k_store), int(n_store_rows),
+                                                     offs, row0, src, len(_a) - 1, int(k), int(norm), _ptr(scores_out),
+                                                     _ptr(q_index_out), _stream(stream)))
 
     def fr_select_topk(self, scores, n: int, k: int, nq: int, q_index_out, stream=None):
         self._check(self._lib.fr_select_topk(self._h, _ptr(scores), int(n), int(k), int(nq), _ptr(q_index_out),

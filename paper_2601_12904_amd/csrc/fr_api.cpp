@@ -388,6 +388,67 @@ fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const
     return FR_OK;
 }
 
+fr_status fr_score_select_shared(fr_ctx* ctx, const void* q_question, int32_t nq, const void* k_store,
+                                 int64_t n_store_rows, const int32_t* chunk_offsets, const int32_t* chunk_store_row0,
+                                 const int32_t* chunk_src_pos0, int32_t n_chunks, int64_t k, int32_t norm,
+                                 float* scores_out, int32_t* q_index_out, void* stream) {
+    if (!ctx) return FR_ERR_INVALID_ARG;
+    ctx->err.clear();
+    const Shape& s = ctx->shape;
+    if (nq < 0) return fail(ctx, FR_ERR_INVALID_ARG, "nq = %d is negative", nq);
+    if (nq > ctx->max_q) return fail(ctx, FR_ERR_WORKSPACE, "nq = %d exceeds max_question_tokens = %d", nq, ctx->max_q);
+    ChunkTable ct;
+    fr_status st = read_chunks(ctx, chunk_offsets, n_chunks, ctx->max_tokens - nq, &ct, nullptr);
+    if (st != FR_OK) return st;
+    const int64_t L_ctx = ct.off[ct.n];
+    if (norm != FR_NORM_PER_CHUNK && norm != FR_NORM_GLOBAL)
+        return fail(ctx, FR_ERR_INVALID_ARG, "score norm %d: the shared-store scoring takes the two softmax scopes", norm);
+    if (k < 0 || k > L_ctx)
+        return fail(ctx, FR_ERR_INVALID_ARG, "k = %lld outside [0, L_ctx = %lld]", (long long)k, (long long)L_ctx);
+    if (n_store_rows < 0) return fail(ctx, FR_ERR_INVALID_ARG, "n_store_rows is negative");
+    if (n_chunks > 0 && (!chunk_store_row0 || !chunk_src_pos0))
+        return fail(ctx, FR_ERR_INVALID_ARG, "chunk_store_row0 / chunk_src_pos0 is NULL");
+    ChunkDeltas dl;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t len = (int64_t)ct.off[c + 1] - ct.off[c];
+        if (chunk_store_row0[c] < 0 || (int64_t)chunk_store_row0[c] + len > n_store_rows)
+            return fail(ctx, FR_ERR_INVALID_ARG, "chunk %d: store rows [%d, %lld) outside the store of %lld rows", c,
+                        chunk_store_row0[c], (long long)chunk_store_row0[c] + len, (long long)n_store_rows);
+        const int64_t delta = (int64_t)ct.off[c] - (int64_t)chunk_src_pos0[c];
+        if (delta > INT32_MAX || delta < INT32_MIN) return fail(ctx, FR_ERR_INVALID_ARG, "position delta overflows");
+        dl.delta[c] = (int32_t)delta;
+    }
+    if (k + nq > 0 && !q_index_out) return fail(ctx, FR_ERR_INVALID_ARG, "q_index_out is NULL");
+    if (nq > 0 && (!q_question || !aligned16(q_question)))
+        return fail(ctx, FR_ERR_INVALID_ARG, "q_question is NULL or not 16-byte aligned");
+    if (L_ctx > 0 && (!k_store || !aligned16(k_store)))
+        return fail(ctx, FR_ERR_INVALID_ARG, "k_store is NULL or not 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scores_out) & 3u) || (reinterpret_cast<uintptr_t>(q_index_out) & 3u))
+        return fail(ctx, FR_ERR_INVALID_ARG, "scores_out / q_index_out must be 4-byte aligned");
+    if (!score_mfma_supported(s))
+        return fail(ctx, FR_ERR_UNSUPPORTED, "the shared-store scoring needs bf16, head_dim 128 and a group size of 1, 2, 4 or 8");
+    if (L_ctx == 0 && nq == 0) return FR_OK;
+    if ((st = need_device(ctx)) != FR_OK) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    float* scores = scores_out ? scores_out : ctx->ws.scores;
+    const bool need_scores = (scores_out != nullptr) || (k > 0 && k < L_ctx);
+    if (L_ctx > 0 && need_scores) {
+        if (nq == 0) {   // no question rows: every score is an empty sum (the generic kernel writes the zeros; no key is read)
+            hipError_t e = launch_score_simt(s, q_question, 0, k_store, ct, norm, ctx->ws, scores, hs);
+            if (e != hipSuccess) return hip_fail(ctx, "score launch", e);
+        } else {
+            hipError_t e = launch_rope_table(s, dl, n_chunks, ctx->ws.rope_table, hs);
+            if (e != hipSuccess) return hip_fail(ctx, "rope table launch", e);
+            e = launch_score_mfma_shared(s, q_question, nq, k_store, ct, chunk_store_row0, ctx->ws.rope_table, norm, ctx->ws,
+                                         scores, hs);
+            if (e != hipSuccess) return hip_fail(ctx, "score launch", e);
+        }
+    }
+    hipError_t e = launch_select(scores, L_ctx, k, nq, q_index_out, ctx->ws.select_tmp, hs);
+    if (e != hipSuccess) return hip_fail(ctx, "select launch", e);
+    return FR_OK;
+}
+
 static fr_status check_rows(fr_ctx* ctx, int32_t R, int64_t L) {
     if (R < 0) return fail(ctx, FR_ERR_INVALID_ARG, "R = %d is negative", R);
     if (L < 0) return fail(ctx, FR_ERR_INVALID_ARG, "L = %lld is negative", (long long)L);

@@ -104,6 +104,10 @@ bool score_mfma_supported(const Shape& s);
 hipError_t launch_score_mfma(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct,
                              int norm, const Workspace& ws, float* scores, hipStream_t st);
 
+hipError_t launch_score_mfma_shared(const Shape& s, const void* q, int nq, const void* k_store, const ChunkTable& ct,
+                                    const int32_t* store_row0, const float2* table, int norm, const Workspace& ws,
+                                    float* scores, hipStream_t st);
+
 hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index,
                          uint32_t* tmp, hipStream_t st);
 size_t select_workspace_bytes();   // what `tmp` must hold

@@ -32,6 +32,7 @@
 // the attention kernels want in LDS.  The fast kernel's tile loop then stages a tile with direct-to-LDS
 // copies: no lookups, no pointer selects, no permutes, no address arithmetic, no staging registers.
 #include "fr_internal.hpp"
+#include "k_rotate.hpp"
 
 #include <algorithm>
 
@@ -200,9 +201,6 @@ __global__ __launch_bounds__(256) void pack_kv_images_kernel(const __bf16* k_cac
 // listed in the Q index (inv[j] >= 0: recomputed context tokens and all question tokens) read the query's own
 // fresh rows instead, so the store's stale entries of those tokens are never read and no per-query copy of the
 // cache exists.  Positions >= L_ctx that are not in the Q index have no data: they read as zero.
-struct ChunkRows {
-    int32_t row0[FR_MAX_CHUNKS];
-};
 
 // Prompt position -> (store row, chunk) for the packing kernel, so that it needs no search and no dependent loads:
 // grid (position tiles of the longest chunk, chunks + 1); the extra y index covers the positions behind the context
@@ -216,39 +214,6 @@ __global__ __launch_bounds__(256) void prompt_map_kernel(ChunkTable ct, ChunkRow
         store_row[j] = (c < ct.n) ? rows.row0[c] + (j - begin) : -1;
         chunk_id[j] = (c < ct.n) ? c : 0;
     }
-}
-
-template <int LAYOUT>
-__device__ __forceinline__ u32x4 rotate_key_vector(u32x4 own, u32x4 partner, const float2* __restrict__ trow, int st_vec) {
-    // own = elements 8 st_vec .. + 7 of the head row.  Interleaved pairs: (2p, 2p + 1) inside the vector.
-    // Half-split pairs: (p, p + 64): `partner` is the vector 64 elements away.
-    u32x4 outv;
-    if (LAYOUT == FR_ROPE_INTERLEAVED) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float2 t = trow[4 * st_vec + e];
-            const float a = __uint_as_float(own[e] << 16), b = __uint_as_float(own[e] & 0xFFFF0000u);
-            const __bf16 ya = (__bf16)(a * t.x - b * t.y), yb = (__bf16)(b * t.x + a * t.y);
-            outv[e] = (uint32_t)__builtin_bit_cast(unsigned short, ya) | ((uint32_t)__builtin_bit_cast(unsigned short, yb) << 16);
-        }
-    } else {
-        const bool low = st_vec < 8;   // this vector holds the first elements of its pairs
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            unsigned short r2[2];
-#pragma unroll
-            for (int hlf = 0; hlf < 2; ++hlf) {
-                const float2 t = trow[(8 * st_vec + 2 * e + hlf) & 63];
-                const float mine = hlf ? __uint_as_float(own[e] & 0xFFFF0000u) : __uint_as_float(own[e] << 16);
-                const float other = hlf ? __uint_as_float(partner[e] & 0xFFFF0000u) : __uint_as_float(partner[e] << 16);
-                const float a = low ? mine : other, b = low ? other : mine;
-                const __bf16 y = low ? (__bf16)(a * t.x - b * t.y) : (__bf16)(b * t.x + a * t.y);
-                r2[hlf] = __builtin_bit_cast(unsigned short, y);
-            }
-            outv[e] = (uint32_t)r2[0] | ((uint32_t)r2[1] << 16);
-        }
-    }
-    return outv;
 }
 
 template <int LAYOUT>

@@ -13,7 +13,13 @@
 // Orientation is chosen so that each reduction runs inside a lane: pass A puts keys on the
 // accumulator's register dimension and query columns on lanes; pass B the other way round.
 // All sums run in a fixed order: the scores are reproducible bit for bit.
+//
+// Key source (template parameter SRC).  SRC_PROMPT: k holds the context keys at their prompt positions.  SRC_STORE_*:
+// k is a chunk store shared between queries (Sec. 4.3); chunk c of the prompt occupies store rows row0[c] .., and its
+// keys are moved to their prompt positions on the way into the kernel (Appendix A: rotation by the chunk's row of
+// `table`, interleaved or half-split pairs), so the selection needs no per-query copy of the keys either.
 #include "fr_internal.hpp"
+#include "k_rotate.hpp"
 
 #include <type_traits>
 
@@ -29,6 +35,22 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int D = 128;
 constexpr int PITCH = D + 8;   // bf16 elements per LDS row (272 B)
 constexpr float NEG_BIG = -1.0e30f;
+enum { SRC_PROMPT = 0, SRC_STORE_INTERLEAVED = 1, SRC_STORE_HALF = 2 };
+
+// Row of `k` that holds prompt position j of chunk c (c0 = the chunk's first position).
+template <int SRC>
+__device__ __forceinline__ int64_t key_row(const ChunkRows& rows, int c, int c0, int j) {
+    return SRC == SRC_PROMPT ? (int64_t)j : (int64_t)rows.row0[c] + (j - c0);
+}
+// 16-byte vector `vec` (8 elements) of one key row, moved to its prompt position where the source is a store.
+template <int SRC>
+__device__ __forceinline__ u32x4 load_key_vector(const __bf16* row, int vec, const float2* trow) {
+    const u32x4 own = *reinterpret_cast<const u32x4*>(row + 8 * vec);
+    if (SRC == SRC_PROMPT) return own;
+    if (SRC == SRC_STORE_INTERLEAVED) return rotate_key_vector<FR_ROPE_INTERLEAVED>(own, own, trow, vec);
+    const u32x4 partner = *reinterpret_cast<const u32x4*>(row + 8 * (vec ^ 8));
+    return rotate_key_vector<FR_ROPE_HALF>(own, partner, trow, vec);
+}
 
 __device__ __forceinline__ bf16x8 zero8() {
     bf16x8 z;
@@ -69,11 +91,12 @@ __device__ __forceinline__ void interleave_hint() {
 // keys, software-pipelined: the products of a half are issued while the exponentials of the half before it
 // run.  Every lane keeps a running maximum and sum over the keys it sees itself (one of the two 4-row groups in
 // every 8 keys); the two lanes of a query column are merged once at the end.
-template <int G>
+template <int G, int SRC>
 __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __restrict__ q,
                                                                 const __bf16* __restrict__ k, ChunkTable ct, int nq,
                                                                 int Hq, int Hkv, int n_qtiles, float scale_log2e,
-                                                                float* __restrict__ lse2) {
+                                                                float* __restrict__ lse2, ChunkRows rows,
+                                                                const float2* __restrict__ table) {
     __shared__ __attribute__((aligned(16))) __bf16 ks_lds[2][64 * PITCH];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int g = blockIdx.x % Hkv;
@@ -82,6 +105,7 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
     const int c0 = ct.off[c], c1 = ct.off[c + 1];
     const int NQG = nq * G;
     const int n_base = (qtile * 4 + wave) * 64;
+    const float2* trow = SRC == SRC_PROMPT ? nullptr : table + (size_t)c * (D / 2);
 
     bf16x8 qf[2][8];
     int col_n[2];
@@ -103,7 +127,7 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int j = min(c0 + kt * 64 + st_key + 16 * i, c1 - 1);
-            kreg[i] = *reinterpret_cast<const u32x4*>(k + ((size_t)j * Hkv + g) * D + 8 * st_vec);
+            kreg[i] = load_key_vector<SRC>(k + ((size_t)key_row<SRC>(rows, c, c0, j) * Hkv + g) * D, st_vec, trow);
         }
     };
     auto write_tile = [&](int buf) {
@@ -188,12 +212,13 @@ __global__ void score_lse2_global_kernel(int n_chunks, int NQG, float* __restric
 // One workgroup = (KV head, chunk, 256 keys of the chunk), KV head fastest in the 1-D grid (see pass A).
 // scope_global: use lse2[g][C].  Query-column tiles are double-buffered in LDS and consumed in pipelined halves
 // like the key tiles of pass A.
-template <int G>
+template <int G, int SRC>
 __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                                                                 ChunkTable ct, int nq, int Hq, int Hkv, int n_ktiles,
                                                                 float scale_log2e, int scope_global,
                                                                 const float* __restrict__ lse2,
-                                                                float* __restrict__ col_partial) {
+                                                                float* __restrict__ col_partial, ChunkRows rows,
+                                                                const float2* __restrict__ table) {
     __shared__ __attribute__((aligned(16))) __bf16 q_lds[2][64 * PITCH];
     __shared__ __attribute__((aligned(16))) float lse_lds[4][64];   // four slots: a tile's normalisers outlive its rows
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
@@ -213,9 +238,12 @@ __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16*
     for (int nb = 0; nb < 2; ++nb) {
         const int j = kbase + 64 * wave + 32 * nb + x;
         col_key[nb] = j;
-        const __bf16* kp = k + ((size_t)min(j, c1 - 1) * Hkv + g) * D + 8 * h;   // keys past the end: copy, never stored
+        // keys past the end: copy, never stored
+        const __bf16* kp = k + ((size_t)key_row<SRC>(rows, c, c0, min(j, c1 - 1)) * Hkv + g) * D;
+        const float2* trow = SRC == SRC_PROMPT ? nullptr : table + (size_t)c * (D / 2);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kf[nb][ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
+        for (int ks = 0; ks < 8; ++ks)
+            kf[nb][ks] = __builtin_bit_cast(bf16x8, load_key_vector<SRC>(kp, 2 * ks + h, trow));
     }
     float csum[2] = {0.f, 0.f};
     const int st_vec = tid & 15, st_row = tid >> 4;
@@ -287,24 +315,36 @@ __global__ void score_reduce_heads_kernel(const float* __restrict__ col_partial,
     scores[j] = t;
 }
 
-template <int G>
+template <int G, int SRC>
 hipError_t run(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct, int norm,
-               const Workspace& ws, float* scores, hipStream_t st) {
+               const Workspace& ws, float* scores, const ChunkRows& rows, const float2* table, hipStream_t st) {
     const int L_ctx = ct.off[ct.n];
     const float c = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
     const int NQG = nq * G;
     int max_len = 0;
     for (int i = 0; i < ct.n; ++i) max_len = ct.off[i + 1] - ct.off[i] > max_len ? ct.off[i + 1] - ct.off[i] : max_len;
     const int n_qtiles = (NQG + 255) / 256, n_ktiles = (max_len + 255) / 256;
-    score_lse_mfma_kernel<G><<<dim3(n_qtiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
-        (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, n_qtiles, c, ws.lse);
+    score_lse_mfma_kernel<G, SRC><<<dim3(n_qtiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
+        (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, n_qtiles, c, ws.lse, rows, table);
     if (norm == FR_NORM_GLOBAL)
         score_lse2_global_kernel<<<dim3((NQG + 255) / 256, s.Hkv), dim3(256), 0, st>>>(ct.n, NQG, ws.lse);
-    score_colsum_mfma_kernel<G><<<dim3(n_ktiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
+    score_colsum_mfma_kernel<G, SRC><<<dim3(n_ktiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
         (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, n_ktiles, c, norm == FR_NORM_GLOBAL ? 1 : 0,
-        ws.lse, ws.col_partial);
+        ws.lse, ws.col_partial, rows, table);
     score_reduce_heads_kernel<<<dim3((L_ctx + 255) / 256), dim3(256), 0, st>>>(ws.col_partial, L_ctx, s.Hkv, scores);
     return hipGetLastError();
+}
+
+template <int SRC>
+hipError_t dispatch(const Shape& s, const void* q, int nq, const void* k, const ChunkTable& ct, int norm,
+                    const Workspace& ws, float* scores, const ChunkRows& rows, const float2* table, hipStream_t st) {
+    if (ct.off[ct.n] == 0 || nq == 0) return hipSuccess;
+    switch (s.G) {
+        case 1: return run<1, SRC>(s, q, nq, k, ct, norm, ws, scores, rows, table, st);
+        case 2: return run<2, SRC>(s, q, nq, k, ct, norm, ws, scores, rows, table, st);
+        case 4: return run<4, SRC>(s, q, nq, k, ct, norm, ws, scores, rows, table, st);
+        default: return run<8, SRC>(s, q, nq, k, ct, norm, ws, scores, rows, table, st);
+    }
 }
 
 }  // namespace
@@ -316,13 +356,20 @@ bool score_mfma_supported(const Shape& s) {
 // Softmax scopes only; the caller routes FR_NORM_RAW to the generic kernels.
 hipError_t launch_score_mfma(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct, int norm,
                              const Workspace& ws, float* scores, hipStream_t st) {
-    if (ct.off[ct.n] == 0 || nq == 0) return hipSuccess;
-    switch (s.G) {
-        case 1: return run<1>(s, q, nq, k_ctx, ct, norm, ws, scores, st);
-        case 2: return run<2>(s, q, nq, k_ctx, ct, norm, ws, scores, st);
-        case 4: return run<4>(s, q, nq, k_ctx, ct, norm, ws, scores, st);
-        default: return run<8>(s, q, nq, k_ctx, ct, norm, ws, scores, st);
-    }
+    const ChunkRows none{};
+    return dispatch<SRC_PROMPT>(s, q, nq, k_ctx, ct, norm, ws, scores, none, nullptr, st);
+}
+
+// The same over a shared chunk store: store_row0 (host) gives every chunk's first store row, `table` (device,
+// [chunks][d / 2]) the (cos, sin) of every chunk's position shift.
+hipError_t launch_score_mfma_shared(const Shape& s, const void* q, int nq, const void* k_store, const ChunkTable& ct,
+                                    const int32_t* store_row0, const float2* table, int norm, const Workspace& ws,
+                                    float* scores, hipStream_t st) {
+    ChunkRows rows{};
+    for (int c = 0; c < ct.n; ++c) rows.row0[c] = store_row0[c];
+    if (s.rope_layout == FR_ROPE_INTERLEAVED)
+        return dispatch<SRC_STORE_INTERLEAVED>(s, q, nq, k_store, ct, norm, ws, scores, rows, table, st);
+    return dispatch<SRC_STORE_HALF>(s, q, nq, k_store, ct, norm, ws, scores, rows, table, st);
 }
 
 }  // namespace fr

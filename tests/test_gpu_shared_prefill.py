@@ -191,3 +191,48 @@ def test_shared_store_batch_full_size_sampled():
                                           k_new, v_new, rows=rows)
         H.assert_close(H.host(q["out"][torch.from_numpy(rows).cuda()]), want, dt, "sampled rows of the batched launch")
     ctx.close()
+
+
+@pytest.mark.parametrize("layout", [B.FR_ROPE_INTERLEAVED, B.FR_ROPE_HALF])
+@pytest.mark.parametrize("norm", [B.FR_NORM_PER_CHUNK, B.FR_NORM_GLOBAL])
+def test_shared_store_score_select(norm, layout):
+    """Query-Guided Selection straight from the shared store: the keys are moved to their prompt positions inside the
+    scoring kernels.  Scores against the oracle (position shift, then critical scores on the shifted keys as stored),
+    index set by the tie-window rule, and agreement with the library's own fr_rope_shift + fr_score_select."""
+    w = synth.config_small_bf16(seed=9, chunk_lens=(200, 0, 333, 91, 256, 130))
+    dt = "bf16"
+    Hkv, d = w.shape.n_kv_heads, w.shape.head_dim
+    rng = np.random.default_rng(17)
+    lay = "half" if layout == B.FR_ROPE_HALF else "interleaved"
+    src_pos0 = rng.integers(0, 5000, size=w.n_chunks).astype(np.int32)
+    k_store, _, row0 = scattered_store(w, rng)
+    ks_d = H.dev(k_store, dt)
+    k = orc.topk_count(w.L_ctx, 0.15)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq, rope_layout=layout)
+    qq = H.dev(w.q_question, dt)
+    scores = torch.zeros(w.L_ctx, dtype=torch.float32, device="cuda")
+    qi = torch.full((k + w.nq,), -1, dtype=torch.int32, device="cuda")
+    ctx.fr_score_select_shared(qq, w.nq, ks_d, len(k_store), w.chunk_offsets, row0, src_pos0, k, norm, scores, qi)
+    torch.cuda.synchronize()
+    k_ctx = synth.round_to_storage(orc.rope_shift(w.k_cached, w.chunk_offsets, src_pos0, None, w.shape.rope_base, lay), dt)
+    want = orc.critical_scores(w.q_question, k_ctx, w.chunk_offsets, "global" if norm == B.FR_NORM_GLOBAL else "per_chunk")
+    got = scores.cpu().numpy().astype(np.float64)
+    assert H.max_rel_err(got, want) <= 2e-3      # the kernel's shifted keys may differ from the oracle's in the last bf16 bit
+    H.assert_index_set(qi.cpu().numpy().astype(np.int64), want, k, w.nq)
+    # the two-call path of the same library
+    k_shift = torch.zeros((w.L_ctx, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    ctx.fr_rope_shift(H.dev(w.k_cached, dt), k_shift, w.chunk_offsets, src_pos0)
+    scores2 = torch.zeros_like(scores)
+    qi2 = torch.zeros_like(qi)
+    ctx.fr_score_select(qq, w.nq, k_shift, w.chunk_offsets, k, norm, scores2, qi2)
+    torch.cuda.synchronize()
+    assert H.max_rel_err(got, scores2.cpu().numpy().astype(np.float64)) <= 2e-3
+    # no question rows: all scores zero, the first k tokens win the ties
+    ctx.fr_score_select_shared(None, 0, ks_d, len(k_store), w.chunk_offsets, row0, src_pos0, 5, norm, scores, qi)
+    torch.cuda.synchronize()
+    assert float(scores.abs().max()) == 0.0 and qi[:5].cpu().tolist() == [0, 1, 2, 3, 4]
+    with pytest.raises(B.FusionRAGError):
+        ctx.fr_score_select_shared(qq, w.nq, ks_d, len(k_store), w.chunk_offsets, row0, src_pos0, k, B.FR_NORM_RAW, scores, qi)
+    with pytest.raises(B.FusionRAGError):      # a chunk reaches past the end of the store
+        ctx.fr_score_select_shared(qq, w.nq, ks_d, 100, w.chunk_offsets, row0, src_pos0, k, norm, scores, qi)
+    ctx.close()
