@@ -178,3 +178,26 @@ def test_shared_batch_argument_errors():
     if not torch.cuda.is_available():
         expect(B.FR_ERR_DEVICE, c.fr_sparse_prefill_attn_shared_batch, [q, q], P, P, 100, P, need)
     c.close()
+
+
+def test_shared_score_select_argument_errors():
+    import torch
+    c = B.Context(32, 8, 128, B.FR_BF16, 5e5, max_tokens=600, max_chunks=4, max_question_tokens=32)
+    P = 4096
+    call = lambda **kw: c.fr_score_select_shared(**{**dict(q_question=P, nq=4, k_store=P, n_store_rows=100, chunk_offsets=[0, 8, 16],
+                                                        chunk_store_row0=[0, 8], chunk_src_pos0=[0, 0], k=3, norm=B.FR_NORM_PER_CHUNK,
+                                                        scores_out=None, q_index_out=P), **kw})
+    expect(B.FR_ERR_INVALID_ARG, call, chunk_store_row0=[0, 96])          # past the end of the store
+    expect(B.FR_ERR_INVALID_ARG, call, norm=B.FR_NORM_RAW)                # softmax scopes only
+    expect(B.FR_ERR_INVALID_ARG, call, k=17)                              # more than there are context tokens
+    expect(B.FR_ERR_INVALID_ARG, call, q_index_out=None)
+    expect(B.FR_ERR_INVALID_ARG, call, k_store=P + 4)                     # alignment
+    expect(B.FR_ERR_WORKSPACE, call, nq=33)
+    if not torch.cuda.is_available():
+        expect(B.FR_ERR_DEVICE, call)
+    c.close()
+    c32 = B.Context(4, 4, 64, B.FR_F32, 1e4, max_tokens=600, max_chunks=4, max_question_tokens=32)
+    with pytest.raises(B.FusionRAGError) as ei:
+        c32.fr_score_select_shared(P, 4, P, 100, [0, 8, 16], [0, 8], [0, 0], 3, B.FR_NORM_PER_CHUNK, None, P)
+    assert ei.value.status == B.FR_ERR_UNSUPPORTED
+    c32.close()
