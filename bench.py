@@ -29,7 +29,7 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E peak
 # this script scaled by a plain copy of known size (profiles/bench_config2_hbm_traffic.md): 335.5 MB fetched +
 # 101.6 MB written by the split launch this workload gets (173 MB unsplit).  Workloads that were not measured
 # report null.
-MEASURED_ATTN_TRAFFIC = {"llama3_8b_layer_16x1024+512": 431.0e6}
+MEASURED_ATTN_TRAFFIC = {"llama3_8b_layer_16x1024+512": 427.0e6}
 
 
 def attention_pairs(q_index: np.ndarray) -> int:
