@@ -274,9 +274,9 @@ def bench_decode(args):
         assert bool(torch.isfinite(out.float()).all())
         # rows the method must read: the unmasked store rows and the page rows of every query, K and V
         needed = nb * ((L_ctx - k_crit) + P) * Hkv * d * e * 2
-        streamed = nb * (L_ctx + P) * Hkv * d * e * 2          # what the kernel touches (masked rows are read, then dropped)
+        # (stale rows are not fetched: their lanes re-read a cached row instead, so needed = what the kernel streams)
         results[mode] = {"ms": round(ms, 4), "needed_gbps": round(needed / (ms * 1e-3) / 1e9, 1),
-                         "streamed_gbps": round(streamed / (ms * 1e-3) / 1e9, 1), "store_gb": round(2 * N * Hkv * d * e / 1e9, 3)}
+                         "store_gb": round(2 * N * Hkv * d * e / 1e9, 3)}
         del ks, vs, bits
     r = results["private_chunks"]
     print(json.dumps({

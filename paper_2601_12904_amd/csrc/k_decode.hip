@@ -348,17 +348,37 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(
     const __bf16* vp = un.vbase + (size_t)g * D + 8 * c;    // + row * row_elems
     const int64_t n_blocks = (len + 31) / 32;
     uint4 kw[8], vw[8];
-    auto load_block = [&](int64_t bi) {   // rows past the end are clamped (loaded, never counted)
-        const int64_t rk = row0 + min(32 * bi + x, len - 1);
+    // which of the 32 rows of block bi count: inside the unit and not stale for this query (bit i = row 32 bi + i)
+    auto rows_that_count = [&](int64_t bi) -> uint32_t {
+        if (bi >= n_blocks) return 0u;
+        const int64_t rowb = row0 + 32 * bi;
+        const int64_t left = len - 32 * bi;
+        uint32_t okbits = (left >= 32) ? 0xFFFFFFFFu : ((1u << (int)left) - 1u);
+        if (stale != nullptr) {
+            const int64_t wd = rowb >> 5;
+            const int sh = (int)(rowb & 31);
+            const uint32_t w0 = (wd < stale_words) ? stale[wd] : 0u;
+            const uint32_t w1 = (wd + 1 < stale_words) ? stale[wd + 1] : 0u;
+            okbits &= ~(uint32_t)((((uint64_t)w1 << 32) | w0) >> sh);
+        }
+        return okbits;
+    };
+    // Rows that do not count (stale for this query, or past the end) are not fetched: their lanes read the unit's
+    // first row instead, which stays in the cache, so the skipped rows cost no memory traffic (their logits are masked
+    // and their weights are zero).  No branch: the address is chosen, not the load.
+    auto load_block = [&](int64_t bi, uint32_t okbits) {
+        const int64_t rk = ((okbits >> x) & 1u) ? row0 + 32 * bi + x : row0;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) kw[ks] = *reinterpret_cast<const uint4*>(kp + (size_t)rk * row_elems + 16 * ks);
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            const int64_t rv = row0 + min(32 * bi + 4 * t + r, len - 1);
+            const int64_t rv = ((okbits >> (4 * t + r)) & 1u) ? row0 + 32 * bi + 4 * t + r : row0;
             vw[t] = *reinterpret_cast<const uint4*>(vp + (size_t)rv * row_elems);
         }
     };
-    if (wave < n_blocks) load_block(wave);
+    // the masks run one block ahead of the loads, the loads one block ahead of the arithmetic
+    uint32_t ok_cur = rows_that_count(wave), ok_next = rows_that_count(wave + 4);
+    if (wave < n_blocks) load_block(wave, ok_cur);
     for (int64_t bi = wave; bi < n_blocks; bi += 4) {
         // ---- logits of the block's 32 rows -----------------------------------------------------------------
         f32x16 s;
@@ -370,18 +390,10 @@ __global__ __launch_bounds__(256, 2) void decode_partial_mfma_kernel(
         uint4 vcur[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) vcur[t] = vw[t];
-        // which of the 32 rows count: inside the unit and not stale for this query
-        const int64_t rowb = row0 + 32 * bi;
-        const int64_t left = len - 32 * bi;
-        uint32_t okbits = (left >= 32) ? 0xFFFFFFFFu : ((1u << (int)left) - 1u);
-        if (stale != nullptr) {
-            const int64_t wd = rowb >> 5;
-            const int sh = (int)(rowb & 31);
-            const uint32_t w0 = (wd < stale_words) ? stale[wd] : 0u;
-            const uint32_t w1 = (wd + 1 < stale_words) ? stale[wd + 1] : 0u;
-            okbits &= ~(uint32_t)((((uint64_t)w1 << 32) | w0) >> sh);
-        }
-        if (bi + 4 < n_blocks) load_block(bi + 4);          // the next block of this wave travels during the rest
+        const uint32_t okbits = ok_cur;
+        if (bi + 4 < n_blocks) load_block(bi + 4, ok_next);  // the next block of this wave travels during the rest
+        ok_cur = ok_next;
+        ok_next = rows_that_count(bi + 8);
 
         // ---- online softmax of column x over the 16 rows this lane holds: 8 (v / 4) + 4 h + v % 4 -----------
         float mx = NEG_BIG;
