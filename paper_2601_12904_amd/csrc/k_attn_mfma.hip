@@ -831,26 +831,26 @@ struct QueryScratch {
     size_t flags_elems;
 };
 
+// Raises the kernels' dynamic LDS limit, once per process (C++ initialises a function-local static exactly once,
+// also when several host threads arrive together).
 template <int G>
 hipError_t set_kernel_attributes() {
-    const size_t lds_fast = sizeof(Rings) > EPILOGUE_LDS ? sizeof(Rings) : EPILOGUE_LDS;
-    const size_t lds_safe = (size_t)IMG_BYTES > EPILOGUE_LDS ? (size_t)IMG_BYTES : EPILOGUE_LDS;
-    static bool attr_set = false;
-    if (attr_set) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 1>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 2>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_combine_kernel<G>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)EPILOGUE_LDS);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_running_max_kernel<G>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_safe);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-    return hipSuccess;
+    static const hipError_t once = [] {
+        const size_t lds_fast = sizeof(Rings) > EPILOGUE_LDS ? sizeof(Rings) : EPILOGUE_LDS;
+        const size_t lds_safe = (size_t)IMG_BYTES > EPILOGUE_LDS ? (size_t)IMG_BYTES : EPILOGUE_LDS;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_combine_kernel<G>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)EPILOGUE_LDS);
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_running_max_kernel<G>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_safe);
+    }();
+    return once;
 }
 
 // Packing pass of one query: tile images of its effective K/V into sc.images; fills the query's line of the table.

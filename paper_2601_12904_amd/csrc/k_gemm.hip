@@ -368,21 +368,24 @@ int g_gemm_split = 1;               // 0: never split the tail (for tests)
 template <int EPI, int WF>
 hipError_t launch_gemm_wf(GemmArgs g, hipStream_t st) {
     using TL = Tiling<WF>;
-    static bool attr_set = false;
-    static int n_cu = 0;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI, WF>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_fixup_kernel<EPI, WF>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-        if (e != hipSuccess) return e;
+    // once per process (a function-local static is initialised exactly once, also under concurrent first calls)
+    struct Setup { hipError_t err; int n_cu; };
+    static const Setup setup = [] {
+        Setup r{hipSuccess, 0};
+        r.err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI, WF>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        if (r.err != hipSuccess) return r;
+        r.err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_fixup_kernel<EPI, WF>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        if (r.err != hipSuccess) return r;
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
-            return hipErrorInvalidDevice;
-        attr_set = true;
-    }
+            hipDeviceGetAttribute(&r.n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || r.n_cu <= 0)
+            r.err = hipErrorInvalidDevice;
+        return r;
+    }();
+    if (setup.err != hipSuccess) return setup.err;
+    const int n_cu = setup.n_cu;
     // One workgroup per CU at a time (the LDS ring fills it), so a launch runs in rounds of n_cu tiles and a last round
     // of `rest` tiles leaves CUs idle.  The tiles of that round are split along K over n_cu / rest workgroups each: the
     // round then takes 1 / n_parts of a tile's time, and the launch rest / n_cu rounds less.
