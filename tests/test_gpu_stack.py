@@ -178,3 +178,47 @@ def test_two_layer_stack_against_oracle():
         H.assert_close(H.host(v_cache[l]), want_v, "bf16", f"layer {l} V cache")
     H.assert_close(H.host(h), ho, "bf16", "stack output")
     ctx.close()
+
+
+def test_full_size_layer_sampled():
+    """One decoder layer at the benchmark's size (hidden 4096, FFN 14336, config 2's prompt: 2970 rows at 15 %), in the
+    launch configuration `bench.py --config 5` times (256-feature workgroups, tail of the down projection split along
+    K): the fresh K/V of all rows and the layer output on sampled rows against the oracle, which follows the pipeline
+    store by store (the Q/K/V projection for all rows, everything after it for the sampled ones)."""
+    from paper_2601_12904_amd import stack as S
+    rng = np.random.default_rng(12)
+    hidden, ffn = 4096, 14336
+    Hq, Hkv, d = SHAPE.n_q_heads, SHAPE.n_kv_heads, SHAPE.head_dim
+    w = synth.config_17k(seed=0)
+    k = orc.topk_count(w.L_ctx, w.ratio)
+    sel = np.sort(rng.choice(w.L_ctx, size=k, replace=False))
+    qi = np.concatenate([sel, w.L_ctx + np.arange(w.nq)]).astype(np.int64)
+    R = len(qi)
+    ctx = H.make_ctx(SHAPE, w.L, w.n_chunks, w.nq)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(8)
+    layer = S.random_layer(hidden, ffn, Hq, Hkv, d, gen)
+    st = S.SelectivePrefillStack(ctx, [layer], hidden, ffn)
+    h0 = bf(rng.standard_normal((R, hidden)))
+    k_cache = torch.zeros((w.L, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    v_cache = torch.zeros((w.L, Hkv, d), dtype=torch.bfloat16, device="cuda")
+    v_cache[: w.L_ctx] = H.dev(w.v_cached, "bf16")
+    h = H.dev(h0, "bf16")
+    qi_d = torch.from_numpy(qi.astype(np.int32)).cuda()
+    st.forward(h, qi_d, [H.dev(w.k_cached, "bf16")], [k_cache], [v_cache], w.chunk_offsets, w.src_pos0, w.nq, w.L)
+    torch.cuda.synchronize()
+
+    rnd = lambda t: synth.round_to_storage(np.asarray(t, dtype=np.float32), "bf16").astype(np.float64)
+    wd = {n: H.host(getattr(layer, n)) for n in ("g1", "w_qkv", "w_o", "g2", "w_gate_up", "w_down")}
+    kc = np.zeros((w.L, Hkv, d))
+    vc = np.zeros((w.L, Hkv, d))
+    kc[: w.L_ctx] = rnd(orc.rope_shift(w.k_cached, w.chunk_offsets, w.src_pos0, None, SHAPE.rope_base))
+    vc[: w.L_ctx] = w.v_cached
+    rows = np.unique(np.concatenate([[0, R - 1], rng.choice(R, size=14, replace=False)]))
+    ho, k_new, v_new = orc.selective_prefill_layer(h0.astype(np.float64), qi, kc, vc, wd, Hq, Hkv, d, SHAPE.rope_base, 1e-5,
+                                                   round_fn=rnd, rows=rows)
+    idx = torch.from_numpy(qi).cuda()
+    H.assert_close(H.host(k_cache[idx]), k_new, "bf16", "fresh K rows written back")
+    H.assert_close(H.host(v_cache[idx]), v_new, "bf16", "fresh V rows written back")
+    H.assert_close(H.host(h[torch.from_numpy(rows).cuda()]), ho, "bf16", "layer output, sampled rows")
+    ctx.close()
