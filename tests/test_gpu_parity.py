@@ -514,10 +514,12 @@ def test_attention_split_with_runaway_logits():
     ctx.close()
 
 
-def test_full_size_low_ratio_split_sampled():
-    """Config 2's prompt at a 5 % recompute ratio: few row tiles, so the default launch splits the key range.
+@pytest.mark.parametrize("ratio", [0.05, 0.30, 1.0])
+def test_full_size_ratio_sweep_sampled(ratio):
+    """Config 3's sweep on config 2's prompt, in the launch configuration of `bench.py --ratio`: at 5 % there are few row
+    tiles, so the default launch splits the key range; at 30 % and 100 % it does not; 100 % is full causal prefill.
     Attention output checked against the oracle on sampled rows."""
-    w = synth.config_17k(seed=0, ratio=0.05)
+    w = synth.config_17k(seed=0, ratio=ratio)
     dt = w.shape.dtype
     rng = np.random.default_rng(0)
     k = orc.topk_count(w.L_ctx, w.ratio)
