@@ -154,3 +154,19 @@ def test_decode_attn_both_kernels(seed):
         got, lse, _ = run_gpu(bt, generic=generic)
         H.assert_close(got, want, "bf16", f"decode attention (generic={generic})")
         assert np.max(np.abs(lse - want_lse)) <= 2e-3
+
+
+def test_decode_attn_full_size_sampled():
+    """The launch configuration `bench.py --config 7` times on its shared store: 32 queries, each over 16 of 64 cached
+    1024-token chunks with 15 % of their rows stale, plus an exclusive page of 2978 rows.  Three of the queries against
+    the oracle."""
+    rng = np.random.default_rng(5)
+    nb = 32
+    prompts = tuple(tuple(int(c) for c in rng.choice(64, size=16, replace=False)) for _ in range(nb))
+    bt = make_batch(SHAPES["llama_bf16"], 21, chunk_lens=(1024,) * 64, prompts=prompts, nq=(512,) * nb, n_gen=(8,) * nb)
+    got, got_lse, _ = run_gpu(bt)
+    for b in (0, 13, 31):
+        want, want_lse = orc.decode_attn(bt["q"][[b]], bt["k_store"], bt["v_store"], [bt["segments"][b]], [bt["stale"][b]],
+                                         [bt["k_pages"][b]], [bt["v_pages"][b]], bt["shape"].rope_base)
+        H.assert_close(got[[b]], want, "bf16", f"decode output of query {b}")
+        assert np.max(np.abs(got_lse[[b]] - want_lse)) <= 2e-3
