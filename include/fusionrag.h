@@ -18,6 +18,10 @@
  *   - Every call enqueues its kernels on the given HIP stream (a hipStream_t passed as void*,
  *     NULL = the default stream) and returns without synchronising it.  Calls that share a
  *     context share its workspace and must be stream-ordered with respect to each other.
+ *     After fr_create no call allocates, frees or synchronises anything, and scratch memory is cleared by
+ *     kernels, so a sequence of calls can be captured into a HIP graph and replayed (run each call once
+ *     eagerly first: a kernel's shared-memory limit is raised at its first launch, outside any capture;
+ *     FR_OPT_ATTN_KERNEL_TIMER records events and is for eager runs).
  *   - Positions and token indices are 0-based (the paper counts from 1).
  *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).  Logits are scaled by
  *     1/sqrt(head_dim).

@@ -365,6 +365,68 @@ def test_chained_layer(name, seed):
     ctx.close()
 
 
+def test_layer_under_hip_graph():
+    """The four calls captured once into a HIP graph and replayed with different cache contents, the program's own eager
+    work and synchronisations between the replays: every replay equals the eager calls on the same inputs bit for bit
+    (the calls allocate nothing, synchronise nothing and clear their scratch with kernels, so they can be captured)."""
+    w = workloads()["small_bf16"](2)
+    dt, tdt = w.shape.dtype, H.TORCH_DTYPE[w.shape.dtype]
+    Hq, Hkv, d = w.shape.n_q_heads, w.shape.n_kv_heads, w.shape.head_dim
+    _, _, k, _ = staged(w)
+    R = k + w.nq
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    rng = np.random.default_rng(4)
+    variants = [(H.dev(w.k_cached, dt), H.dev(w.v_cached, dt))]
+    for _ in range(2):   # two more stale caches of the same prompt
+        noise = lambda a: synth.round_to_storage((a + 0.2 * rng.standard_normal(a.shape) * a.std()).astype(np.float32), dt)
+        variants.append((H.dev(noise(w.k_cached), dt), H.dev(noise(w.v_cached), dt)))
+    q_question = H.dev(w.q_question, dt)
+    q_full, k_full, v_full = H.dev(w.q_full, dt), H.dev(w.k_full, dt), H.dev(w.v_full, dt)
+    # static buffers of the captured step
+    k_in = torch.empty_like(variants[0][0])
+    k_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    v_cache = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
+    qi = torch.empty(R, dtype=torch.int32, device="cuda")
+    q_rows = torch.empty((R, Hq, d), dtype=tdt, device="cuda")
+    k_new = torch.empty((R, Hkv, d), dtype=tdt, device="cuda")
+    v_new = torch.empty((R, Hkv, d), dtype=tdt, device="cuda")
+    out = torch.empty((R, Hq, d), dtype=tdt, device="cuda")
+
+    def step():
+        ctx.fr_rope_shift(k_in, k_cache, w.chunk_offsets, w.src_pos0)
+        ctx.fr_score_select(q_question, w.nq, k_cache, w.chunk_offsets, k, B.FR_NORM_PER_CHUNK, None, qi)
+        idx = qi.long()                                   # the harness's stand-in for the QKV projection of the chosen rows
+        q_rows.copy_(q_full[idx]); k_new.copy_(k_full[idx]); v_new.copy_(v_full[idx])
+        ctx.fr_sparse_prefill_attn(q_rows, qi, R, k_cache, v_cache, w.L, k_new, v_new, out)
+        ctx.fr_kv_scatter(k_new, v_new, qi, R, k_cache, v_cache, w.L)
+
+    def load(i):
+        k_in.copy_(variants[i][0])
+        v_cache.zero_()
+        v_cache[: w.L_ctx] = variants[i][1]
+
+    eager = []
+    for i in range(3):
+        load(i)
+        step()
+        torch.cuda.synchronize()
+        eager.append((qi.clone(), out.clone(), k_cache.clone(), v_cache.clone()))
+    graph = torch.cuda.CUDAGraph()
+    load(0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        step()
+    for i in (1, 0, 2, 1):
+        load(i)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = eager[i]
+        assert torch.equal(qi, want[0]) and torch.equal(out, want[1])
+        assert torch.equal(k_cache, want[2]) and torch.equal(v_cache, want[3])
+    ctx.close()
+
+
 def test_attention_softmax_modes_agree():
     """The running-maximum kernel alone (forced through fr_set_option) gives the oracle's result too."""
     w = workloads()["small_bf16"](5)
