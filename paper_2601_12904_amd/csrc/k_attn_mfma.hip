@@ -98,6 +98,11 @@ struct Geometry {
     // ordinal counts the row tiles of a query from the longest one; ordinal < n_row_tiles
     __device__ __forceinline__ void init(const int32_t* __restrict__ q_index, int R, int Hkv, int n_row_tiles,
                                          int g_, int split_, int ordinal) {
+        init_rows(Hkv, n_row_tiles, g_, split_, ordinal);
+        init_positions(q_index, R);
+    }
+    // The part that does not read the Q index: which rows and heads the lane's two columns are.
+    __device__ __forceinline__ void init_rows(int Hkv, int n_row_tiles, int g_, int split_, int ordinal) {
         const int tid = threadIdx.x, lane = tid & 63;
         wave = tid >> 6;
         x = lane & 31;
@@ -113,8 +118,12 @@ struct Geometry {
             const int r = row0 + wave * TRW + (col % TRW);
             col_row[nb] = r;                                 // rows past the end compute a copy of the last
             col_head[nb] = g * G + col / TRW;                // row and are never stored
-            col_pos[nb] = q_index[min(r, R - 1)];
         }
+    }
+    // The positions of the rows, from the Q index.
+    __device__ __forceinline__ void init_positions(const int32_t* __restrict__ q_index, int R) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) col_pos[nb] = q_index[min(col_row[nb], R - 1)];
         const int p_first = q_index[row0];                   // rows ascend: every key <= p_first is visible to all
         const int p_max = q_index[min(R, row0 + TR) - 1];    // the workgroup's furthest key
         wp_max = q_index[min(row0 + wave * TRW + TRW, R) - 1];   // a wave past the end copies the last row
@@ -542,19 +551,17 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
     float* __restrict__ lse_out = aq.lse;
     int32_t* __restrict__ redo_flags = aq.flags;
     const int R = aq.R, n_img_tiles = aq.n_img_tiles;
+    // ---- prologue.  Everything that does not depend on the Q index is requested first (the query fragments, and K
+    //      image 0 for the exponent reference), then the Q index itself, so that the three memory round trips of the
+    //      prologue overlap instead of following one another. ------------------------------------------------------
     Geometry<G> ge;
-    ge.init(q_index, R, Hkv, n_row_tiles, bw.g, bw.split, bw.ordinal);
+    ge.init_rows(Hkv, n_row_tiles, bw.g, bw.split, bw.ordinal);
     const int x = ge.x, h = ge.h;
-    // this workgroup's key tiles [kb, ke)
-    const int per_split = (ge.n_kt + NS - 1) / NS;
-    const int kb = ge.split * per_split, ke = min(ge.n_kt, kb + per_split);
-    float* part = (NS > 1) ? partials + ((size_t)ge.item * NS + ge.split) * PART_FLOATS + threadIdx.x : nullptr;
-    if (NS > 1 && kb >= ke) {   // fewer key tiles than parts: this one adds nothing
-        for (int r = 0; r < PART_REGS; ++r) part[r * 256] = 0.f;
-        return;
-    }
     FragOffsets fo;
     fo.init(x, h);
+    const unsigned char* head_images = images + (size_t)ge.g * n_img_tiles * IMG_BYTES;
+    const int wave = __builtin_amdgcn_readfirstlane(ge.wave), lane = threadIdx.x & 63;
+    dma_image(head_images, rg.k[2], wave, lane);   // K image 0 into ring slot 2: the exponent reference comes from it
 
     // Q fragments: B operand of S^T = K Q^T, kept in registers for the whole loop
     bf16x8 qf[2][8];
@@ -563,6 +570,15 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
         const __bf16* qp = q_rows + ((size_t)min(ge.col_row[nb], R - 1) * Hq + ge.col_head[nb]) * D + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    }
+    ge.init_positions(q_index, R);
+    // this workgroup's key tiles [kb, ke)
+    const int per_split = (ge.n_kt + NS - 1) / NS;
+    const int kb = ge.split * per_split, ke = min(ge.n_kt, kb + per_split);
+    float* part = (NS > 1) ? partials + ((size_t)ge.item * NS + ge.split) * PART_FLOATS + threadIdx.x : nullptr;
+    if (NS > 1 && kb >= ke) {   // fewer key tiles than parts: this one adds nothing
+        for (int r = 0; r < PART_REGS; ++r) part[r * 256] = 0.f;
+        return;                 // (the hardware waits for the outstanding copy before it retires the wave)
     }
     f32x16 o[4][2];
 #pragma unroll
@@ -573,15 +589,12 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
             for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
     float lsum[2] = {0.f, 0.f};
 
-    // ---- prologue: K images 0 and 1 and V image 0 land in LDS ---------------------------------------------
-    const unsigned char* head_images = images + (size_t)ge.g * n_img_tiles * IMG_BYTES;
-    const int wave = __builtin_amdgcn_readfirstlane(ge.wave), lane = threadIdx.x & 63;
+    // K images kb and kb + 1 and V image kb land in LDS
     const int n_kt = ge.n_kt;
     const unsigned char* first_image = head_images + (size_t)kb * IMG_BYTES;
     dma_image(first_image, rg.k[0], wave, lane);
     dma_image(first_image + K_IMG_BYTES, rg.vt[0], wave, lane);
     if (kb + 1 < n_kt) dma_image(first_image + IMG_BYTES, rg.k[1], wave, lane);
-    if (NS > 1 && kb > 0) dma_image(head_images, rg.k[2], wave, lane);   // K image 0, for the exponent reference only
     {   // V ring slot 2 is read (against all-zero weights) by the very first step: it must hold finite numbers
         const u32x4 z = {0u, 0u, 0u, 0u};
         for (int i = threadIdx.x; i < V_IMG_BYTES / 16; i += 256) *reinterpret_cast<u32x4*>(&rg.vt[2][16 * i]) = z;
@@ -591,7 +604,7 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
 
     // exponent reference of each column = the maximum of its logits over the visible ones of keys 0..31
     f32x16 s_a[2], s_b[2];
-    qk_half((NS > 1 && kb > 0) ? rg.k[2] : rg.k[0], 0, qf, fo, s_a);
+    qk_half(rg.k[2], 0, qf, fo, s_a);
     float mref[2];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
@@ -604,10 +617,8 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
         t = fmaxf(t, __shfl_xor(t, 32));   // key 0 (held by the h = 0 lane) is visible to every row
         mref[nb] = t * scale_log2e;
     }
-    if (NS > 1 && kb > 0) {
-        __syncthreads();                     // ring slot 2 is free again before the loop copies into it
-        qk_half(rg.k[0], 0, qf, fo, s_a);    // logits of this part's first 32 keys
-    }
+    __syncthreads();                                      // ring slot 2 is free again before the loop copies into it
+    if (NS > 1 && kb > 0) qk_half(rg.k[0], 0, qf, fo, s_a);   // logits of this part's first 32 keys (else: those above)
     bf16x8 pf_a[2][2], pf_b[2][2];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
