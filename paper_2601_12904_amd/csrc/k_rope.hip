@@ -50,14 +50,19 @@ __global__ __launch_bounds__(256) void rope_shift_kernel(const T* __restrict__ s
     if (LAYOUT == FR_ROPE_INTERLEAVED) {
         const int vec_per_head = d / N;
         const int nvec = ntok * Hkv * vec_per_head;
-#pragma unroll 4
+        // vec_per_head divides 256 (d is 64 or 128), so a thread meets the same slice of the head row in every step:
+        // its (cos, sin) values stay in registers
+        const int p0 = (threadIdx.x % vec_per_head) * (N / 2);  // first rotary pair of this thread's vectors
+        float2 tw[N / 2];
+#pragma unroll
+        for (int e = 0; e < N / 2; ++e) tw[e] = cs[p0 + e];
+#pragma unroll 8
         for (int i = threadIdx.x; i < nvec; i += 256) {
-            const int p0 = (i % vec_per_head) * (N / 2);  // first rotary pair of this vector
             Vec16<T> x = *reinterpret_cast<const Vec16<T>*>(s + (size_t)i * N);
             Vec16<T> y;
 #pragma unroll
             for (int e = 0; e < N / 2; ++e) {
-                const float2 t = cs[p0 + e];
+                const float2 t = tw[e];
                 const float a = Elem<T>::to_f32(x.v[2 * e]), b = Elem<T>::to_f32(x.v[2 * e + 1]);
                 y.v[2 * e] = Elem<T>::from_f32(a * t.x - b * t.y);
                 y.v[2 * e + 1] = Elem<T>::from_f32(b * t.x + a * t.y);
