@@ -166,7 +166,8 @@ fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const
  *   k_store  dev [n_store_rows, Hkv, d], read only
  *   chunk_offsets, chunk_store_row0, chunk_src_pos0  host, as in fr_sparse_prefill_attn_shared
  *   norm     FR_NORM_PER_CHUNK or FR_NORM_GLOBAL
- * Everything else as in fr_score_select.  FR_ERR_UNSUPPORTED unless the context is bf16 with head_dim 128. */
+ * Everything else as in fr_score_select.  Contexts the tiled kernels do not take (fp32, head_dim 64, group sizes
+ * other than 1, 2, 4, 8) gather the shifted keys into the context's workspace and run the generic kernel. */
 fr_status fr_score_select_shared(fr_ctx* ctx, const void* q_question, int32_t nq, const void* k_store,
                                  int64_t n_store_rows, const int32_t* chunk_offsets, const int32_t* chunk_store_row0,
                                  const int32_t* chunk_src_pos0, int32_t n_chunks, int64_t k, int32_t norm,
@@ -222,8 +223,9 @@ fr_status fr_sparse_prefill_attn_writeback(fr_ctx* ctx, const void* q_rows, cons
  *   chunk_store_row0, chunk_src_pos0   host [n_chunks]
  *   L                  prompt length; every position in [L_ctx, L) must be listed in q_index
  *   q_rows, q_index, R, k_new, v_new (both required), out, lse_out: as in fr_sparse_prefill_attn
- * Errors as fr_sparse_prefill_attn, plus FR_ERR_INVALID_ARG for chunk rows outside the store and
- * FR_ERR_UNSUPPORTED unless the context is bf16 with head_dim 128. */
+ * Errors as fr_sparse_prefill_attn, plus FR_ERR_INVALID_ARG for chunk rows outside the store.  Contexts the tiled
+ * kernels do not take (fp32, head_dim 64, group sizes other than 1, 2, 4, 8) gather the query's shifted keys and its
+ * values into the context's workspace (2 x max_tokens rows, part of fr_workspace_bytes) and run the generic kernel. */
 fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const int32_t* q_index, int32_t R,
                                         const void* k_store, const void* v_store, int64_t n_store_rows,
                                         const int32_t* chunk_offsets, const int32_t* chunk_store_row0,
@@ -241,7 +243,9 @@ fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const i
  *              query); owned by the caller, contents undefined afterwards, must stay untouched until the call's
  *              work on the stream has finished
  * Every query is validated before the first launch.  Errors as fr_sparse_prefill_attn_shared (the message names
- * the query), plus FR_ERR_WORKSPACE when workspace_bytes is too small. */
+ * the query), plus FR_ERR_WORKSPACE when workspace_bytes is too small.  Contexts served by the generic kernel run
+ * the queries one after the other from the context's own workspace: fr_shared_batch_workspace_bytes is 0 for them
+ * and workspace may be NULL. */
 typedef struct {
     const void* q_rows;                /* dev [R, Hq, d] */
     const int32_t* q_index;            /* dev [R] */

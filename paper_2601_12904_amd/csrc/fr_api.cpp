@@ -149,6 +149,11 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_rr = take((size_t)max_tokens * (s.d / 2) * sizeof(float2));
     w.gemm_partials_bytes = (s.dtype == FR_BF16) ? gemm_partials_bytes() : 0;
     const size_t o_gp = take(w.gemm_partials_bytes);
+    // shapes without a tiled path serve the shared chunk store through a gathered copy of the query's keys and values
+    const size_t store_copy_bytes =
+        (attn_mfma_supported(s) && score_mfma_supported(s)) ? 0 : (size_t)max_tokens * s.Hkv * s.d * s.esize;
+    const size_t o_sk = take(store_copy_bytes);
+    const size_t o_sv = take(store_copy_bytes);
     w.bytes = off;
     hipError_t e = hipMalloc((void**)&w.base, w.bytes);
     if (e != hipSuccess) {
@@ -171,6 +176,8 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.decode_rot = (float2*)(w.base + o_drot);
     w.rope_rows = (float2*)(w.base + o_rr);
     w.gemm_partials = w.gemm_partials_bytes ? (float*)(w.base + o_gp) : nullptr;
+    w.store_k = store_copy_bytes ? (void*)(w.base + o_sk) : nullptr;
+    w.store_v = store_copy_bytes ? (void*)(w.base + o_sv) : nullptr;
     ctx->has_device = true;
     *out = ctx;
     return FR_OK;
@@ -302,7 +309,7 @@ fr_status fr_rope_shift(fr_ctx* ctx, const void* k_src, void* k_dst, const int32
     hipError_t e = launch_rope_table(s, dl, n_chunks, ctx->ws.rope_table, hs);
     if (e != hipSuccess) return hip_fail(ctx, "rope table launch", e);
     e = launch_rope_shift(s, k_src, k_dst, ct, max_len, ctx->ws.rope_table, n_batch, src_batch_stride,
-                          dst_batch_stride, hs);
+                          dst_batch_stride, nullptr, hs);
     if (e != hipSuccess) return hip_fail(ctx, "rope shift launch", e);
     return FR_OK;
 }
@@ -388,6 +395,42 @@ fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const
     return FR_OK;
 }
 
+// Shapes the tiled kernels do not take: the query's keys (moved to their prompt positions, Appendix A) and, when
+// v_store is given, its values are gathered from the chunk store into the workspace's [L, Hkv, d] copies, on which
+// the generic kernels then run.  Values go through the same kernel with a rotation by zero positions, which is
+// the identity in every arithmetic (cos 0 = 1, sin 0 = 0).  Rows [L_ctx, L) are cleared.
+static fr_status gather_from_store(fr_ctx* ctx, const void* k_store, const void* v_store, const ChunkTable& ct,
+                                   const int32_t* chunk_store_row0, const ChunkDeltas& dl, int64_t L, hipStream_t hs) {
+    const Shape& s = ctx->shape;
+    const int64_t L_ctx = ct.off[ct.n];
+    ChunkRows rows{};
+    int max_len = 0;
+    for (int c = 0; c < ct.n; ++c) {
+        rows.row0[c] = chunk_store_row0[c];
+        max_len = std::max(max_len, ct.off[c + 1] - ct.off[c]);
+    }
+    hipError_t e = hipSuccess;
+    if (v_store && L_ctx > 0) {
+        const ChunkDeltas zero{};
+        e = launch_rope_table(s, zero, ct.n, ctx->ws.rope_table, hs);
+        if (e == hipSuccess) e = launch_rope_shift(s, v_store, ctx->ws.store_v, ct, max_len, ctx->ws.rope_table, 1, 0, 0, &rows, hs);
+        if (e != hipSuccess) return hip_fail(ctx, "value gather launch", e);
+    }
+    if (L_ctx > 0) {
+        e = launch_rope_table(s, dl, ct.n, ctx->ws.rope_table, hs);
+        if (e == hipSuccess) e = launch_rope_shift(s, k_store, ctx->ws.store_k, ct, max_len, ctx->ws.rope_table, 1, 0, 0, &rows, hs);
+        if (e != hipSuccess) return hip_fail(ctx, "key gather launch", e);
+    }
+    const int64_t row_words = (int64_t)s.Hkv * s.d * s.esize / 4;
+    if (L > L_ctx) {
+        e = launch_clear_words((uint32_t*)ctx->ws.store_k + L_ctx * row_words, (L - L_ctx) * row_words, hs);
+        if (e == hipSuccess && v_store)
+            e = launch_clear_words((uint32_t*)ctx->ws.store_v + L_ctx * row_words, (L - L_ctx) * row_words, hs);
+        if (e != hipSuccess) return hip_fail(ctx, "clear launch", e);
+    }
+    return FR_OK;
+}
+
 fr_status fr_score_select_shared(fr_ctx* ctx, const void* q_question, int32_t nq, const void* k_store,
                                  int64_t n_store_rows, const int32_t* chunk_offsets, const int32_t* chunk_store_row0,
                                  const int32_t* chunk_src_pos0, int32_t n_chunks, int64_t k, int32_t norm,
@@ -425,8 +468,6 @@ fr_status fr_score_select_shared(fr_ctx* ctx, const void* q_question, int32_t nq
         return fail(ctx, FR_ERR_INVALID_ARG, "k_store is NULL or not 16-byte aligned");
     if ((reinterpret_cast<uintptr_t>(scores_out) & 3u) || (reinterpret_cast<uintptr_t>(q_index_out) & 3u))
         return fail(ctx, FR_ERR_INVALID_ARG, "scores_out / q_index_out must be 4-byte aligned");
-    if (!score_mfma_supported(s))
-        return fail(ctx, FR_ERR_UNSUPPORTED, "the shared-store scoring needs bf16, head_dim 128 and a group size of 1, 2, 4 or 8");
     if (L_ctx == 0 && nq == 0) return FR_OK;
     if ((st = need_device(ctx)) != FR_OK) return st;
     hipStream_t hs = (hipStream_t)stream;
@@ -435,6 +476,10 @@ fr_status fr_score_select_shared(fr_ctx* ctx, const void* q_question, int32_t nq
     if (L_ctx > 0 && need_scores) {
         if (nq == 0) {   // no question rows: every score is an empty sum (the generic kernel writes the zeros; no key is read)
             hipError_t e = launch_score_simt(s, q_question, 0, k_store, ct, norm, ctx->ws, scores, hs);
+            if (e != hipSuccess) return hip_fail(ctx, "score launch", e);
+        } else if (!score_mfma_supported(s)) {   // no tiled kernel for this shape: gathered keys, generic kernel
+            if ((st = gather_from_store(ctx, k_store, nullptr, ct, chunk_store_row0, dl, L_ctx, hs)) != FR_OK) return st;
+            hipError_t e = launch_score_simt(s, q_question, nq, ctx->ws.store_k, ct, norm, ctx->ws, scores, hs);
             if (e != hipSuccess) return hip_fail(ctx, "score launch", e);
         } else {
             hipError_t e = launch_rope_table(s, dl, n_chunks, ctx->ws.rope_table, hs);
@@ -543,8 +588,6 @@ static fr_status check_shared_query(fr_ctx* ctx, const void* q_rows, const int32
         return fail(ctx, FR_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     if ((reinterpret_cast<uintptr_t>(q_index) & 3u) || (reinterpret_cast<uintptr_t>(lse_out) & 3u))
         return fail(ctx, FR_ERR_INVALID_ARG, "q_index / lse_out must be 4-byte aligned");
-    if (!attn_mfma_supported(ctx->shape))
-        return fail(ctx, FR_ERR_UNSUPPORTED, "the shared-store attention needs bf16, head_dim 128 and a group size of 1, 2, 4 or 8");
     sh->store_row0 = chunk_store_row0;
     return FR_OK;
 }
@@ -567,6 +610,13 @@ fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const i
     hipStream_t hs = (hipStream_t)stream;
     hipError_t e = launch_inv_index(q_index, R, L, ctx->ws.inv_index, hs);
     if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
+    if (!attn_mfma_supported(s)) {   // no tiled kernel for this shape: gathered keys and values, generic kernel
+        if ((st = gather_from_store(ctx, k_store, v_store, sh.ct, chunk_store_row0, dl, L, hs)) != FR_OK) return st;
+        e = launch_attn_simt(s, q_rows, q_index, R, ctx->ws.store_k, ctx->ws.store_v, L, k_new, v_new, ctx->ws.inv_index, out,
+                             lse_out, hs);
+        if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
+        return FR_OK;
+    }
     e = launch_rope_table(s, dl, n_chunks, ctx->ws.rope_table, hs);
     if (e != hipSuccess) return hip_fail(ctx, "rope table launch", e);
     sh.table = ctx->ws.rope_table;
@@ -605,6 +655,7 @@ BatchScratch batch_scratch(const Shape& s, int64_t L, int64_t R, size_t base) {
 
 int64_t fr_shared_batch_workspace_bytes(const fr_ctx* ctx, int32_t n_queries, int64_t max_L) {
     if (!ctx || n_queries <= 0 || max_L <= 0) return 0;
+    if (!attn_mfma_supported(ctx->shape)) return 0;   // such shapes are served query by query from the context's own workspace
     const int64_t group = n_queries < ATTN_MAX_BATCH ? n_queries : ATTN_MAX_BATCH;
     return group * (int64_t)batch_scratch(ctx->shape, max_L, max_L, 0).end;
 }
@@ -643,6 +694,17 @@ fr_status fr_sparse_prefill_attn_shared_batch(fr_ctx* ctx, const fr_shared_query
         deltas.push_back(dl);
     }
     if (work.empty()) return FR_OK;
+    if (!attn_mfma_supported(s)) {   // no tiled kernel for this shape: one query after the other, on the same stream
+        for (int i = 0; i < n_queries; ++i) {
+            const fr_shared_query& q = queries[i];
+            if (q.R == 0) continue;
+            fr_status st = fr_sparse_prefill_attn_shared(ctx, q.q_rows, q.q_index, q.R, k_store, v_store, n_store_rows,
+                                                         q.chunk_offsets, q.chunk_store_row0, q.chunk_src_pos0, q.n_chunks, q.L,
+                                                         q.k_new, q.v_new, q.out, q.lse_out, stream);
+            if (st != FR_OK) return st;
+        }
+        return FR_OK;
+    }
     // groups of at most ATTN_MAX_BATCH queries share one attention launch; the groups reuse the workspace (the
     // stream orders them)
     for (size_t g0 = 0; g0 < work.size(); g0 += ATTN_MAX_BATCH) {

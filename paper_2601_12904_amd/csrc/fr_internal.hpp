@@ -19,6 +19,10 @@ struct ChunkTable {
 struct ChunkDeltas {
     int32_t delta[FR_MAX_CHUNKS];
 };
+// Store row of prompt position j inside chunk c of a query over a shared chunk store: row0[c] + (j - chunk offset).
+struct ChunkRows {
+    int32_t row0[FR_MAX_CHUNKS];
+};
 
 struct Shape {
     int Hq, Hkv, d, G;
@@ -43,6 +47,8 @@ struct Workspace {
     float* qsum = nullptr;              // [Hkv][d] question queries summed per KV head (raw scores), then partial sums
     uint32_t* select_tmp = nullptr; // state, histogram, per-wave counts and candidate list of the selection kernels
     int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
+    void* store_k = nullptr;        // shapes without a tiled path: a query's keys / values gathered from a shared
+    void* store_v = nullptr;        // chunk store ([max_tokens, Hkv, d] each), for the generic kernels
     float* gemm_partials = nullptr; // partial sums of the GEMM tiles that are split along K
     size_t gemm_partials_bytes = 0;
     size_t attn_flags_elems = 0;
@@ -88,9 +94,12 @@ namespace fr {
 // Launchers.  Each returns hipSuccess or the launch error; none synchronises.
 hipError_t launch_rope_table(const Shape& s, const ChunkDeltas& deltas, int n_chunks, float2* table,
                              hipStream_t st);
+// src_rows != NULL: chunk c's source rows start at src row src_rows->row0[c] (a chunk store) instead of at its
+// prompt offset.
 hipError_t launch_rope_shift(const Shape& s, const void* src, void* dst, const ChunkTable& ct,
                              int max_chunk_len, const float2* table, int n_batch, int64_t src_stride,
-                             int64_t dst_stride, hipStream_t st);
+                             int64_t dst_stride, const ChunkRows* src_rows, hipStream_t st);
+hipError_t launch_clear_words(uint32_t* words, int64_t n_words, hipStream_t st);
 hipError_t launch_kv_scatter(const Shape& s, const void* k_new, const void* v_new, const int32_t* q_index,
                              int R, void* k_cache, void* v_cache, hipStream_t st);
 

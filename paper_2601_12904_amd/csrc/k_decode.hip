@@ -591,6 +591,11 @@ hipError_t launch_decode_attn(const Shape& s, const DecodeArgs& a, float* partia
     return s.d == 128 ? run_g<float, 128>(s, a, partials, rot_table, st) : run_g<float, 64>(s, a, partials, rot_table, st);
 }
 
+hipError_t launch_clear_words(uint32_t* words, int64_t n_words, hipStream_t st) {
+    if (n_words > 0) clear_words_kernel<<<dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st>>>(words, n_words);
+    return hipGetLastError();
+}
+
 hipError_t launch_mark_stale(uint32_t* bits, int64_t n_words, const int32_t* rows, int n_rows, int clear, hipStream_t st) {
     if (clear && n_words > 0)
         clear_words_kernel<<<dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st>>>(bits, n_words);

@@ -31,7 +31,7 @@ template <typename T, int LAYOUT, int TOK>
 __global__ __launch_bounds__(256) void rope_shift_kernel(const T* __restrict__ src, T* __restrict__ dst,
                                                          ChunkTable ct, const float2* __restrict__ table,
                                                          int Hkv, int d, int64_t src_stride,
-                                                         int64_t dst_stride) {
+                                                         int64_t dst_stride, ChunkRows src_rows, int from_store) {
     constexpr int N = 16 / sizeof(T);  // elements per 16-byte vector
     __shared__ float2 cs[64];          // d/2 <= 64 (cos, sin) pairs of this chunk
     const int c = blockIdx.y;
@@ -44,7 +44,9 @@ __global__ __launch_bounds__(256) void rope_shift_kernel(const T* __restrict__ s
 
     const int ntok = min(TOK, c1 - tok0);
     const size_t row = (size_t)Hkv * d;  // elements per token
-    const T* s = src + (size_t)blockIdx.z * src_stride + (size_t)tok0 * row;
+    // source row of the block's first token: its prompt position, or its row in a chunk store
+    const size_t src_tok0 = from_store ? (size_t)src_rows.row0[c] + (size_t)(tok0 - c0) : (size_t)tok0;
+    const T* s = src + (size_t)blockIdx.z * src_stride + src_tok0 * row;
     T* o = dst + (size_t)blockIdx.z * dst_stride + (size_t)tok0 * row;
 
     if (LAYOUT == FR_ROPE_INTERLEAVED) {
@@ -103,13 +105,16 @@ hipError_t launch_rope_table(const Shape& s, const ChunkDeltas& deltas, int n_ch
 
 hipError_t launch_rope_shift(const Shape& s, const void* src, void* dst, const ChunkTable& ct,
                              int max_chunk_len, const float2* table, int n_batch, int64_t src_stride,
-                             int64_t dst_stride, hipStream_t st) {
+                             int64_t dst_stride, const ChunkRows* src_rows, hipStream_t st) {
     if (ct.n == 0 || max_chunk_len == 0 || n_batch == 0) return hipSuccess;
+    const ChunkRows none{};
+    const ChunkRows& rows = src_rows ? *src_rows : none;
+    const int from_store = src_rows ? 1 : 0;
     constexpr int TOK = 32;
     dim3 grid((max_chunk_len + TOK - 1) / TOK, ct.n, n_batch);
 #define FR_ROPE_LAUNCH(T, LAY)                                                                      \
     rope_shift_kernel<T, LAY, TOK><<<grid, dim3(256), 0, st>>>((const T*)src, (T*)dst, ct, table, \
-                                                               s.Hkv, s.d, src_stride, dst_stride)
+                                                               s.Hkv, s.d, src_stride, dst_stride, rows, from_store)
     if (s.dtype == FR_BF16) {
         if (s.rope_layout == FR_ROPE_INTERLEAVED)
             FR_ROPE_LAUNCH(__bf16, FR_ROPE_INTERLEAVED);

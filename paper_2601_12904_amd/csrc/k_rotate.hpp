@@ -9,11 +9,6 @@ namespace fr {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t rot_u32x4;
 
-// Store row of prompt position j inside chunk c: rows.row0[c] + (j - chunk offset).
-struct ChunkRows {
-    int32_t row0[FR_MAX_CHUNKS];
-};
-
 template <int LAYOUT>
 __device__ __forceinline__ rot_u32x4 rotate_key_vector(rot_u32x4 own, rot_u32x4 partner, const float2* __restrict__ trow, int st_vec) {
     // own = elements 8 st_vec .. + 7 of the head row.  Interleaved pairs: (2p, 2p + 1) inside the vector.

@@ -76,11 +76,70 @@ def test_shared_store_prefill_argument_errors():
     with pytest.raises(B.FusionRAGError):      # the page is required
         ctx.fr_sparse_prefill_attn_shared(P, P, 5, P, P, 100, [0, 8, 16], [0, 8], [0, 0], 20, None, None, P)
     ctx.close()
-    c32 = H.make_ctx(synth.TINY_F32, 256, 4, 8)
-    with pytest.raises(B.FusionRAGError) as ei:
-        c32.fr_sparse_prefill_attn_shared(P, P, 5, P, P, 100, [0, 8, 16], [0, 8], [0, 0], 20, P, P, P)
-    assert ei.value.status == B.FR_ERR_UNSUPPORTED
-    c32.close()
+
+
+GENERIC_SHAPES = {
+    "f32_d64": synth.TINY_F32,
+    "f32_d128_g2": synth.LayerShape(n_q_heads=4, n_kv_heads=2, head_dim=128, dtype="f32", rope_base=500000.0),
+    "bf16_d64_g4": synth.LayerShape(n_q_heads=8, n_kv_heads=2, head_dim=64, dtype="bf16", rope_base=10000.0),
+    "bf16_d128_g3": synth.LayerShape(n_q_heads=6, n_kv_heads=2, head_dim=128, dtype="bf16", rope_base=500000.0),
+}
+
+
+@pytest.mark.parametrize("layout", [B.FR_ROPE_INTERLEAVED, B.FR_ROPE_HALF])
+@pytest.mark.parametrize("name", sorted(GENERIC_SHAPES))
+def test_shared_store_entry_points_on_shapes_without_tiled_kernels(name, layout):
+    """fp32, head_dim 64 and group sizes the tiled kernels do not take: the shared-store entry points gather the
+    query's keys (moved to their prompt positions) and values into the context's workspace and run the generic
+    kernels.  Selection scores, index set and attention output against the oracle; the batch call against the
+    one-query call, bit for bit."""
+    shape = GENERIC_SHAPES[name]
+    dt = shape.dtype
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+    w = synth.config_small_bf16(seed=13, ratio=0.2, chunk_lens=(70, 0, 133, 41, 96), nq=19, shape=shape)
+    Hq, Hkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    rng = np.random.default_rng(5)
+    lay = "half" if layout == B.FR_ROPE_HALF else "interleaved"
+    src_pos0 = rng.integers(0, 3000, size=w.n_chunks).astype(np.int32)
+    k_store, v_store, row0 = scattered_store(w, rng)
+    ks_d, vs_d = H.dev(k_store, dt), H.dev(v_store, dt)
+    ctx = H.make_ctx(shape, w.L, w.n_chunks, w.nq, rope_layout=layout)
+    k_ctx = synth.round_to_storage(orc.rope_shift(w.k_cached, w.chunk_offsets, src_pos0, None, shape.rope_base, lay), dt)
+    # selection
+    k = orc.topk_count(w.L_ctx, 0.2)
+    for norm, scope in ((B.FR_NORM_PER_CHUNK, "per_chunk"), (B.FR_NORM_GLOBAL, "global")):
+        scores = torch.zeros(w.L_ctx, dtype=torch.float32, device="cuda")
+        qi_d = torch.full((k + w.nq,), -1, dtype=torch.int32, device="cuda")
+        ctx.fr_score_select_shared(H.dev(w.q_question, dt), w.nq, ks_d, len(k_store), w.chunk_offsets, row0, src_pos0, k,
+                                   norm, scores, qi_d)
+        torch.cuda.synchronize()
+        want = orc.critical_scores(w.q_question, k_ctx, w.chunk_offsets, scope)
+        assert H.max_rel_err(scores.cpu().numpy().astype(np.float64), want) <= (2e-3 if dt == "bf16" else 1e-5)
+        H.assert_index_set(qi_d.cpu().numpy().astype(np.int64), want, k, w.nq)
+    # attention, one query and the same query twice through the batch call
+    qi = qi_d.cpu().numpy().astype(np.int64)
+    R = len(qi)
+    q_rows, k_new, v_new = H.dev(w.q_full[qi], dt), H.dev(w.k_full[qi], dt), H.dev(w.v_full[qi], dt)
+    out = torch.zeros((R, Hq, d), dtype=tdt, device="cuda")
+    lse = torch.zeros((R, Hq), dtype=torch.float32, device="cuda")
+    ctx.fr_sparse_prefill_attn_shared(q_rows, qi_d, R, ks_d, vs_d, len(k_store), w.chunk_offsets, row0, src_pos0, w.L,
+                                      k_new, v_new, out, lse)
+    torch.cuda.synchronize()
+    pad = np.zeros((w.nq, Hkv, d))
+    want, want_lse = orc.sparse_prefill_attn(w.q_full[qi], qi, np.concatenate([k_ctx, pad]),
+                                             np.concatenate([w.v_cached, pad]), w.k_full[qi], w.v_full[qi])
+    H.assert_close(H.host(out), want, dt, "shared-store attention, generic kernels")
+    assert np.max(np.abs(lse.cpu().numpy() - want_lse)) <= (2e-3 if dt == "bf16" else 1e-5)
+    assert ctx.fr_shared_batch_workspace_bytes(2, w.L) == 0       # served from the context's own workspace
+    mkq = lambda: dict(q_rows=q_rows, q_index=qi_d, R=R, chunk_offsets=w.chunk_offsets, chunk_store_row0=row0,
+                       chunk_src_pos0=src_pos0, L=w.L, k_new=k_new, v_new=v_new,
+                       out=torch.zeros_like(out), lse_out=torch.zeros_like(lse))
+    batch = [mkq(), mkq()]
+    ctx.fr_sparse_prefill_attn_shared_batch(batch, ks_d, vs_d, len(k_store), None, 0)
+    torch.cuda.synchronize()
+    for q in batch:
+        assert torch.equal(q["out"], out) and torch.equal(q["lse_out"], lse)
+    ctx.close()
 
 
 def test_shared_store_prefill_batch_of_queries():

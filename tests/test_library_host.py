@@ -196,8 +196,14 @@ def test_shared_score_select_argument_errors():
     if not torch.cuda.is_available():
         expect(B.FR_ERR_DEVICE, call)
     c.close()
+    # fp32 / head_dim 64 contexts take the same arguments (served by the generic kernels) and the same checks
     c32 = B.Context(4, 4, 64, B.FR_F32, 1e4, max_tokens=600, max_chunks=4, max_question_tokens=32)
-    with pytest.raises(B.FusionRAGError) as ei:
-        c32.fr_score_select_shared(P, 4, P, 100, [0, 8, 16], [0, 8], [0, 0], 3, B.FR_NORM_PER_CHUNK, None, P)
-    assert ei.value.status == B.FR_ERR_UNSUPPORTED
+    call32 = lambda **kw: c32.fr_score_select_shared(**{**dict(q_question=P, nq=4, k_store=P, n_store_rows=100,
+                                                              chunk_offsets=[0, 8, 16], chunk_store_row0=[0, 8],
+                                                              chunk_src_pos0=[0, 0], k=3, norm=B.FR_NORM_PER_CHUNK,
+                                                              scores_out=None, q_index_out=P), **kw})
+    expect(B.FR_ERR_INVALID_ARG, call32, chunk_store_row0=[0, 96])
+    assert c32.fr_shared_batch_workspace_bytes(2, 20) == 0
+    if not torch.cuda.is_available():
+        expect(B.FR_ERR_DEVICE, call32)
     c32.close()
