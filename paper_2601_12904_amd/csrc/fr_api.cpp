@@ -130,7 +130,9 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
         return o;
     };
     const size_t o_table = take((size_t)max_chunks * (s.d / 2) * sizeof(float2));
-    const size_t o_lse = take((size_t)s.Hq * (max_chunks + 1) * (size_t)(max_question_tokens > 0 ? max_question_tokens : 1) * 4);
+    // normalisers per (head, chunk or whole context, question token); the tiled kernels pad every row of
+    // G x question tokens to a multiple of 64
+    const size_t o_lse = take((size_t)s.Hkv * (max_chunks + 1) * ((size_t)s.G * (max_question_tokens > 0 ? max_question_tokens : 1) + 63) * 4);
     const size_t o_col = take((size_t)s.Hkv * max_tokens * 4);
     const size_t o_scores = take((size_t)max_tokens * 4);
     const size_t o_inv = take((size_t)max_tokens * 4);

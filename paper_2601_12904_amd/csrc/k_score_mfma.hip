@@ -84,6 +84,67 @@ __device__ __forceinline__ void interleave_hint() {
     }
 }
 
+// ---- streamed tiles, copied global -> LDS directly -------------------------------------------------------------
+// A streamed tile is 64 rows of 256 bytes, unpadded: row r at byte 256 r, its 16-byte chunk c in slot
+// c ^ row_key(r).  The fragment reads (lane = row x of a 32-row half, chunk 2 ks + h) then hit 16 different slots in
+// any 16 lanes that the LDS serves together, whether those are 16 rows of one h or 8 rows of both.
+constexpr int TILE_BYTES = 64 * D * 2;
+__device__ __forceinline__ int row_key(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
+
+// Byte offsets, inside a 32-row half, of this lane's eight A fragments.
+__device__ __forceinline__ void frag_offsets(int x, int h, uint32_t (&a_off)[8]) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) a_off[ks] = (uint32_t)(x * 256 + (((2 * ks + h) ^ row_key(x)) << 4));
+}
+__device__ __forceinline__ void load_frags(const unsigned char* tile, int mb, const uint32_t (&a_off)[8], bf16x8 (&a)[8]) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(tile + mb * (32 * 256) + a_off[ks]);
+}
+__device__ __forceinline__ void mfma_half(const bf16x8 (&a)[8], const bf16x8 (&bf)[2][8], f32x16 (&s)[2]) {
+    f32x16 zero;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+            s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bf[nb][ks], ks == 0 ? zero : s[nb], 0, 0, 0);
+}
+// Which LDS row this lane fills in copy j of its wave (each copy: 1 KB = 4 rows, lane = (row, slot)), and which
+// chunk of the source row belongs there.
+__device__ __forceinline__ int copy_row(int j, int wave, int lane) { return 4 * (4 * j + wave) + (lane >> 4); }
+__device__ __forceinline__ int copy_chunk(int j, int wave, int lane) { return (lane & 15) ^ row_key(copy_row(j, wave, lane)); }
+// One tile, global -> LDS without passing through registers (global_load_lds_dwordx4: lane i of a wave deposits its
+// 16 bytes at the LDS address in M0 + 16 i).  The source is a workgroup-uniform base in scalar registers plus a
+// 32-bit per-lane offset, so a copy costs the vector ALU nothing.  Written out rather than left to the builtin: with
+// it the compiler takes the pending copy for an access that may complete out of order with the LDS reads and waits
+// for all outstanding fragment reads before every matrix instruction.  Completion: the issuing wave's vmcnt, then
+// a workgroup barrier.
+__device__ __forceinline__ void dma_tile(const unsigned char* src, const uint32_t (&lane_off)[4], uint32_t lds_tile, int wave_u) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t l = lds_tile + (uint32_t)(4 * j + wave_u) * 1024u;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off[j]), "s"(src), "s"(l) : "memory");
+    }
+}
+// 64 floats (one per lane) global -> LDS the same way.
+__device__ __forceinline__ void dma_floats(const float* src, uint32_t lane_off, uint32_t lds_dst) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" : : "v"(lane_off), "s"(src), "s"(lds_dst) : "memory");
+}
+// This wave's copies have landed (vmcnt(0)) and all its LDS reads except the eight youngest (the fragments requested
+// for the next step, which come from a tile that nobody overwrites yet) have returned (lgkmcnt(8)).
+__device__ __forceinline__ void wait_copies_and_older_reads() { __builtin_amdgcn_s_waitcnt(0x0870); }
+// Workgroup barrier without the fences of __syncthreads(), which would make the compiler drain the fragment reads
+// that are meant to stay in flight across it; the empty asm statements keep it from moving LDS accesses across.
+__device__ __forceinline__ void barrier_keep_reads_in_flight() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)p);
+}
+
 // ---- pass A -------------------------------------------------------------------------------------
 // One workgroup = (KV head, chunk, 256 query columns).  1-D grid with the KV head as the fastest index:
 // consecutive workgroups land on different XCDs, so all query-column tiles of one (head, chunk) share one L2.
@@ -103,7 +164,7 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
     const int qtile = (blockIdx.x / Hkv) % n_qtiles;
     const int c = blockIdx.x / (Hkv * n_qtiles);
     const int c0 = ct.off[c], c1 = ct.off[c + 1];
-    const int NQG = nq * G;
+    const int NQG = nq * G, NQG_pad = (NQG + 63) & ~63;
     const int n_base = (qtile * 4 + wave) * 64;
     const float2* trow = SRC == SRC_PROMPT ? nullptr : table + (size_t)c * (D / 2);
 
@@ -188,30 +249,41 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
         const float m_o = __shfl_xor(m2[nb], 32), l_o = __shfl_xor(lsum[nb], 32);
         const float m = fmaxf(m2[nb], m_o);
         const float l = lsum[nb] * __builtin_amdgcn_exp2f(m2[nb] - m) + l_o * __builtin_amdgcn_exp2f(m_o - m);
-        if (h == 0 && col_n[nb] < NQG)
-            lse2[((size_t)g * (ct.n + 1) + c) * NQG + col_n[nb]] = (l > 0.f) ? m + __builtin_amdgcn_logf(l) : -INFINITY;
+        // columns NQG .. NQG_pad - 1 hold +inf: pass B copies whole 64-column tiles and their weights must be 0
+        if (h == 0 && col_n[nb] < NQG_pad)
+            lse2[((size_t)g * (ct.n + 1) + c) * NQG_pad + col_n[nb]] =
+                col_n[nb] >= NQG ? INFINITY : (l > 0.f) ? m + __builtin_amdgcn_logf(l) : -INFINITY;
     }
 }
 
-// Global scope: lse2[g][C][n] = base-2 log-sum-exp over the chunks.  grid (ceil(NQG / 256), Hkv).
-__global__ void score_lse2_global_kernel(int n_chunks, int NQG, float* __restrict__ lse2) {
+// Global scope: lse2[g][C][n] = base-2 log-sum-exp over the chunks.  grid (NQG_pad / 256 rounded up, Hkv); rows of
+// NQG_pad columns, the padding +inf.
+__global__ void score_lse2_global_kernel(int n_chunks, int NQG, int NQG_pad, float* __restrict__ lse2) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= NQG) return;
-    float* base = lse2 + (size_t)blockIdx.y * (n_chunks + 1) * NQG;
+    if (n >= NQG_pad) return;
+    float* base = lse2 + (size_t)blockIdx.y * (n_chunks + 1) * NQG_pad;
+    if (n >= NQG) {
+        base[(size_t)n_chunks * NQG_pad + n] = INFINITY;
+        return;
+    }
     float m = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, base[(size_t)c * NQG + n]);
+    for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, base[(size_t)c * NQG_pad + n]);
     float l = 0.f;
     for (int c = 0; c < n_chunks; ++c) {
-        const float v = base[(size_t)c * NQG + n];
+        const float v = base[(size_t)c * NQG_pad + n];
         if (v != -INFINITY) l += exp2f(v - m);
     }
-    base[(size_t)n_chunks * NQG + n] = m + log2f(l);
+    base[(size_t)n_chunks * NQG_pad + n] = m + log2f(l);
 }
 
 // ---- pass B -------------------------------------------------------------------------------------
-// One workgroup = (KV head, chunk, 256 keys of the chunk), KV head fastest in the 1-D grid (see pass A).
-// scope_global: use lse2[g][C].  Query-column tiles are double-buffered in LDS and consumed in pipelined halves
-// like the key tiles of pass A.
+// One workgroup = (KV head, chunk, 256 keys of the chunk), KV head fastest in the 1-D grid (see pass A); a wave
+// keeps its 64 keys in registers (B operand) and all query columns of the group stream past them.
+// scope_global: use lse2[g][C].  The query-column tiles (64 columns with their normalisers) go global -> LDS
+// directly into a ring of three; step t (one workgroup barrier) multiplies rows 32..63 of tile t while the
+// weights of rows 0..31 are formed, then rows 0..31 of tile t + 1 against the weights of rows 32..63, and copies
+// tile t + 2 into the slot tile t - 1 has left.  A tile lands a whole step before it is read; the fragments of the
+// next step's first half are requested at the end of a step and are in flight across the barrier.
 template <int G, int SRC>
 __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                                                                 ChunkTable ct, int nq, int Hq, int Hkv, int n_ktiles,
@@ -219,18 +291,19 @@ __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16*
                                                                 const float* __restrict__ lse2,
                                                                 float* __restrict__ col_partial, ChunkRows rows,
                                                                 const float2* __restrict__ table) {
-    __shared__ __attribute__((aligned(16))) __bf16 q_lds[2][64 * PITCH];
-    __shared__ __attribute__((aligned(16))) float lse_lds[4][64];   // four slots: a tile's normalisers outlive its rows
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    __shared__ __attribute__((aligned(1024))) unsigned char q_lds[3 * TILE_BYTES];
+    __shared__ __attribute__((aligned(256))) float lse_lds[3][64];
+    const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = blockIdx.x % Hkv;
     const int ktile = (blockIdx.x / Hkv) % n_ktiles;
     const int c = blockIdx.x / (Hkv * n_ktiles);
     const int c0 = ct.off[c], c1 = ct.off[c + 1];
     const int kbase = c0 + ktile * 256;
     if (kbase >= c1) return;
-    const int NQG = nq * G;
+    const int NQG = nq * G, NQG_pad = (NQG + 63) & ~63;
     const int L_ctx = ct.off[ct.n];
-    const float* lrow = lse2 + ((size_t)g * (ct.n + 1) + (scope_global ? ct.n : c)) * NQG;
+    const float* lrow = lse2 + ((size_t)g * (ct.n + 1) + (scope_global ? ct.n : c)) * NQG_pad;
 
     bf16x8 kf[2][8];   // B operand: this wave's 64 keys
     int col_key[2];
@@ -246,31 +319,35 @@ __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16*
             kf[nb][ks] = __builtin_bit_cast(bf16x8, load_key_vector<SRC>(kp, 2 * ks + h, trow));
     }
     float csum[2] = {0.f, 0.f};
-    const int st_vec = tid & 15, st_row = tid >> 4;
-    const int n_qt = (NQG + 63) / 64;
-    u32x4 qreg[4];
-    float lv = 0.f;
-    auto load_tile = [&](int qt) {   // tiles past the last one re-read it
-        const int n0 = min(qt, n_qt - 1) * 64;
+    const int n_qt = NQG_pad / 64;
+    // Query column n of the group = (question token n / G, head g G + n % G): tile t starts at token 64 t / G, and
+    // the per-lane part of a copy's address is the same for every tile but the last, whose rows past the end
+    // repeat the last column (finite numbers; their normaliser is +inf).
+    const unsigned char* q_head = reinterpret_cast<const unsigned char*>(q + (size_t)g * G * D);
+    const size_t tile_stride = (size_t)(64 / G) * Hq * D * 2;
+    uint32_t off_full[4], off_last[4], a_off[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int n = min(n0 + st_row + 16 * i, NQG - 1);
-            qreg[i] = *reinterpret_cast<const u32x4*>(q + ((size_t)(n / G) * Hq + g * G + (n % G)) * D + 8 * st_vec);
-        }
-        // all four waves fetch the same 64 normalisers (no branch); rows past the end contribute exp2(-inf) = 0
-        const float lraw = lrow[min(n0 + lane, NQG - 1)];
-        lv = (n0 + lane < NQG) ? lraw : INFINITY;
-    };
-    auto write_tile = [&](int qt) {
+    for (int j = 0; j < 4; ++j) {
+        const int r = copy_row(j, wave, lane), ch = copy_chunk(j, wave, lane);
+        const int rl = min(64 * (n_qt - 1) + r, NQG - 1) - 64 * (n_qt - 1);
+        off_full[j] = (uint32_t)(((r / G) * Hq + (r % G)) * (D * 2) + 16 * ch);
+        off_last[j] = (uint32_t)(((rl / G) * Hq + (rl % G)) * (D * 2) + 16 * ch);
+    }
+    frag_offsets(x, h, a_off);
+    const uint32_t lds_q = lds_address(q_lds), lds_l = lds_address(lse_lds);
+    auto copy_tile = [&](int t, int slot) {
+        uint32_t off[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&q_lds[qt & 1][(st_row + 16 * i) * PITCH + 8 * st_vec]) = qreg[i];
-        lse_lds[qt & 3][lane] = lv;
+        for (int j = 0; j < 4; ++j) off[j] = (t == n_qt - 1) ? off_last[j] : off_full[j];
+        dma_tile(q_head + (size_t)t * tile_stride, off, lds_q + (uint32_t)slot * TILE_BYTES, wave);
+        // (every wave copies the tile's 64 normalisers, the same values to the same place: no branch in the step)
+        dma_floats(lrow + 64 * t, (uint32_t)lane * 4u, lds_l + (uint32_t)slot * 256u);
     };
     // weights of one half (32 query rows), summed down the rows into the lane's key columns
-    auto fold_half = [&](const f32x16 (&s)[2], int qt, int mb) {
+    auto fold_half = [&](const f32x16 (&s)[2], int slot, int mb) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-            const f32x4 lz = *reinterpret_cast<const f32x4*>(&lse_lds[qt & 3][32 * mb + 8 * q4 + 4 * h]);
+            const f32x4 lz = *reinterpret_cast<const f32x4*>(&lse_lds[slot][32 * mb + 8 * q4 + 4 * h]);
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -278,31 +355,46 @@ __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16*
                     csum[nb] += __builtin_amdgcn_exp2f(__builtin_fmaf(s[nb][4 * q4 + e], scale_log2e, -lz[e]));
         }
     };
-    // Same half-tile pipeline as pass A; the stale products past the last tile are dropped.
     f32x16 s_a[2], s_b[2];
-    load_tile(0);
-    write_tile(0);
-    load_tile(1);
-    write_tile(1);
-    load_tile(2);
-    __syncthreads();
-    half_product(q_lds[0], 0, x, h, kf, s_a);
-    for (int qt = 0; qt < n_qt; ++qt) {
-        const int buf = qt & 1;
-        half_product(q_lds[buf], 1, x, h, kf, s_b);
-        fold_half(s_a, qt, 0);
+    bf16x8 fa[8];   // fragments of rows 32..63 of the step's tile, requested a step ahead
+    auto step = [&](auto slot_c, int t) {
+        constexpr int b = decltype(slot_c)::value, b1 = (b + 1) % 3, b2 = (b + 2) % 3;   // slots of tiles t, t + 1, t + 2
+        wait_copies_and_older_reads();
+        barrier_keep_reads_in_flight();   // tile t + 1 is complete; every wave is done with tile t - 1
+        __builtin_amdgcn_sched_barrier(0);
+        copy_tile(min(t + 2, n_qt - 1), b2);   // past the last tile: once more the last one, into a slot nobody reads
+        mfma_half(fa, kf, s_b);
+        fold_half(s_a, b, 0);
         interleave_hint();
-        __syncthreads();   // everyone is done with the rows of tile qt; tile qt+1 (written one iteration ago) is visible
-        write_tile(qt + 2);
-        load_tile(qt + 3);
-        half_product(q_lds[buf ^ 1], 0, x, h, kf, s_a);
-        fold_half(s_b, qt, 1);
+        bf16x8 fb[8];
+        load_frags(q_lds + b1 * TILE_BYTES, 0, a_off, fb);   // past the last tile: a stale slot, the products are dropped
+        mfma_half(fb, kf, s_a);
+        fold_half(s_b, b, 1);
         interleave_hint();
+        load_frags(q_lds + b1 * TILE_BYTES, 1, a_off, fa);
+    };
+    copy_tile(0, 0);
+    if (n_qt > 1) copy_tile(1, 1);
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+    barrier_keep_reads_in_flight();
+    {
+        bf16x8 fb[8];
+        load_frags(q_lds, 0, a_off, fb);
+        mfma_half(fb, kf, s_a);
+        load_frags(q_lds, 1, a_off, fa);
     }
+    int t = 0;
+    for (; t + 3 <= n_qt; t += 3) {
+        step(std::integral_constant<int, 0>{}, t);
+        step(std::integral_constant<int, 1>{}, t + 1);
+        step(std::integral_constant<int, 2>{}, t + 2);
+    }
+    if (t < n_qt) step(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < n_qt) step(std::integral_constant<int, 1>{}, t + 1);
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-        const float t = csum[nb] + __shfl_xor(csum[nb], 32);
-        if (h == 0 && col_key[nb] < c1) col_partial[(size_t)g * L_ctx + col_key[nb]] = t;
+        const float tot = csum[nb] + __shfl_xor(csum[nb], 32);
+        if (h == 0 && col_key[nb] < c1) col_partial[(size_t)g * L_ctx + col_key[nb]] = tot;
     }
 }
 
@@ -327,7 +419,7 @@ hipError_t run(const Shape& s, const void* q, int nq, const void* k_ctx, const C
     score_lse_mfma_kernel<G, SRC><<<dim3(n_qtiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
         (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, n_qtiles, c, ws.lse, rows, table);
     if (norm == FR_NORM_GLOBAL)
-        score_lse2_global_kernel<<<dim3((NQG + 255) / 256, s.Hkv), dim3(256), 0, st>>>(ct.n, NQG, ws.lse);
+        score_lse2_global_kernel<<<dim3((NQG + 255) / 256, s.Hkv), dim3(256), 0, st>>>(ct.n, NQG, (NQG + 63) & ~63, ws.lse);
     score_colsum_mfma_kernel<G, SRC><<<dim3(n_ktiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
         (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, n_ktiles, c, norm == FR_NORM_GLOBAL ? 1 : 0,
         ws.lse, ws.col_partial, rows, table);
