@@ -33,7 +33,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int D = 128;
-constexpr int PITCH = D + 8;   // bf16 elements per LDS row (272 B)
 constexpr float NEG_BIG = -1.0e30f;
 enum { SRC_PROMPT = 0, SRC_STORE_INTERLEAVED = 1, SRC_STORE_HALF = 2 };
 
@@ -57,21 +56,6 @@ __device__ __forceinline__ bf16x8 zero8() {
 #pragma unroll
     for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.0f;
     return z;
-}
-
-// One 32-row half of a 64-row LDS tile against this wave's 64 register-resident columns: s[nb] (32 x 32 each).
-__device__ __forceinline__ void half_product(const __bf16* tile, int mb, int x, int h, const bf16x8 (&bf)[2][8],
-                                             f32x16 (&s)[2]) {
-    f32x16 zero;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&tile[(32 * mb + x) * PITCH + 16 * ks + 8 * h]);
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-            s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bf[nb][ks], ks == 0 ? zero : s[nb], 0, 0, 0);
-    }
 }
 
 // Asks the scheduler to alternate matrix and transcendental instructions in the enclosing block, so that the
@@ -148,18 +132,23 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 // ---- pass A -------------------------------------------------------------------------------------
 // One workgroup = (KV head, chunk, 256 query columns).  1-D grid with the KV head as the fastest index:
 // consecutive workgroups land on different XCDs, so all query-column tiles of one (head, chunk) share one L2.
-// Key tiles are double-buffered in LDS; the tile after the next waits in registers.  The work runs in halves of 32
-// keys, software-pipelined: the products of a half are issued while the exponentials of the half before it
-// run.  Every lane keeps a running maximum and sum over the keys it sees itself (one of the two 4-row groups in
-// every 8 keys); the two lanes of a query column are merged once at the end.
+// A wave keeps its 64 query columns in registers (B operand); the chunk's key tiles stream past them through a
+// ring of three LDS slots.  Step t (one workgroup barrier) multiplies keys 32..63 of tile t while the exponentials
+// of keys 0..31 run, then keys 0..31 of tile t + 1 against the exponentials of keys 32..63, and fills the slot
+// tile t - 1 has left with tile t + 2: copied global -> LDS directly where the keys are used as stored
+// (SRC_PROMPT), through registers where they are rotated on the way (chunk store).  Every lane keeps a running
+// maximum and sum over the keys it sees itself (one of the two 4-row groups in every 8 keys); the two lanes of a
+// query column are merged once at the end.
 template <int G, int SRC>
 __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __restrict__ q,
                                                                 const __bf16* __restrict__ k, ChunkTable ct, int nq,
                                                                 int Hq, int Hkv, int n_qtiles, float scale_log2e,
                                                                 float* __restrict__ lse2, ChunkRows rows,
                                                                 const float2* __restrict__ table) {
-    __shared__ __attribute__((aligned(16))) __bf16 ks_lds[2][64 * PITCH];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    constexpr bool DIRECT = (SRC == SRC_PROMPT);
+    __shared__ __attribute__((aligned(1024))) unsigned char k_lds[3 * TILE_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = blockIdx.x % Hkv;
     const int qtile = (blockIdx.x / Hkv) % n_qtiles;
     const int c = blockIdx.x / (Hkv * n_qtiles);
@@ -180,20 +169,52 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
         for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
     }
     float m2[2] = {NEG_BIG, NEG_BIG}, lsum[2] = {0.f, 0.f};
-    const int st_vec = tid & 15, st_key = tid >> 4;
     const int n_kt = (c1 - c0 + 63) / 64;
+    if (n_kt == 0) {   // an empty chunk: no key, the log-sum-exp of nothing
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+            if (h == 0 && col_n[nb] < NQG_pad)
+                lse2[((size_t)g * (ct.n + 1) + c) * NQG_pad + col_n[nb]] = col_n[nb] >= NQG ? INFINITY : -INFINITY;
+        return;
+    }
+    uint32_t a_off[8];
+    frag_offsets(x, h, a_off);
+    // DIRECT: key row j of the chunk starts at byte j Hkv 256 of the head's slice; the per-lane part of a copy's
+    // address is the same for every tile but the last, whose rows past the chunk's end repeat its last key.
+    const unsigned char* k_head = reinterpret_cast<const unsigned char*>(k + ((size_t)c0 * Hkv + g) * D);
+    const size_t tile_stride = (size_t)64 * Hkv * D * 2;
+    uint32_t off_full[4], off_last[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = copy_row(j, wave, lane), ch = copy_chunk(j, wave, lane);
+        const int rl = min(64 * (n_kt - 1) + r, c1 - c0 - 1) - 64 * (n_kt - 1);
+        off_full[j] = (uint32_t)(r * Hkv * (D * 2) + 16 * ch);
+        off_last[j] = (uint32_t)(rl * Hkv * (D * 2) + 16 * ch);
+    }
+    const uint32_t lds_k = lds_address(k_lds);
+    auto copy_tile = [&](int t, int slot) {
+        uint32_t off[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) off[j] = (t == n_kt - 1) ? off_last[j] : off_full[j];
+        dma_tile(k_head + (size_t)t * tile_stride, off, lds_k + (uint32_t)slot * TILE_BYTES, wave);
+    };
+    // chunk store: a tile waits in registers for one step (its rows rotated as they arrive), then goes to its slot
+    const int st_vec = tid & 15, st_key = tid >> 4;
     u32x4 kreg[4];
-    auto load_tile = [&](int kt) {   // tiles past the last one re-read it; keys past the chunk's end are clamped
-        kt = min(kt, n_kt - 1);
+    auto load_tile = [&](int t) {   // tiles past the last one re-read it; keys past the chunk's end are clamped
+        t = min(t, n_kt - 1);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int j = min(c0 + kt * 64 + st_key + 16 * i, c1 - 1);
+            const int j = min(c0 + t * 64 + st_key + 16 * i, c1 - 1);
             kreg[i] = load_key_vector<SRC>(k + ((size_t)key_row<SRC>(rows, c, c0, j) * Hkv + g) * D, st_vec, trow);
         }
     };
-    auto write_tile = [&](int buf) {
+    auto write_tile = [&](int slot) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&ks_lds[buf][(st_key + 16 * i) * PITCH + 8 * st_vec]) = kreg[i];
+        for (int i = 0; i < 4; ++i) {
+            const int r = st_key + 16 * i;
+            *reinterpret_cast<u32x4*>(k_lds + slot * TILE_BYTES + r * 256 + ((st_vec ^ row_key(r)) << 4)) = kreg[i];
+        }
     };
     // running log-sum-exp of one half: rows (keys) key_lo + 8 (v / 4) + 4 h + v % 4 of the accumulator
     auto fold_half = [&](auto ragged, f32x16 (&s)[2], int key_lo) {
@@ -217,32 +238,67 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
             m2[nb] = m_new;
         }
     };
-    // One key tile, branch-free: the products that are issued past the last tile read a stale buffer and are
-    // dropped; the tiles written past the last one are never read.
     f32x16 s_a[2], s_b[2];
-    auto tile_step = [&](auto ragged, int kt) {
-        const int key0 = c0 + kt * 64;
-        const int buf = kt & 1;
-        half_product(ks_lds[buf], 1, x, h, qf, s_b);
-        fold_half(ragged, s_a, key0);
+    bf16x8 fa[8];   // fragments of keys 32..63 of the step's tile; DIRECT: requested a step ahead
+    auto step = [&](auto slot_c, auto ragged, int t) {
+        constexpr int b = decltype(slot_c)::value, b1 = (b + 1) % 3, b2 = (b + 2) % 3;   // slots of tiles t, t + 1, t + 2
+        wait_copies_and_older_reads();
+        barrier_keep_reads_in_flight();   // tile t + 1 is complete; every wave is done with tile t - 1
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (DIRECT) {
+            copy_tile(min(t + 2, n_kt - 1), b2);   // past the last tile: once more the last one, into a slot nobody reads
+        } else {
+            write_tile(b2);      // tile t + 2, loaded a step ago
+            load_tile(t + 3);
+            load_frags(k_lds + b * TILE_BYTES, 1, a_off, fa);   // (no registers to spare for requesting these a step ahead)
+        }
+        mfma_half(fa, qf, s_b);
+        fold_half(ragged, s_a, c0 + 64 * t);
         interleave_hint();
-        __syncthreads();   // everyone is done with tile kt; tile kt+1 (written one iteration ago) is visible
-        write_tile(buf);        // tile kt+2
-        load_tile(kt + 3);
-        half_product(ks_lds[buf ^ 1], 0, x, h, qf, s_a);
-        fold_half(ragged, s_b, key0 + 32);
+        bf16x8 fb[8];
+        load_frags(k_lds + b1 * TILE_BYTES, 0, a_off, fb);   // past the last tile: a stale slot, the products are dropped
+        mfma_half(fb, qf, s_a);
+        fold_half(ragged, s_b, c0 + 64 * t + 32);
         interleave_hint();
+        if constexpr (DIRECT) load_frags(k_lds + b1 * TILE_BYTES, 1, a_off, fa);
     };
-    if (n_kt > 0) {
+    if constexpr (DIRECT) {
+        copy_tile(0, 0);
+        copy_tile(min(1, n_kt - 1), 1);
+    } else {
         load_tile(0);
         write_tile(0);
         load_tile(1);
         write_tile(1);
         load_tile(2);
-        __syncthreads();
-        half_product(ks_lds[0], 0, x, h, qf, s_a);
-        for (int kt = 0; kt < n_kt - 1; ++kt) tile_step(std::false_type{}, kt);
-        tile_step(std::true_type{}, n_kt - 1);
+    }
+    __builtin_amdgcn_s_waitcnt(DIRECT ? 0x0f70 : 0xc07f);   // the copies (vmcnt(0)) or the LDS writes (lgkmcnt(0)) are done
+    barrier_keep_reads_in_flight();
+    {
+        bf16x8 fb[8];
+        load_frags(k_lds, 0, a_off, fb);
+        mfma_half(fb, qf, s_a);
+        if constexpr (DIRECT) load_frags(k_lds, 1, a_off, fa);
+    }
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    using S2 = std::integral_constant<int, 2>;
+    int t = 0;
+    for (; t + 3 < n_kt; t += 3) {   // whole tiles only: at least one step is left for the ragged end
+        step(S0{}, std::false_type{}, t);
+        step(S1{}, std::false_type{}, t + 1);
+        step(S2{}, std::false_type{}, t + 2);
+    }
+    const int left = n_kt - t;   // 1, 2 or 3 steps; the last one masks the keys past the chunk's end
+    if (left == 1) {
+        step(S0{}, std::true_type{}, t);
+    } else if (left == 2) {
+        step(S0{}, std::false_type{}, t);
+        step(S1{}, std::true_type{}, t + 1);
+    } else {
+        step(S0{}, std::false_type{}, t);
+        step(S1{}, std::false_type{}, t + 1);
+        step(S2{}, std::true_type{}, t + 2);
     }
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {   // merge the two lanes of a query column
