@@ -136,6 +136,63 @@ def test_score_select(name, seed, norm):
     ctx.close()
 
 
+TILED_SCORE_CASES = [
+    # (query heads, KV heads, question tokens, chunk lengths): group sizes 1, 2, 4, 8; question columns (G x tokens)
+    # below, at and above one 64-column tile and one 256-column workgroup; chunks below, at and above one 64-key
+    # tile and one 256-key workgroup, empty chunks, a single chunk
+    (4, 4, 1, (5,)),
+    (4, 4, 64, (64, 65, 1)),
+    (4, 4, 65, (256, 0, 257)),
+    (4, 2, 32, (63, 64)),
+    (4, 2, 33, (300, 7, 129)),
+    (8, 2, 16, (64,)),
+    (8, 2, 17, (0, 200, 0, 70)),
+    (8, 2, 130, (191, 513)),
+    (16, 2, 8, (100, 28)),
+    (16, 2, 9, (64, 320)),
+    (16, 2, 71, (33, 0, 450)),
+]
+
+
+@pytest.mark.parametrize("norm", [B.FR_NORM_PER_CHUNK, B.FR_NORM_GLOBAL])
+@pytest.mark.parametrize("Hq,Hkv,nq,chunk_lens", TILED_SCORE_CASES)
+def test_score_select_tiled_kernel_shapes(Hq, Hkv, nq, chunk_lens, norm):
+    """The matrix-core scoring passes (bf16, head_dim 128) at every group size and at tile boundaries of both
+    operands, against the oracle; the chunk-store entry point on the same keys gives the same scores."""
+    shape = synth.LayerShape(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=128, dtype="bf16", rope_base=500000.0)
+    w = synth.config_small_bf16(seed=Hq + nq, chunk_lens=chunk_lens, nq=nq, shape=shape)
+    dt = "bf16"
+    k_ctx = synth.round_to_storage(orc.rope_shift(w.k_cached, w.chunk_offsets, w.src_pos0, None, shape.rope_base), dt)
+    want = orc.critical_scores(w.q_question, k_ctx, w.chunk_offsets, "global" if norm == B.FR_NORM_GLOBAL else "per_chunk")
+    k = orc.topk_count(w.L_ctx, 0.3)
+    ctx = H.make_ctx(shape, w.L, w.n_chunks, w.nq)
+    scores = torch.full((w.L_ctx,), -7.0, dtype=torch.float32, device="cuda")
+    qi = torch.full((k + w.nq,), -1, dtype=torch.int32, device="cuda")
+    qq, kc = H.dev(w.q_question, dt), H.dev(k_ctx, dt)
+    ctx.fr_score_select(qq, w.nq, kc, w.chunk_offsets, k, norm, scores, qi)
+    torch.cuda.synchronize()
+    got = scores.cpu().numpy().astype(np.float64)
+    assert H.max_rel_err(got, want) <= 1e-4
+    H.assert_index_set(qi.cpu().numpy(), want, k, w.nq)
+    # the same keys as a chunk store with zero position shift (chunks in reverse order, a gap in front)
+    gap = 3
+    order = list(range(w.n_chunks))[::-1]
+    row0 = np.zeros(w.n_chunks, dtype=np.int32)
+    parts, at = [np.zeros((gap,) + k_ctx.shape[1:], dtype=k_ctx.dtype)], gap
+    for c in order:
+        row0[c] = at
+        parts.append(k_ctx[w.chunk_offsets[c]:w.chunk_offsets[c + 1]])
+        at += int(w.chunk_offsets[c + 1] - w.chunk_offsets[c])
+    store = np.concatenate(parts)
+    scores2 = torch.full_like(scores, -7.0)
+    qi2 = torch.full_like(qi, -1)
+    ctx.fr_score_select_shared(qq, w.nq, H.dev(store, dt), len(store), w.chunk_offsets, row0, w.chunk_offsets[:-1], k, norm,
+                               scores2, qi2)
+    torch.cuda.synchronize()
+    assert torch.equal(scores, scores2) and torch.equal(qi, qi2)     # a rotation by zero positions leaves the keys as stored
+    ctx.close()
+
+
 @pytest.mark.parametrize("n,k,nq", [(1, 1, 0), (1, 0, 3), (7, 3, 2), (1000, 150, 5), (1024, 1024, 0), (4097, 1, 1),
                                     (16384, 2458, 512), (20001, 3000, 0), (50000, 7500, 17), (16384, 16383, 0)])
 def test_select_topk_exact(n, k, nq):
