@@ -16,6 +16,10 @@ SHAPES = {
     "llama_bf16": synth.LLAMA3_8B_BF16,
     "bf16_d64_g2": synth.LayerShape(n_q_heads=4, n_kv_heads=2, head_dim=64, dtype="bf16", rope_base=10000.0),
     "f32_d128_g4": synth.LayerShape(n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="f32", rope_base=500000.0),
+    # the other group sizes of the matrix-core kernel (bf16, head_dim 128), and one it does not take
+    "bf16_d128_g1": synth.LayerShape(n_q_heads=4, n_kv_heads=4, head_dim=128, dtype="bf16", rope_base=500000.0),
+    "bf16_d128_g2": synth.LayerShape(n_q_heads=4, n_kv_heads=2, head_dim=128, dtype="bf16", rope_base=500000.0),
+    "bf16_d128_g8": synth.LayerShape(n_q_heads=16, n_kv_heads=2, head_dim=128, dtype="bf16", rope_base=500000.0),
 }
 
 

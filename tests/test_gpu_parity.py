@@ -345,6 +345,35 @@ def test_sparse_prefill_attn(name, seed):
     ctx.close()
 
 
+@pytest.mark.parametrize("split", [B.FR_ATTN_SPLIT_OFF, B.FR_ATTN_SPLIT_ON])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (16, 2)])
+def test_sparse_prefill_attn_tiled_kernel_group_sizes(Hq, Hkv, split):
+    """The matrix-core attention kernels (bf16, head_dim 128) at group sizes 1, 2 and 8 (a row tile holds 64, 32 or 8
+    tokens), with and without the key-range split, fused write-back included."""
+    shape = synth.LayerShape(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=128, dtype="bf16", rope_base=500000.0)
+    w = synth.config_small_bf16(seed=Hq, ratio=0.2, chunk_lens=(130, 0, 333, 61), nq=37, shape=shape)
+    dt = "bf16"
+    k_ctx, _, k, qi = staged(w)
+    k_cache, v_cache = assembled_cache(w, k_ctx)
+    ctx = H.make_ctx(shape, w.L, w.n_chunks, w.nq)
+    ctx.fr_set_option(B.FR_OPT_ATTN_SPLIT, split)
+    got, lse = run_attention(ctx, w, qi, k_cache, v_cache)
+    want, want_lse = orc.sparse_prefill_attn(w.q_full[qi], qi, k_cache, v_cache, w.k_full[qi], w.v_full[qi])
+    H.assert_close(got, want, dt, "attention output")
+    assert np.max(np.abs(lse - want_lse)) <= 2e-3, "lse"
+    # write-back fused into the call: same output, and the caches end up as after the scatter
+    R = len(qi)
+    kc, vc = H.dev(k_cache, dt), H.dev(v_cache, dt)
+    out = torch.zeros((R, Hq, 128), dtype=torch.bfloat16, device="cuda")
+    ctx.fr_sparse_prefill_attn_writeback(H.dev(w.q_full[qi], dt), torch.from_numpy(qi.astype(np.int32)).cuda(), R, kc, vc, w.L,
+                                         H.dev(w.k_full[qi], dt), H.dev(w.v_full[qi], dt), out)
+    torch.cuda.synchronize()
+    H.assert_close(H.host(out), want, dt, "attention output with write-back")
+    k_eff, v_eff = orc.kv_scatter(qi, w.k_full[qi], w.v_full[qi], k_cache, v_cache)
+    assert np.array_equal(H.host(kc), k_eff) and np.array_equal(H.host(vc), v_eff)
+    ctx.close()
+
+
 @pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
 @pytest.mark.parametrize("ratio", [0.0, 0.05, 0.30, 1.0])
 def test_ratio_extremes(name, ratio):

@@ -67,6 +67,47 @@ def test_shared_store_prefill_matches_oracle_and_three_call_path(ratio, layout):
     ctx.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 2), (16, 2)])
+def test_shared_store_prefill_group_sizes(Hq, Hkv):
+    """Group sizes 1, 2 and 8 of the tiled kernels over the chunk store: one query, and the same query twice through
+    the batch call."""
+    shape = synth.LayerShape(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=128, dtype="bf16", rope_base=500000.0)
+    w = synth.config_small_bf16(seed=Hkv, ratio=0.2, chunk_lens=(130, 0, 333, 61), nq=37, shape=shape)
+    dt, tdt = "bf16", torch.bfloat16
+    rng = np.random.default_rng(Hq)
+    src_pos0 = rng.integers(0, 5000, size=w.n_chunks).astype(np.int32)
+    k_store, v_store, row0 = scattered_store(w, rng)
+    ks_d, vs_d = H.dev(k_store, dt), H.dev(v_store, dt)
+    k = orc.topk_count(w.L_ctx, 0.2)
+    qi = np.concatenate([np.sort(rng.choice(w.L_ctx, size=k, replace=False)), w.L_ctx + np.arange(w.nq)]).astype(np.int64)
+    R = len(qi)
+    ctx = H.make_ctx(shape, w.L, w.n_chunks, w.nq)
+    ctx.fr_set_option(B.FR_OPT_ATTN_SPLIT, B.FR_ATTN_SPLIT_OFF)
+    q_rows, k_new, v_new = H.dev(w.q_full[qi], dt), H.dev(w.k_full[qi], dt), H.dev(w.v_full[qi], dt)
+    qi_d = torch.from_numpy(qi.astype(np.int32)).cuda()
+    out = torch.zeros((R, Hq, 128), dtype=tdt, device="cuda")
+    lse = torch.zeros((R, Hq), dtype=torch.float32, device="cuda")
+    ctx.fr_sparse_prefill_attn_shared(q_rows, qi_d, R, ks_d, vs_d, len(k_store), w.chunk_offsets, row0, src_pos0, w.L,
+                                      k_new, v_new, out, lse)
+    torch.cuda.synchronize()
+    k_ctx = synth.round_to_storage(orc.rope_shift(w.k_cached, w.chunk_offsets, src_pos0, None, shape.rope_base), dt)
+    pad = np.zeros((w.nq, Hkv, 128))
+    want, want_lse = orc.sparse_prefill_attn(w.q_full[qi], qi, np.concatenate([k_ctx, pad]),
+                                             np.concatenate([w.v_cached, pad]), w.k_full[qi], w.v_full[qi])
+    H.assert_close(H.host(out), want, dt, "shared-store attention")
+    assert np.max(np.abs(lse.cpu().numpy() - want_lse)) <= 2e-3
+    mkq = lambda: dict(q_rows=q_rows, q_index=qi_d, R=R, chunk_offsets=w.chunk_offsets, chunk_store_row0=row0,
+                       chunk_src_pos0=src_pos0, L=w.L, k_new=k_new, v_new=v_new,
+                       out=torch.zeros_like(out), lse_out=torch.zeros_like(lse))
+    batch = [mkq(), mkq()]
+    ws = torch.empty(ctx.fr_shared_batch_workspace_bytes(2, w.L), dtype=torch.uint8, device="cuda")
+    ctx.fr_sparse_prefill_attn_shared_batch(batch, ks_d, vs_d, len(k_store), ws)
+    torch.cuda.synchronize()
+    for q in batch:
+        assert torch.equal(q["out"], out) and torch.equal(q["lse_out"], lse)
+    ctx.close()
+
+
 def test_shared_store_prefill_argument_errors():
     w = synth.config_small_bf16(seed=1)
     ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
