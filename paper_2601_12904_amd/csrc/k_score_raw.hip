@@ -35,7 +35,7 @@ struct Load16<__bf16> {
 // qsum[g * d + e] = sum over question tokens of the sum over the G heads of group g, in two fixed-order stages:
 // slice y of the tokens -> part[y][g * d + e] (one thread per (g, e), rows read coalesced along e), then the
 // QSUM_SLICES partial sums in slice order.
-constexpr int QSUM_SLICES = 32;
+constexpr int QSUM_SLICES = 128;   // a few question tokens per thread: the loads of a slice are all in flight at once
 
 template <typename T>
 __global__ __launch_bounds__(256) void question_sum_kernel(const T* __restrict__ q, int nq, int Hq, int G, int d,
@@ -47,8 +47,10 @@ __global__ __launch_bounds__(256) void question_sum_kernel(const T* __restrict__
     const int per = (nq + QSUM_SLICES - 1) / QSUM_SLICES;
     const int i0 = blockIdx.y * per, i1 = min(nq, i0 + per);
     float acc = 0.f;
+#pragma unroll 4
     for (int i = i0; i < i1; ++i) {
         float t = 0.f;
+#pragma unroll 4
         for (int hh = 0; hh < G; ++hh) t += Elem<T>::to_f32(q[((size_t)i * Hq + g * G + hh) * d + e]);
         acc += t;
     }
