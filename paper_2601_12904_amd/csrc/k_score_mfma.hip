@@ -104,7 +104,16 @@ __device__ __forceinline__ int copy_chunk(int j, int wave, int lane) { return (l
 // it the compiler takes the pending copy for an access that may complete out of order with the LDS reads and waits
 // for all outstanding fragment reads before every matrix instruction.  Completion: the issuing wave's vmcnt, then
 // a workgroup barrier.
+// A workgroup-uniform address, pinned to scalar registers (the copies take their base address from there; without
+// this the compiler may keep a pointer it also uses for vector loads in vector registers).
+template <typename T>
+__device__ __forceinline__ const T* uniform_ptr(const T* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ void dma_tile(const unsigned char* src, const uint32_t (&lane_off)[4], uint32_t lds_tile, int wave_u) {
+    src = uniform_ptr(src);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t l = lds_tile + (uint32_t)(4 * j + wave_u) * 1024u;
@@ -113,6 +122,7 @@ __device__ __forceinline__ void dma_tile(const unsigned char* src, const uint32_
 }
 // 64 floats (one per lane) global -> LDS the same way.
 __device__ __forceinline__ void dma_floats(const float* src, uint32_t lane_off, uint32_t lds_dst) {
+    src = uniform_ptr(src);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" : : "v"(lane_off), "s"(src), "s"(lds_dst) : "memory");
 }
 // This wave's copies have landed (vmcnt(0)) and all its LDS reads except the eight youngest (the fragments requested
