@@ -125,12 +125,14 @@ __device__ __forceinline__ void dma_floats(const float* src, uint32_t lane_off, 
     src = uniform_ptr(src);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" : : "v"(lane_off), "s"(src), "s"(lds_dst) : "memory");
 }
-// This wave's copies have landed (vmcnt(0)) and all its LDS reads except the eight youngest (the fragments requested
-// for the next step, which come from a tile that nobody overwrites yet) have returned (lgkmcnt(8)).
-__device__ __forceinline__ void wait_copies_and_older_reads() { __builtin_amdgcn_s_waitcnt(0x0870); }
-// Workgroup barrier without the fences of __syncthreads(), which would make the compiler drain the fragment reads
-// that are meant to stay in flight across it; the empty asm statements keep it from moving LDS accesses across.
-__device__ __forceinline__ void barrier_keep_reads_in_flight() {
+// Top of a step: this wave's copies have landed and its LDS reads have returned (vmcnt(0), lgkmcnt(0)); after the
+// barrier that follows, the slot that is overwritten next has no reader left anywhere in the workgroup.  (The reads
+// still outstanding here are the fragments requested at the end of the step before, which the first matrix
+// instruction after the barrier needs at once: waiting for them here costs nothing measurable.)
+__device__ __forceinline__ void wait_copies_and_reads() { __builtin_amdgcn_s_waitcnt(0x0070); }
+// Workgroup barrier without the fences of __syncthreads() (which add nothing here: the waits are explicit); the
+// empty asm statements keep the compiler from moving LDS accesses across it.
+__device__ __forceinline__ void plain_barrier() {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -252,8 +254,8 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
     bf16x8 fa[8];   // fragments of keys 32..63 of the step's tile; DIRECT: requested a step ahead
     auto step = [&](auto slot_c, auto ragged, int t) {
         constexpr int b = decltype(slot_c)::value, b1 = (b + 1) % 3, b2 = (b + 2) % 3;   // slots of tiles t, t + 1, t + 2
-        wait_copies_and_older_reads();
-        barrier_keep_reads_in_flight();   // tile t + 1 is complete; every wave is done with tile t - 1
+        wait_copies_and_reads();
+        plain_barrier();   // tile t + 1 is complete; every wave is done with tile t - 1
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (DIRECT) {
             copy_tile(min(t + 2, n_kt - 1), b2);   // past the last tile: once more the last one, into a slot nobody reads
@@ -283,7 +285,7 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
         load_tile(2);
     }
     __builtin_amdgcn_s_waitcnt(DIRECT ? 0x0f70 : 0xc07f);   // the copies (vmcnt(0)) or the LDS writes (lgkmcnt(0)) are done
-    barrier_keep_reads_in_flight();
+    plain_barrier();
     {
         bf16x8 fb[8];
         load_frags(k_lds, 0, a_off, fb);
@@ -349,7 +351,7 @@ __global__ void score_lse2_global_kernel(int n_chunks, int NQG, int NQG_pad, flo
 // directly into a ring of three; step t (one workgroup barrier) multiplies rows 32..63 of tile t while the
 // weights of rows 0..31 are formed, then rows 0..31 of tile t + 1 against the weights of rows 32..63, and copies
 // tile t + 2 into the slot tile t - 1 has left.  A tile lands a whole step before it is read; the fragments of the
-// next step's first half are requested at the end of a step and are in flight across the barrier.
+// next step's first half are requested at the end of a step, so that they arrive while the wave waits at the barrier.
 template <int G, int SRC>
 __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                                                                 ChunkTable ct, int nq, int Hq, int Hkv, int n_ktiles,
@@ -425,8 +427,8 @@ __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16*
     bf16x8 fa[8];   // fragments of rows 32..63 of the step's tile, requested a step ahead
     auto step = [&](auto slot_c, int t) {
         constexpr int b = decltype(slot_c)::value, b1 = (b + 1) % 3, b2 = (b + 2) % 3;   // slots of tiles t, t + 1, t + 2
-        wait_copies_and_older_reads();
-        barrier_keep_reads_in_flight();   // tile t + 1 is complete; every wave is done with tile t - 1
+        wait_copies_and_reads();
+        plain_barrier();   // tile t + 1 is complete; every wave is done with tile t - 1
         __builtin_amdgcn_sched_barrier(0);
         copy_tile(min(t + 2, n_qt - 1), b2);   // past the last tile: once more the last one, into a slot nobody reads
         mfma_half(fa, kf, s_b);
@@ -442,7 +444,7 @@ __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16*
     copy_tile(0, 0);
     if (n_qt > 1) copy_tile(1, 1);
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
-    barrier_keep_reads_in_flight();
+    plain_barrier();
     {
         bf16x8 fb[8];
         load_frags(q_lds, 0, a_off, fb);
