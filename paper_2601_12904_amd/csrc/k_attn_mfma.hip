@@ -34,6 +34,8 @@
 #include "fr_internal.hpp"
 #include "k_rotate.hpp"
 
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 
 #ifndef FR_SCHED_HINTS
@@ -938,21 +940,32 @@ hipError_t run_batch(const Shape& s, AttnBatch& batch, float* partials, size_t p
     const bool fits = batch.n == 1 && (size_t)grid.x * 2 * PART_FLOATS * sizeof(float) <= partials_bytes;
     const bool split = fits && (split_mode == FR_ATTN_SPLIT_ON ||
                                 (split_mode == FR_ATTN_SPLIT_AUTO && (int)grid.x <= ATTN_SPLIT_AUTO_ITEMS && max_img_tiles >= 32));
+    // Kernel timer: the event pair rides on the kernel's own dispatch (start and end of its execution), so the
+    // stream carries no extra marker packets and the kernels before and after it are not held up.
     const bool timed = timer != nullptr && timer->n_slots > 0 && mode != FR_ATTN_SOFTMAX_RUNNING_MAX;
     const int slot = timed ? (int)(timer->n_recorded % timer->n_slots) : 0;
-    if (timed && hipEventRecord(timer->start[slot], st) != hipSuccess) return hipGetLastError();
     int use_flags = 1;
     if (mode == FR_ATTN_SOFTMAX_RUNNING_MAX) {
         use_flags = 0;   // recompute every workgroup with the running maximum
     } else if (split) {
-        attn_fixed_ref_kernel<G, 2><<<dim3(grid.x * 2), block, lds_fast, st>>>(batch, partials, s.Hq, s.Hkv, scale_log2e);
-        if (timed) { (void)hipEventRecord(timer->stop[slot], st); ++timer->n_recorded; }
+        if (timed) {
+            hipExtLaunchKernelGGL((attn_fixed_ref_kernel<G, 2>), dim3(grid.x * 2), block, (uint32_t)lds_fast, st,
+                                  timer->start[slot], timer->stop[slot], 0u, batch, partials, s.Hq, s.Hkv, scale_log2e);
+            ++timer->n_recorded;
+        } else {
+            attn_fixed_ref_kernel<G, 2><<<dim3(grid.x * 2), block, lds_fast, st>>>(batch, partials, s.Hq, s.Hkv, scale_log2e);
+        }
         const AttnQuery& q0 = batch.q[0];
         attn_combine_kernel<G><<<grid, block, EPILOGUE_LDS, st>>>(q0.q_index, q0.R, partials, q0.out, q0.lse, q0.flags,
                                                                   s.Hq, s.Hkv, q0.n_row_tiles);
     } else {
-        attn_fixed_ref_kernel<G, 1><<<grid, block, lds_fast, st>>>(batch, nullptr, s.Hq, s.Hkv, scale_log2e);
-        if (timed) { (void)hipEventRecord(timer->stop[slot], st); ++timer->n_recorded; }
+        if (timed) {
+            hipExtLaunchKernelGGL((attn_fixed_ref_kernel<G, 1>), grid, block, (uint32_t)lds_fast, st, timer->start[slot],
+                                  timer->stop[slot], 0u, batch, (float*)nullptr, s.Hq, s.Hkv, scale_log2e);
+            ++timer->n_recorded;
+        } else {
+            attn_fixed_ref_kernel<G, 1><<<grid, block, lds_fast, st>>>(batch, nullptr, s.Hq, s.Hkv, scale_log2e);
+        }
     }
     attn_running_max_kernel<G><<<grid, block, lds_safe, st>>>(batch, use_flags, s.Hq, s.Hkv, scale_log2e);
     return hipGetLastError();
