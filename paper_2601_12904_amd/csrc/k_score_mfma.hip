@@ -5,7 +5,8 @@
 // logits are formed twice (recomputing a 128-deep bf16 product is far cheaper than storing and
 // re-reading nq x Hq x L_ctx fp32 values):
 //   pass A  per (KV head, chunk, 256 query columns): S^T = K Q^T tile by tile, running max / sum per
-//           query column -> base-2 log-sum-exp of the scaled logits, lse2[g][chunk][column]
+//           query column -> base-2 log-sum-exp of the scaled logits, lse2[g][chunk][column] (rows padded to a
+//           multiple of 64 columns, the padding +inf: pass B copies whole 64-column tiles and their weights are 0)
 //   pass B  per (KV head, 256 keys of one chunk): S = Q K^T over all query columns of the group,
 //           p = exp2(s * c - lse2), summed down the rows -> col_partial[g][key]
 //   reduce  scores[j] = sum over KV heads g of col_partial[g][j], in a fixed order.
