@@ -105,9 +105,10 @@ int64_t fr_workspace_bytes(const fr_ctx* ctx);
  * FR_OPT_GEMM_TAIL_SPLIT: 1 (default): when the output tiles of a projection do not fill the last round of
  * workgroups (one per CU), the tiles of that round are split along K over several workgroups each and a second small
  * kernel adds the parts; 0: never.  Same results up to fp32 summation order; process-wide, for tests and tuning.
- * FR_OPT_ATTN_KERNEL_TIMER: value n in [0, 256]: the tiled attention launch records an event pair on its stream around
- * its dominant kernel (the key-tile loop) and keeps the last n pairs; 0 (default) switches the timer off.  Read
- * with fr_attn_kernel_times.  For benchmarks: the events see one kernel, not the whole call. */
+ * FR_OPT_ATTN_KERNEL_TIMER: value n in [0, 256]: the tiled attention launch attaches an event pair to the dispatch of
+ * its dominant kernel (the key-tile loop) on the call's stream, start and end of that kernel's execution, and keeps
+ * the last n pairs; 0 (default) switches the timer off.  Read with fr_attn_kernel_times.  For benchmarks: the events
+ * see one kernel, not the whole call. */
 typedef enum { FR_OPT_ATTN_SOFTMAX = 1, FR_OPT_ATTN_SPLIT = 2, FR_OPT_DECODE_KERNEL = 3, FR_OPT_GEMM_TILE = 4,
                FR_OPT_ATTN_KERNEL_TIMER = 5, FR_OPT_GEMM_TAIL_SPLIT = 6 } fr_option;
 typedef enum { FR_DECODE_KERNEL_AUTO = 0, FR_DECODE_KERNEL_GENERIC = 1 } fr_decode_kernel;
