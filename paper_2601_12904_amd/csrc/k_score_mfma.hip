@@ -74,6 +74,9 @@ __device__ __forceinline__ void interleave_hint() {
 // c ^ row_key(r).  The fragment reads (lane = row x of a 32-row half, chunk 2 ks + h) then hit 16 different slots in
 // any 16 lanes that the LDS serves together, whether those are 16 rows of one h or 8 rows of both.
 constexpr int TILE_BYTES = 64 * D * 2;
+constexpr int NW = 4;                 // waves per workgroup: they share every streamed tile (8 was measured: half the
+                                      // copies per wave and half the L2 traffic, same time; 4 wastes less on short chunks)
+constexpr int COPIES = 16 / NW;       // 1 KB copies per wave and tile
 __device__ __forceinline__ int row_key(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
 
 // Byte offsets, inside a 32-row half, of this lane's eight A fragments.
@@ -97,7 +100,7 @@ __device__ __forceinline__ void mfma_half(const bf16x8 (&a)[8], const bf16x8 (&b
 }
 // Which LDS row this lane fills in copy j of its wave (each copy: 1 KB = 4 rows, lane = (row, slot)), and which
 // chunk of the source row belongs there.
-__device__ __forceinline__ int copy_row(int j, int wave, int lane) { return 4 * (4 * j + wave) + (lane >> 4); }
+__device__ __forceinline__ int copy_row(int j, int wave, int lane) { return 4 * (NW * j + wave) + (lane >> 4); }
 __device__ __forceinline__ int copy_chunk(int j, int wave, int lane) { return (lane & 15) ^ row_key(copy_row(j, wave, lane)); }
 // One tile, global -> LDS without passing through registers (global_load_lds_dwordx4: lane i of a wave deposits its
 // 16 bytes at the LDS address in M0 + 16 i).  The source is a workgroup-uniform base in scalar registers plus a
@@ -113,11 +116,11 @@ __device__ __forceinline__ const T* uniform_ptr(const T* p) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
     return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
 }
-__device__ __forceinline__ void dma_tile(const unsigned char* src, const uint32_t (&lane_off)[4], uint32_t lds_tile, int wave_u) {
+__device__ __forceinline__ void dma_tile(const unsigned char* src, const uint32_t (&lane_off)[COPIES], uint32_t lds_tile, int wave_u) {
     src = uniform_ptr(src);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t l = lds_tile + (uint32_t)(4 * j + wave_u) * 1024u;
+    for (int j = 0; j < COPIES; ++j) {
+        const uint32_t l = lds_tile + (uint32_t)(NW * j + wave_u) * 1024u;
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off[j]), "s"(src), "s"(l) : "memory");
     }
 }
@@ -153,7 +156,7 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 // maximum and sum over the keys it sees itself (one of the two 4-row groups in every 8 keys); the two lanes of a
 // query column are merged once at the end.
 template <int G, int SRC>
-__global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __restrict__ q,
+__global__ __launch_bounds__(64 * NW, 8 / NW) void score_lse_mfma_kernel(const __bf16* __restrict__ q,
                                                                 const __bf16* __restrict__ k, ChunkTable ct, int nq,
                                                                 int Hq, int Hkv, int n_qtiles, float scale_log2e,
                                                                 float* __restrict__ lse2, ChunkRows rows,
@@ -167,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
     const int c = blockIdx.x / (Hkv * n_qtiles);
     const int c0 = ct.off[c], c1 = ct.off[c + 1];
     const int NQG = nq * G, NQG_pad = (NQG + 63) & ~63;
-    const int n_base = (qtile * 4 + wave) * 64;
+    const int n_base = (qtile * NW + wave) * 64;
     const float2* trow = SRC == SRC_PROMPT ? nullptr : table + (size_t)c * (D / 2);
 
     bf16x8 qf[2][8];
@@ -196,9 +199,9 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
     // address is the same for every tile but the last, whose rows past the chunk's end repeat its last key.
     const unsigned char* k_head = reinterpret_cast<const unsigned char*>(k + ((size_t)c0 * Hkv + g) * D);
     const size_t tile_stride = (size_t)64 * Hkv * D * 2;
-    uint32_t off_full[4], off_last[4];
+    uint32_t off_full[COPIES], off_last[COPIES];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < COPIES; ++j) {
         const int r = copy_row(j, wave, lane), ch = copy_chunk(j, wave, lane);
         const int rl = min(64 * (n_kt - 1) + r, c1 - c0 - 1) - 64 * (n_kt - 1);
         off_full[j] = (uint32_t)(r * Hkv * (D * 2) + 16 * ch);
@@ -206,26 +209,26 @@ __global__ __launch_bounds__(256, 2) void score_lse_mfma_kernel(const __bf16* __
     }
     const uint32_t lds_k = lds_address(k_lds);
     auto copy_tile = [&](int t, int slot) {
-        uint32_t off[4];
+        uint32_t off[COPIES];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) off[j] = (t == n_kt - 1) ? off_last[j] : off_full[j];
+        for (int j = 0; j < COPIES; ++j) off[j] = (t == n_kt - 1) ? off_last[j] : off_full[j];
         dma_tile(k_head + (size_t)t * tile_stride, off, lds_k + (uint32_t)slot * TILE_BYTES, wave);
     };
     // chunk store: a tile waits in registers for one step (its rows rotated as they arrive), then goes to its slot
-    const int st_vec = tid & 15, st_key = tid >> 4;
-    u32x4 kreg[4];
+    const int st_vec = tid & 15, st_key = tid >> 4;   // 4 NW rows per round of the workgroup
+    u32x4 kreg[COPIES];
     auto load_tile = [&](int t) {   // tiles past the last one re-read it; keys past the chunk's end are clamped
         t = min(t, n_kt - 1);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int j = min(c0 + t * 64 + st_key + 16 * i, c1 - 1);
+        for (int i = 0; i < COPIES; ++i) {
+            const int j = min(c0 + t * 64 + st_key + 4 * NW * i, c1 - 1);
             kreg[i] = load_key_vector<SRC>(k + ((size_t)key_row<SRC>(rows, c, c0, j) * Hkv + g) * D, st_vec, trow);
         }
     };
     auto write_tile = [&](int slot) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = st_key + 16 * i;
+        for (int i = 0; i < COPIES; ++i) {
+            const int r = st_key + 4 * NW * i;
             *reinterpret_cast<u32x4*>(k_lds + slot * TILE_BYTES + r * 256 + ((st_vec ^ row_key(r)) << 4)) = kreg[i];
         }
     };
@@ -354,7 +357,7 @@ __global__ void score_lse2_global_kernel(int n_chunks, int NQG, int NQG_pad, flo
 // tile t + 2 into the slot tile t - 1 has left.  A tile lands a whole step before it is read; the fragments of the
 // next step's first half are requested at the end of a step, so that they arrive while the wave waits at the barrier.
 template <int G, int SRC>
-__global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+__global__ __launch_bounds__(64 * NW, 8 / NW) void score_colsum_mfma_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                                                                 ChunkTable ct, int nq, int Hq, int Hkv, int n_ktiles,
                                                                 float scale_log2e, int scope_global,
                                                                 const float* __restrict__ lse2,
@@ -368,7 +371,7 @@ __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16*
     const int ktile = (blockIdx.x / Hkv) % n_ktiles;
     const int c = blockIdx.x / (Hkv * n_ktiles);
     const int c0 = ct.off[c], c1 = ct.off[c + 1];
-    const int kbase = c0 + ktile * 256;
+    const int kbase = c0 + ktile * (64 * NW);
     if (kbase >= c1) return;
     const int NQG = nq * G, NQG_pad = (NQG + 63) & ~63;
     const int L_ctx = ct.off[ct.n];
@@ -394,9 +397,9 @@ __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16*
     // repeat the last column (finite numbers; their normaliser is +inf).
     const unsigned char* q_head = reinterpret_cast<const unsigned char*>(q + (size_t)g * G * D);
     const size_t tile_stride = (size_t)(64 / G) * Hq * D * 2;
-    uint32_t off_full[4], off_last[4], a_off[8];
+    uint32_t off_full[COPIES], off_last[COPIES], a_off[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < COPIES; ++j) {
         const int r = copy_row(j, wave, lane), ch = copy_chunk(j, wave, lane);
         const int rl = min(64 * (n_qt - 1) + r, NQG - 1) - 64 * (n_qt - 1);
         off_full[j] = (uint32_t)(((r / G) * Hq + (r % G)) * (D * 2) + 16 * ch);
@@ -405,9 +408,9 @@ __global__ __launch_bounds__(256, 2) void score_colsum_mfma_kernel(const __bf16*
     frag_offsets(x, h, a_off);
     const uint32_t lds_q = lds_address(q_lds), lds_l = lds_address(lse_lds);
     auto copy_tile = [&](int t, int slot) {
-        uint32_t off[4];
+        uint32_t off[COPIES];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) off[j] = (t == n_qt - 1) ? off_last[j] : off_full[j];
+        for (int j = 0; j < COPIES; ++j) off[j] = (t == n_qt - 1) ? off_last[j] : off_full[j];
         dma_tile(q_head + (size_t)t * tile_stride, off, lds_q + (uint32_t)slot * TILE_BYTES, wave);
         // (every wave copies the tile's 64 normalisers, the same values to the same place: no branch in the step)
         dma_floats(lrow + 64 * t, (uint32_t)lane * 4u, lds_l + (uint32_t)slot * 256u);
@@ -484,12 +487,12 @@ hipError_t run(const Shape& s, const void* q, int nq, const void* k_ctx, const C
     const int NQG = nq * G;
     int max_len = 0;
     for (int i = 0; i < ct.n; ++i) max_len = ct.off[i + 1] - ct.off[i] > max_len ? ct.off[i + 1] - ct.off[i] : max_len;
-    const int n_qtiles = (NQG + 255) / 256, n_ktiles = (max_len + 255) / 256;
-    score_lse_mfma_kernel<G, SRC><<<dim3(n_qtiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
+    const int n_qtiles = (NQG + 64 * NW - 1) / (64 * NW), n_ktiles = (max_len + 64 * NW - 1) / (64 * NW);
+    score_lse_mfma_kernel<G, SRC><<<dim3(n_qtiles * ct.n * s.Hkv), dim3(64 * NW), 0, st>>>(
         (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, n_qtiles, c, ws.lse, rows, table);
     if (norm == FR_NORM_GLOBAL)
         score_lse2_global_kernel<<<dim3((NQG + 255) / 256, s.Hkv), dim3(256), 0, st>>>(ct.n, NQG, (NQG + 63) & ~63, ws.lse);
-    score_colsum_mfma_kernel<G, SRC><<<dim3(n_ktiles * ct.n * s.Hkv), dim3(256), 0, st>>>(
+    score_colsum_mfma_kernel<G, SRC><<<dim3(n_ktiles * ct.n * s.Hkv), dim3(64 * NW), 0, st>>>(
         (const __bf16*)q, (const __bf16*)k_ctx, ct, nq, s.Hq, s.Hkv, n_ktiles, c, norm == FR_NORM_GLOBAL ? 1 : 0,
         ws.lse, ws.col_partial, rows, table);
     score_reduce_heads_kernel<<<dim3((L_ctx + 255) / 256), dim3(256), 0, st>>>(ws.col_partial, L_ctx, s.Hkv, scores);
