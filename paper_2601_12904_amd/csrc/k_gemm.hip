@@ -15,6 +15,8 @@
 // of any 16 consecutive rows then fall into 16 distinct bank groups.
 #include "fr_internal.hpp"
 
+#include <type_traits>
+
 #include <algorithm>
 
 namespace fr {
@@ -243,7 +245,26 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
     for (int p = 0; p < N_STAGE - 1; ++p)
         if (p < n_kt) issue(p);
 
-    for (int kt = 0; kt < n_kt; ++kt) {
+    // One K tile.  The ring slot is a compile-time constant (the loop below is unrolled by the ring's length) and the
+    // LDS address of every fragment read sits in a register of its own, set up once (the ring is larger than the 64 KB
+    // an instruction's offset field reaches, and the compiler, left to itself, adds the slot's offset before every
+    // read): no address arithmetic between the matrix instructions.
+    uint32_t rd_w[N_STAGE][4][2], rd_a[N_STAGE][4][2];   // [slot][k step][row block parity]
+    {
+        const uint32_t lds_v = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+#pragma unroll
+        for (int sl = 0; sl < N_STAGE; ++sl)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int par = 0; par < 2; ++par) {
+                    rd_w[sl][ks][par] = lds_v + sl * STAGE_BYTES + (64 * wf) * 128 + frag[ks][par];
+                    rd_a[sl][ks][par] = lds_v + sl * STAGE_BYTES + TL::W_TILE_BYTES + (64 * wr) * 128 + frag[ks][par];
+                    asm volatile("" : "+v"(rd_w[sl][ks][par]), "+v"(rd_a[sl][ks][par]));   // keep them: no re-derivation in the loop
+                }
+    }
+    auto step = [&](auto slot_c, int kt) {
+        constexpr int slot = decltype(slot_c)::value;
         // own copies of tile kt are the oldest outstanding: wait until at most the (N_STAGE - 2) newer tiles remain
         if (kt + N_STAGE - 2 < n_kt) {
             constexpr int newer = DMA_PER_TILE * (N_STAGE - 2);
@@ -253,15 +274,14 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
         }
         barrier_keep_loads_in_flight();   // tile kt complete and visible; everyone is done with tile kt-1, whose stage is refilled next
         if (kt + N_STAGE - 1 < n_kt) issue(kt + N_STAGE - 1);
-        const unsigned char* wt = smem + (kt % N_STAGE) * STAGE_BYTES + (64 * wf) * 128;
-        const unsigned char* at = smem + (kt % N_STAGE) * STAGE_BYTES + TL::W_TILE_BYTES + (64 * wr) * 128;
         // fragments of K step ks + 1 are requested before the matrix instructions of step ks are issued
+        typedef const bf16x8 __attribute__((address_space(3))) * lds_frag_ptr;
         bf16x8 wfrag[2][2], afrag[2][2];
         auto request = [&](int ks, int buf) {
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
-                wfrag[buf][b] = *reinterpret_cast<const bf16x8*>(wt + b * (32 * 128) + frag[ks][b]);
-                afrag[buf][b] = *reinterpret_cast<const bf16x8*>(at + b * (32 * 128) + frag[ks][b]);
+                wfrag[buf][b] = *reinterpret_cast<lds_frag_ptr>((uintptr_t)(rd_w[slot][ks][b] + b * (32 * 128)));
+                afrag[buf][b] = *reinterpret_cast<lds_frag_ptr>((uintptr_t)(rd_a[slot][ks][b] + b * (32 * 128)));
             }
         };
         request(0, 0);
@@ -280,6 +300,22 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
             if (ks + 1 < 4) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);   // matrix
         }
+    };
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    using S2 = std::integral_constant<int, 2>;
+    using S3 = std::integral_constant<int, 3>;
+    int kt = 0;
+    for (; kt + N_STAGE <= n_kt; kt += N_STAGE) {
+        step(S0{}, kt);
+        step(S1{}, kt + 1);
+        step(S2{}, kt + 2);
+        if constexpr (N_STAGE == 4) step(S3{}, kt + 3);
+    }
+    if (kt < n_kt) step(S0{}, kt);
+    if (kt + 1 < n_kt) step(S1{}, kt + 1);
+    if constexpr (N_STAGE == 4) {
+        if (kt + 2 < n_kt) step(S2{}, kt + 2);
     }
 
     if (split_tile) {   // leave the partial sums: register-major, one coalesced 256-byte line per wave and register
