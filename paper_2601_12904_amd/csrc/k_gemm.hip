@@ -273,7 +273,6 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
             __builtin_amdgcn_s_waitcnt(0x0f70);
         }
         barrier_keep_loads_in_flight();   // tile kt complete and visible; everyone is done with tile kt-1, whose stage is refilled next
-        if (kt + N_STAGE - 1 < n_kt) issue(kt + N_STAGE - 1);
         // fragments of K step ks + 1 are requested before the matrix instructions of step ks are issued
         typedef const bf16x8 __attribute__((address_space(3))) * lds_frag_ptr;
         bf16x8 wfrag[2][2], afrag[2][2];
@@ -285,6 +284,9 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
             }
         };
         request(0, 0);
+        // the refill of the freed stage is issued behind the first fragment requests: its issue time passes while they
+        // are on their way, instead of in front of them
+        if (kt + N_STAGE - 1 < n_kt) issue(kt + N_STAGE - 1);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             if (ks + 1 < 4) request(ks + 1, (ks + 1) & 1);
