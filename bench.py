@@ -83,6 +83,28 @@ def cpu_baseline(w, k, sample_rows: int = 4096):
     }, qi, scores
 
 
+_RUNTIME_WARM = False
+
+
+def warm_runtime(ctx):
+    """The HIP runtime stalls once, for 33-39 ms, after about 4,200 kernel launches of a process (measured: a step loop
+    from a cold start always stops at the same step, and never again in 6,000 more): 4,096 launch-sized position shifts
+    (two kernels each, about 0.1 s together) put that behind us before anything is timed."""
+    global _RUNTIME_WARM
+    if _RUNTIME_WARM:
+        return
+    from paper_2601_12904_amd import binding as B
+    src = torch.zeros((8, ctx.desc.n_kv_heads, ctx.desc.head_dim),
+                      dtype=torch.bfloat16 if ctx.desc.dtype == B.FR_BF16 else torch.float32, device="cuda")
+    dst = torch.zeros_like(src)
+    for i in range(4096):
+        ctx.fr_rope_shift(src, dst, [0, 8], [0])
+        if i % 64 == 63:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    _RUNTIME_WARM = True
+
+
 def settle(fn, ms: float):
     """Untimed repetitions of `fn` for `ms` milliseconds: after idling the chip needs about 30 ms of load to reach its
     sustained clocks, and the first launches run up to 30 % slower."""
@@ -108,6 +130,7 @@ def bench_stack(args):
     k = B.fr_topk_count(w.L_ctx, w.ratio)
     R = k + w.nq
     ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    warm_runtime(ctx)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(args.seed)
     layers = [S.random_layer(hidden, ffn, Hq, Hkv, d, gen) for _ in range(n_layers)]
@@ -177,6 +200,7 @@ def bench_offline(args):
     dt, tdt = w.shape.dtype, H.TORCH_DTYPE[w.shape.dtype]
     Hq, Hkv = shape.n_q_heads, shape.n_kv_heads
     ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    warm_runtime(ctx)
     k_cached = H.dev(w.k_cached, dt)
     k_x = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
     v_x = torch.zeros((w.L, Hkv, d), dtype=tdt, device="cuda")
@@ -239,6 +263,7 @@ def bench_decode(args):
     gen.manual_seed(args.seed)
     rng = np.random.default_rng(args.seed)
     ctx = H.make_ctx(shape, 1024, 4, 8)
+    warm_runtime(ctx)
     sig = 1.0 / np.sqrt(d)
     L_ctx = chunks_per_q * clen
     k_crit = B.fr_topk_count(L_ctx, ratio)
@@ -329,6 +354,7 @@ def bench_shared_prefill(args):
     k_store = (torch.randn((N, Hkv, d), generator=gen, device="cuda") * sig).to(bf)
     v_store = (torch.randn((N, Hkv, d), generator=gen, device="cuda") * sig).to(bf)
     ctx = H.make_ctx(shape, L, cpq, nq)
+    warm_runtime(ctx)
     offs = np.arange(0, L_ctx + 1, clen, dtype=np.int32)
     queries = []
     for b in range(nb):
@@ -431,6 +457,7 @@ def bench_async_load(args):
     k = B.fr_topk_count(w.L_ctx, w.ratio)
     R = k + w.nq
     ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    warm_runtime(ctx)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(args.seed)
     layers = [S.random_layer(hidden, ffn, Hq, Hkv, d, gen) for _ in range(n_layers)]
@@ -541,6 +568,7 @@ def main():
     R = k + w.nq
 
     ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    warm_runtime(ctx)
     ctx.fr_set_option(B.FR_OPT_ATTN_SPLIT, {"auto": B.FR_ATTN_SPLIT_AUTO, "off": B.FR_ATTN_SPLIT_OFF,
                                             "on": B.FR_ATTN_SPLIT_ON}[args.attn_split])
     k_cached = H.dev(w.k_cached, dt)
