@@ -32,6 +32,18 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E peak
 MEASURED_ATTN_TRAFFIC = {"llama3_8b_layer_16x1024+512": 427.0e6}
 
 
+def attention_executed_pairs(q_index: np.ndarray, group: int) -> int:
+    """(row, key) pairs per query head the tiled attention kernel walks, masked ones included: a row tile holds
+    256 / group consecutive Q-index rows (the columns of one workgroup are rows x the group's heads) and walks whole
+    64-key tiles up to the position of its last row; the last row tile is padded to full size."""
+    rows_per_tile = 256 // group
+    total = 0
+    for r0 in range(0, len(q_index), rows_per_tile):
+        last = int(q_index[min(len(q_index), r0 + rows_per_tile) - 1])
+        total += rows_per_tile * ((last // 64 + 1) * 64)
+    return total
+
+
 def attention_pairs(q_index: np.ndarray) -> int:
     """Number of (row, key) pairs the method must evaluate per query head: sum over rows of pos + 1."""
     return int(np.sum(q_index.astype(np.int64) + 1))
@@ -655,6 +667,7 @@ def main():
     names = ["rope_shift", "score_select", "sparse_prefill_attn", "kv_scatter"]
     call_ms = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
                for i, n in enumerate(names)}
+    step_ms_events = [evs[s][0].elapsed_time(evs[s][4]) for s in range(args.steps)]   # per step, from the second pass
     assert np.array_equal(qi.cpu().numpy(), qi_host), "the Q index changed between steps"
 
     # ---- algorithmic work -------------------------------------------------------------------
@@ -765,11 +778,19 @@ def main():
         "select_stress": {"scores": n_sel, "selected": k_sel, "ms": round(sel_ms, 4),
                           "passes_over_the_scores": 5, "ms_of_one_read_at_hbm_peak": round(4 * n_sel / PEAK_HBM_GBPS / 1e6, 4),
                           "gbps_of_five_reads_and_the_output": round((5 * 4 * n_sel + 4 * k_sel) / (sel_ms * 1e-3) / 1e9, 1)},
+        "step_ms_events": {"median": round(float(np.median(step_ms_events)), 4), "min": round(float(np.min(step_ms_events)), 4),
+                           "note": "per-step event times of the second pass (events after every call)"},
         "roofline": {"kernel": "attn_fixed_ref_kernel (key-tile loop of fr_sparse_prefill_attn)" if kernel_ms
                      else "sparse_prefill_attn", "bound": "mfma", "achieved": round(kernel_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS if dt == "bf16" else 157.3, "unit": "TFLOP/s",
                      "frac": round(kernel_tflops / (PEAK_BF16_TFLOPS if dt == "bf16" else 157.3), 4),
                      "kernel_ms": round(attn_kernel_ms, 4), "launches_timed": len(kernel_ms),
+                     "kernel_ms_median": round(float(np.median(kernel_ms)), 4) if len(kernel_ms) else None,
+                     "kernel_ms_min": round(float(np.min(kernel_ms)), 4) if len(kernel_ms) else None,
+                     # masked-tile overhead: pairs the tiled kernel walks (whole 64-key tiles up to a row tile's last
+                     # position, padded last row tile) / pairs the method needs
+                     "executed_over_algorithmic_flops": round(attention_executed_pairs(qi_host, Hq // Hkv) / pairs, 4)
+                     if timer_on and (Hq // Hkv) in (1, 2, 4, 8) else None,
                      "whole_call_tflops": round(attn_tflops, 2),
                      "traffic": MEASURED_ATTN_TRAFFIC.get(w.name) if args.ratio is None and args.attn_split == "auto"
                      else None},
