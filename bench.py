@@ -183,6 +183,30 @@ def bench_stack(args):
     ms_every, ms_once = float(np.mean(t_every)), float(np.mean(t_once))
     gemm_flops = 2.0 * R * n_layers * (hidden * (Hq + 2 * Hkv) * d + Hq * d * hidden + 3 * hidden * ffn)
     attn_flops = 4.0 * d * Hq * attention_pairs(qi.cpu().numpy()) * n_layers
+    base = None
+    if not args.no_cpu_baseline:
+        # The oracle on the host cores: one layer of the stack in full (layer 0 on the same inputs: position shift,
+        # the layer's steps on all rows, write-back; the selection is config 2's and is timed there), times the number
+        # of layers: 32 layers would take minutes.
+        from oracle import fusionrag_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        rnd = lambda t: synth.round_to_storage(np.asarray(t, dtype=np.float32), "bf16").astype(np.float64)
+        wd = {n: H.host(getattr(layers[0], n)) for n in ("g1", "w_qkv", "w_o", "g2", "w_gate_up", "w_down")}
+        qi_h = qi.cpu().numpy().astype(np.int64)
+        kc0, vc0, h_host = H.host(k_cached[0]), H.host(v_cache[0][: w.L_ctx]), H.host(h0).astype(np.float64)
+        t0 = time.perf_counter()
+        kc = np.zeros((w.L, Hkv, d))
+        vc = np.zeros((w.L, Hkv, d))
+        kc[: w.L_ctx] = rnd(orc.rope_shift(kc0, w.chunk_offsets, w.src_pos0, None, w.shape.rope_base))
+        vc[: w.L_ctx] = vc0
+        orc.selective_prefill_layer(h_host, qi_h, kc, vc, wd, Hq, Hkv, d, w.shape.rope_base, 1e-5, round_fn=rnd)
+        t_layer = time.perf_counter() - t0
+        base = {"value": round(t_layer * n_layers * 1e3, 1), "unit": "ms/prompt", "cores": int(cores), "kind": "oracle",
+                "sample": f"layer 0 of {n_layers} in full on the same inputs ({t_layer:.1f} s), extrapolated x {n_layers}"}
     print(json.dumps({
         "metric": "TTFT-equivalent of the selective-prefill stack (ms), 17k ctx",
         "value": round(ms_every, 3), "unit": "ms/prompt", "n_gpus": 1, "steps": steps, "warmup": max(1, args.warmup // 3),
@@ -194,6 +218,7 @@ def bench_stack(args):
         "ms_selection_once": round(ms_once, 3),
         "gemm_tflop": round(gemm_flops / 1e12, 2), "attn_tflop": round(attn_flops / 1e12, 2),
         "overall_tflops": round((gemm_flops + attn_flops) / (ms_once * 1e-3) / 1e12, 1),
+        **({"cpu_baseline": base} if base else {}),
     }))
     ctx.close()
 
