@@ -207,3 +207,20 @@ def test_shared_score_select_argument_errors():
     if not torch.cuda.is_available():
         expect(B.FR_ERR_DEVICE, call32)
     c32.close()
+
+
+def test_bench_work_counts():
+    """The two pair counts bench.py prices the attention kernel with: the pairs the method needs (sum of pos + 1) and
+    the pairs the tiled kernel walks (whole 64-key tiles up to a row tile's last position, last row tile padded)."""
+    import bench
+    qi = np.array([0, 5, 63, 64, 200])
+    assert bench.attention_pairs(qi) == 1 + 6 + 64 + 65 + 201
+    # group size 4: 64 rows per tile -> one tile, padded to 64 rows, walking keys 0 .. 255 (four key tiles)
+    assert bench.attention_executed_pairs(qi, 4) == 64 * 256
+    # group size 8: 32 rows per tile; 40 rows -> two tiles, the first ends at position 31 (one key tile), the second at 39
+    qi = np.arange(40)
+    assert bench.attention_executed_pairs(qi, 8) == 32 * 64 + 32 * 64
+    # a full causal block of aligned size: the overhead is what the mask removes inside the diagonal tiles
+    qi = np.arange(256)
+    assert bench.attention_executed_pairs(qi, 4) == sum(64 * 64 * (t + 1) for t in range(4))
+    assert bench.attention_executed_pairs(qi, 4) >= bench.attention_pairs(qi)
