@@ -102,12 +102,6 @@ __device__ __forceinline__ void mfma_half(const bf16x8 (&a)[8], const bf16x8 (&b
 // chunk of the source row belongs there.
 __device__ __forceinline__ int copy_row(int j, int wave, int lane) { return 4 * (NW * j + wave) + (lane >> 4); }
 __device__ __forceinline__ int copy_chunk(int j, int wave, int lane) { return (lane & 15) ^ row_key(copy_row(j, wave, lane)); }
-// One tile, global -> LDS without passing through registers (global_load_lds_dwordx4: lane i of a wave deposits its
-// 16 bytes at the LDS address in M0 + 16 i).  The source is a workgroup-uniform base in scalar registers plus a
-// 32-bit per-lane offset, so a copy costs the vector ALU nothing.  Written out rather than left to the builtin: with
-// it the compiler takes the pending copy for an access that may complete out of order with the LDS reads and waits
-// for all outstanding fragment reads before every matrix instruction.  Completion: the issuing wave's vmcnt, then
-// a workgroup barrier.
 // A workgroup-uniform address, pinned to scalar registers (the copies take their base address from there; without
 // this the compiler may keep a pointer it also uses for vector loads in vector registers).
 template <typename T>
@@ -116,6 +110,12 @@ __device__ __forceinline__ const T* uniform_ptr(const T* p) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
     return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
 }
+// One tile, global -> LDS without passing through registers (global_load_lds_dwordx4: lane i of a wave deposits its
+// 16 bytes at the LDS address in M0 + 16 i).  The source is a workgroup-uniform base in scalar registers plus a
+// 32-bit per-lane offset, so a copy costs the vector ALU nothing.  Written out rather than left to the builtin: with
+// it the compiler takes the pending copy for an access that may complete out of order with the LDS reads and waits
+// for all outstanding fragment reads before every matrix instruction.  Completion: the issuing wave's vmcnt, then
+// a workgroup barrier.
 __device__ __forceinline__ void dma_tile(const unsigned char* src, const uint32_t (&lane_off)[COPIES], uint32_t lds_tile, int wave_u) {
     src = uniform_ptr(src);
 #pragma unroll
