@@ -109,7 +109,7 @@ struct GemmArgs {
     size_t partials_bytes;  // (host side: what the buffer holds)
 };
 constexpr int PARTIAL_FLOATS_PER_WAVE = 64 * 64;
-constexpr int MIN_K_TILES_PER_PART = 96;
+constexpr int MIN_K_TILES_PER_PART = 16;
 
 // Epilogue shared by the kernels: this wave's fp32 64 x 64 tile goes through LDS ([row][feature]), then every lane
 // handles 8 consecutive features of a row.  fw0 / rw0 = first feature / row of the wave's tile.
@@ -333,16 +333,19 @@ __global__ __launch_bounds__(128 * WF) void gemm_bf16_kernel(GemmArgs g) {
     gemm_epilogue<EPI>(g, acc, smem, wave, lane, f0 + 64 * wf, r0 + 64 * wr);
 }
 
-// Adds the n_parts partial sums of every split tile and runs the epilogue on the result.  grid.x = split tiles.
+// Adds the n_parts partial sums of every split tile and runs the epilogue on the result.  One wave per workgroup and
+// grid.x = split tiles * NW: the work is a stream of partial sums, and with a 17 KB staging area instead of the
+// ring's LDS many of these small workgroups share a CU and keep enough loads in flight.
 template <int EPI, int WF>
-__global__ __launch_bounds__(128 * WF) void gemm_fixup_kernel(GemmArgs g) {
+__global__ __launch_bounds__(64) void gemm_fixup_kernel(GemmArgs g) {
     using TL = Tiling<WF>;
     constexpr int NW = TL::NW, BF = TL::BF;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[64 * EPI_PITCH * 4];
+    const int lane = threadIdx.x;
+    const int split = (int)blockIdx.x / NW, wave = (int)blockIdx.x % NW;
     const int wf = wave % WF, wr = wave / WF;
     const int n_ftiles = (g.N + BF - 1) / BF;
-    const int tile = g.n_whole + (int)blockIdx.x;
+    const int tile = g.n_whole + split;
     const int f0 = (tile % n_ftiles) * BF, r0 = (tile / n_ftiles) * BR;
     f32x16 acc[2][2];
 #pragma unroll
@@ -352,7 +355,7 @@ __global__ __launch_bounds__(128 * WF) void gemm_fixup_kernel(GemmArgs g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
     for (int p = 0; p < g.n_parts; ++p) {
-        const float* src = g.partials + ((size_t)(((int)blockIdx.x * g.n_parts + p) * NW + wave)) * PARTIAL_FLOATS_PER_WAVE + lane;
+        const float* src = g.partials + ((size_t)((split * g.n_parts + p) * NW + wave)) * PARTIAL_FLOATS_PER_WAVE + lane;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -360,7 +363,7 @@ __global__ __launch_bounds__(128 * WF) void gemm_fixup_kernel(GemmArgs g) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][nb][v] += src[((2 * mb + nb) * 16 + v) * 64];
     }
-    gemm_epilogue<EPI>(g, acc, smem, wave, lane, f0 + 64 * wf, r0 + 64 * wr);
+    gemm_epilogue<EPI>(g, acc, smem, /*staging slot*/ 0, lane, f0 + 64 * wf, r0 + 64 * wr);
 }
 
 // y = x * rsqrt(mean(x^2) + eps) * gain, one wave per row, fp32 statistics.
@@ -413,9 +416,6 @@ hipError_t launch_gemm_wf(GemmArgs g, hipStream_t st) {
         r.err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI, WF>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
         if (r.err != hipSuccess) return r;
-        r.err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_fixup_kernel<EPI, WF>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-        if (r.err != hipSuccess) return r;
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&r.n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || r.n_cu <= 0)
@@ -430,8 +430,10 @@ hipError_t launch_gemm_wf(GemmArgs g, hipStream_t st) {
     const int n_tiles = ((g.N + TL::BF - 1) / TL::BF) * ((g.M + BR - 1) / BR);
     const int rest = n_tiles % n_cu;
     int n_parts = (rest == 0 || g_gemm_split == 0) ? 1 : std::min(n_cu / rest, 8);
-    // A part pays its own pipeline fill, a 128 KB dump of partial sums and its share of the second kernel: measured,
-    // parts of 112 K tiles gain 9 % (K = 14336, 384 tiles), parts of 32 or 16 lose 10 - 15 % (K = 4096).
+    // A part pays its own pipeline fill, a 128 KB dump of partial sums and its share of the second kernel (13 us for 128
+    // tiles in two parts).  Measured at 2970 rows: K = 14336, 384 tiles, two parts of 112 K tiles: 9 % less time;
+    // K = 4096, 576 tiles, four parts of 16: 8 % less; K = 4096, 384 tiles, two parts of 32: 4 % less; K = 4096,
+    // 2688 tiles (a tenth of them in the last round): no change.
     n_parts = std::min(n_parts, (g.K / BK) / MIN_K_TILES_PER_PART);
     if (n_parts > 1 &&
         (g.partials == nullptr || (size_t)rest * n_parts * TL::NW * PARTIAL_FLOATS_PER_WAVE * sizeof(float) > g.partials_bytes))
@@ -441,7 +443,7 @@ hipError_t launch_gemm_wf(GemmArgs g, hipStream_t st) {
     const int grid = g.n_whole + (n_tiles - g.n_whole) * g.n_parts;
     gemm_bf16_kernel<EPI, WF><<<dim3(grid), dim3(64 * TL::NW), TL::LDS_BYTES, st>>>(g);
     if (g.n_parts > 1)
-        gemm_fixup_kernel<EPI, WF><<<dim3(n_tiles - g.n_whole), dim3(64 * TL::NW), TL::LDS_BYTES, st>>>(g);
+        gemm_fixup_kernel<EPI, WF><<<dim3((n_tiles - g.n_whole) * TL::NW), dim3(64), 0, st>>>(g);
     return hipGetLastError();
 }
 

@@ -58,13 +58,14 @@ def test_linear_both_tilings(ctx, M, N, K, tile):
 
 @pytest.mark.parametrize("split", [0, 1])
 @pytest.mark.parametrize("tile", [128, 256])
-def test_epilogues_with_and_without_tail_split(ctx, tile, split):
+@pytest.mark.parametrize("K", [2 * 16 * 64, 2 * 96 * 64])   # two parts of 16 K tiles: the shortest split the launcher makes
+def test_epilogues_with_and_without_tail_split(ctx, tile, split, K):
     """Few output tiles and a long K: every tile belongs to the launch's last round and is computed by several
     workgroups along K, whose partial sums a second kernel adds before the epilogue (residual, SwiGLU, rotary Q/K/V).
     Forced off for comparison: same oracle, same tolerance."""
-    rng = np.random.default_rng(40 + tile + split)
+    rng = np.random.default_rng(40 + tile + split + K)
     Hq, Hkv, d = SHAPE.n_q_heads, SHAPE.n_kv_heads, SHAPE.head_dim
-    M, K = 300, 2 * 96 * 64          # two parts of 96 K tiles each is the shortest split the launcher makes
+    M = 300
     a = bf(rng.standard_normal((M, K)))
     ctx.fr_set_option(B.FR_OPT_GEMM_TILE, tile)
     ctx.fr_set_option(B.FR_OPT_GEMM_TAIL_SPLIT, split)
@@ -182,7 +183,7 @@ def test_two_layer_stack_against_oracle():
 
 def test_full_size_layer_sampled():
     """One decoder layer at the benchmark's size (hidden 4096, FFN 14336, config 2's prompt: 2970 rows at 15 %), in the
-    launch configuration `bench.py --config 5` times (256-feature workgroups, tail of the down projection split along
+    launch configuration `bench.py --config 5` times (256-feature workgroups, last round of each projection split along
     K): the fresh K/V of all rows and the layer output on sampled rows against the oracle, which follows the pipeline
     store by store (the Q/K/V projection for all rows, everything after it for the sampled ones)."""
     from paper_2601_12904_amd import stack as S
