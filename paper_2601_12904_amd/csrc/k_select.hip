@@ -23,9 +23,13 @@ constexpr int SEL_THREADS = 1024;
 // Among the candidates of this pass (keys that share the digits fixed so far), the digit of the k-th largest
 // key is the largest d whose suffix count S[d] = sum_{b >= d} hist[b] still reaches `remaining`.  One thread
 // per bin: suffix sums by wave shuffles, then the single thread that satisfies the condition publishes it.
+// `remaining` is read before the first barrier: between the two barriers the matching thread overwrites it, and the
+// four bin waves do not run in lockstep, so a read behind the first barrier could see the reduced value and let a
+// second bin match.  (The caller's barrier after the histogram orders this read behind the previous pass's write.)
 __device__ __forceinline__ void pick_digit(const uint32_t* hist, uint32_t* wave_tot, uint32_t* s_prefix,
                                            uint32_t* s_remaining, int shift) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t remaining = *s_remaining;
     uint32_t suf = 0u, own = 0u;
     if (tid < 256) {
         own = hist[tid];
@@ -39,7 +43,6 @@ __device__ __forceinline__ void pick_digit(const uint32_t* hist, uint32_t* wave_
     __syncthreads();
     if (tid < 256) {
         for (int w2 = wave + 1; w2 < 4; ++w2) suf += wave_tot[w2];
-        const uint32_t remaining = *s_remaining;
         const uint32_t above = suf - own;      // candidates with a larger digit
         if (suf >= remaining && above < remaining) {
             *s_remaining = remaining - above;  // still to take among keys with this digit
