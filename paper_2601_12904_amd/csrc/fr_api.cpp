@@ -331,7 +331,7 @@ fr_status fr_select_topk(fr_ctx* ctx, const float* scores, int64_t n, int64_t k,
         return fail(ctx, FR_ERR_INVALID_ARG, "scores / q_index_out must be 4-byte aligned");
     fr_status st = need_device(ctx);
     if (st != FR_OK) return st;
-    hipError_t e = launch_select(scores, n, k, nq, q_index_out, ctx->ws.select_tmp, (hipStream_t)stream);
+    hipError_t e = launch_select(scores, n, k, nq, q_index_out, ctx->ws.select_tmp, select_workspace_bytes(), (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "select launch", e);
     return FR_OK;
 }
@@ -392,7 +392,7 @@ fr_status fr_score_select(fr_ctx* ctx, const void* q_question, int32_t nq, const
             e = launch_score_simt(s, q_question, nq, k_ctx, ct, norm, ctx->ws, scores, hs);
         if (e != hipSuccess) return hip_fail(ctx, "score launch", e);
     }
-    hipError_t e = launch_select(scores, L_ctx, k, nq, q_index_out, ctx->ws.select_tmp, hs);
+    hipError_t e = launch_select(scores, L_ctx, k, nq, q_index_out, ctx->ws.select_tmp, select_workspace_bytes(), hs);
     if (e != hipSuccess) return hip_fail(ctx, "select launch", e);
     return FR_OK;
 }
@@ -491,7 +491,7 @@ fr_status fr_score_select_shared(fr_ctx* ctx, const void* q_question, int32_t nq
             if (e != hipSuccess) return hip_fail(ctx, "score launch", e);
         }
     }
-    hipError_t e = launch_select(scores, L_ctx, k, nq, q_index_out, ctx->ws.select_tmp, hs);
+    hipError_t e = launch_select(scores, L_ctx, k, nq, q_index_out, ctx->ws.select_tmp, select_workspace_bytes(), hs);
     if (e != hipSuccess) return hip_fail(ctx, "select launch", e);
     return FR_OK;
 }

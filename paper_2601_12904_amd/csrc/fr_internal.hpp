@@ -117,11 +117,22 @@ hipError_t launch_score_mfma_shared(const Shape& s, const void* q, int nq, const
                                     const int32_t* store_row0, const float2* table, int norm, const Workspace& ws,
                                     float* scores, hipStream_t st);
 
+// `tmp` (tmp_bytes bytes of device scratch) is used beyond SELECT_ONE_WORKGROUP_MAX scores only; a scratch too small
+// for n gives hipErrorInvalidValue before anything is launched.
+constexpr int64_t SELECT_ONE_WORKGROUP_MAX = 32768;
 hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index,
-                         uint32_t* tmp, hipStream_t st);
-size_t select_workspace_bytes();   // what `tmp` must hold
+                         uint32_t* tmp, size_t tmp_bytes, hipStream_t st);
+// Scratch layout of the multi-workgroup selection, in 32-bit words: state and histograms (fixed), two words per tile of
+// SELECT_TILE scores (the tiles' status words), candidate list.
+constexpr int64_t SELECT_TILE = 32768;
+constexpr size_t SELECT_FIXED_WORDS = 16 + 2 * 16384 + 16;
+constexpr size_t SELECT_CAND_WORDS = (size_t)1 << 20;
+constexpr size_t select_workspace_words(int64_t max_n) {   // scratch that serves every n <= max_n
+    return SELECT_FIXED_WORDS + 2 * (size_t)((max_n + SELECT_TILE - 1) / SELECT_TILE) + SELECT_CAND_WORDS;
+}
+size_t select_workspace_bytes();                    // scratch for any n up to 2^31 - 1
 hipError_t launch_select_large(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index, uint32_t* tmp,
-                               hipStream_t st);   // n beyond one workgroup's registers
+                               size_t tmp_bytes, hipStream_t st);   // n beyond one workgroup's registers
 
 hipError_t launch_kv_deviation(const Shape& s, const void* kv_a, const void* kv_b, int64_t n_tokens, float* out,
                                hipStream_t st);

@@ -161,8 +161,10 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topk_kernel(const float* _
     for (int i = 0; i < PER; ++i) emit(i, keys[i]);
 }
 
+static_assert(SELECT_ONE_WORKGROUP_MAX == (int64_t)SEL_THREADS * 32, "largest score vector of the one-workgroup kernel");
+
 hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index, uint32_t* tmp,
-                         hipStream_t st) {
+                         size_t tmp_bytes, hipStream_t st) {
     if (k + nq == 0) return hipSuccess;
     if (n <= (int64_t)SEL_THREADS * 8)
         select_topk_kernel<8><<<dim3(1), dim3(SEL_THREADS), 0, st>>>(scores, n, k, nq, q_index);
@@ -171,7 +173,7 @@ hipError_t launch_select(const float* scores, int64_t n, int64_t k, int nq, int3
     else if (n <= (int64_t)SEL_THREADS * 32)
         select_topk_kernel<32><<<dim3(1), dim3(SEL_THREADS), 0, st>>>(scores, n, k, nq, q_index);
     else
-        return launch_select_large(scores, n, k, nq, q_index, tmp, st);
+        return launch_select_large(scores, n, k, nq, q_index, tmp, tmp_bytes, st);
     return hipGetLastError();
 }
 

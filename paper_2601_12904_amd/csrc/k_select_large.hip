@@ -1,14 +1,16 @@
 // argTopk + Q index (Table 1, Sec. 3.2; Sec. 4.3) for score vectors that no longer fit one workgroup's registers:
 // the same definition as k_select.hip (the k largest scores, ties to the lowest index, emitted in ascending index
 // order, then the question positions), spread over the chip.  At these sizes the selection is bound by reading the
-// scores, so the aim is few passes over them:
-//   1. minimum and maximum key                                                    (one read)
-//   2. 4096-bin histogram of the top 12 bits of key - min, pick the bin of the k-th largest   (one read)
-//   3. the same for the next 12 bits among the keys of that bin; these candidates (about n / 4096 of them for spread
-//      data) are also listed, and the last 8 bits are settled on the list alone   (one read)
-//   4. per wave: how many of its keys lie above the threshold key / equal it, then a scan over the waves  (one read)
-//   5. every wave emits its selected indices at its offset, in index order        (one read)
-// Integer work only: the result is unique and equal to the single-workgroup kernel's.
+// scores, so the aim is few passes over them.  Three reads:
+//   1. histogram of the top 14 bits of the order-preserving key (sign, exponent, 5 mantissa bits); the bin that holds
+//      the k-th largest key follows from its suffix sums                                              (one read)
+//   2. histogram of the next 14 bits among the keys of that bin, whose indices are also listed; the last 4 bits are
+//      settled on the list alone (on all scores only if the list overflowed)                           (one read)
+//   3. one kernel counts, scans and emits: a workgroup keeps its 32768 keys in registers, counts those above / equal
+//      to the threshold, publishes the counts, obtains the counts of all tiles before it by a decoupled look-back
+//      over the tiles' status words, and writes its selected indices at their final places          (one read)
+// No minimum / maximum pass: the digits are those of the raw key.  Integer work only: the result is unique and equal
+// to the single-workgroup kernel's.
 #include "fr_internal.hpp"
 
 #include <algorithm>
@@ -22,41 +24,53 @@ __device__ __forceinline__ uint32_t score_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger score <=> larger key
 }
 
-constexpr int BINS = 4096, DIGIT = 12;
-constexpr int MAX_UNITS = 8192;          // waves of the counting / emitting passes
-constexpr int CAND_CAP = 1 << 18;        // listed candidates; more than that and the last level re-reads the scores
+// digit positions of the three levels
+constexpr int BITS0 = 14, BITS1 = 14, BITS2 = 4;
+constexpr int SHIFT0 = 18, SHIFT1 = 4, SHIFT2 = 0;
+constexpr int BINS = 1 << 14;            // bins of levels 0 and 1 (level 2: 16)
+static_assert(BITS0 + BITS1 + BITS2 == 32 && SHIFT0 == BITS1 + BITS2 && SHIFT1 == BITS2, "digits");
 constexpr int WG_LIST = 2048;            // candidates one workgroup collects in LDS before it appends them
+constexpr int TILE = (int)SELECT_TILE;    // scores per workgroup of the emitting pass (1024 threads x 32 keys)
+constexpr int64_t MAX_TILES = 65536;     // 2^31 scores
 
 struct State {
-    uint32_t kmin, kmax;
-    uint32_t prefix, mask;   // digits of (key - kmin) fixed so far
+    uint32_t prefix, mask;   // digits of the key fixed so far
     uint32_t remaining;      // how many keys are still to be taken among those that match the prefix
-    uint32_t cand_count;     // candidates seen by level 1 (listed up to CAND_CAP)
-    uint32_t thr_key, need_eq;
-    uint32_t pad[8];
+    uint32_t cand_count;     // candidates seen by level 1 (listed up to the list's capacity)
+    uint32_t ticket;         // tiles of the emitting pass are numbered in the order in which their workgroups start
+    uint32_t pad[11];
 };
-// workspace, in 32-bit words
-constexpr size_t W_STATE = 0, W_HIST = 16, W_GT = W_HIST + BINS, W_EQ = W_GT + MAX_UNITS, W_POS = W_EQ + MAX_UNITS,
-                 W_SEEN = W_POS + MAX_UNITS, W_CAND = W_SEEN + MAX_UNITS, W_END = W_CAND + CAND_CAP;
+// workspace, in 32-bit words: state, three histograms, the tiles' status words (64 bits each), candidate list
+constexpr size_t W_STATE = 0, W_HIST0 = 16, W_HIST1 = W_HIST0 + BINS, W_HIST2 = W_HIST1 + BINS, W_STATUS = W_HIST2 + 16;
+static_assert(W_STATUS % 2 == 0, "status words are 8-byte aligned");
+static_assert(W_STATUS == SELECT_FIXED_WORDS, "layout as announced to the callers that size the scratch");
+constexpr size_t CAND_MIN = 1 << 16;     // smallest candidate list worth having
 
-__device__ __forceinline__ int bits_of(uint32_t span) { return span == 0u ? 1 : 32 - __clz((int)span); }
-// digit position of a level: hi = bits not yet fixed before it; width = 0 means the level has nothing to do
-__device__ __forceinline__ void level_digit(const State& s, int level, int& width, int& shift) {
-    const int hi = bits_of(s.kmax - s.kmin) - DIGIT * level;
-    width = hi <= 0 ? 0 : (hi < DIGIT ? hi : DIGIT);
-    shift = hi - width;
+struct Layout {
+    int64_t n_tiles;
+    size_t w_cand;        // first word of the candidate list
+    uint32_t cand_cap;    // its capacity
+};
+// false: the workspace cannot hold the status words of n scores plus a minimal candidate list
+bool make_layout(int64_t n, size_t ws_words, Layout* l) {
+    l->n_tiles = (n + TILE - 1) / TILE;
+    l->w_cand = W_STATUS + 2 * (size_t)l->n_tiles;
+    if (l->n_tiles > MAX_TILES || l->w_cand + CAND_MIN > ws_words) return false;
+    const size_t cap = ws_words - l->w_cand;
+    l->cand_cap = (uint32_t)std::min<size_t>(cap, (size_t)1 << 30);
+    return true;
 }
 
-__global__ __launch_bounds__(1024) void select_init_kernel(uint32_t* __restrict__ ws, int64_t n, int64_t k, int nq,
-                                                           int32_t* __restrict__ out) {
-    State* s = reinterpret_cast<State*>(ws + W_STATE);
-    const int tid = threadIdx.x;
-    if (tid == 0) {
-        s->kmin = 0xFFFFFFFFu; s->kmax = 0u; s->prefix = 0u; s->mask = 0u;
-        s->remaining = (uint32_t)k; s->cand_count = 0u; s->thr_key = 0u; s->need_eq = 0u;
+__global__ __launch_bounds__(256) void select_init_kernel(uint32_t* __restrict__ ws, int64_t n, int64_t k, int nq,
+                                                          int64_t n_tiles, int32_t* __restrict__ out) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x, stride = (int64_t)gridDim.x * 256;
+    if (t == 0) {
+        State* s = reinterpret_cast<State*>(ws + W_STATE);
+        s->prefix = 0u; s->mask = 0u; s->remaining = (uint32_t)k; s->cand_count = 0u; s->ticket = 0u;
     }
-    for (int i = tid; i < BINS; i += 1024) ws[W_HIST + i] = 0u;
-    for (int i = tid; i < nq; i += 1024) out[k + i] = (int32_t)(n + i);   // question tokens: positions n .. n + nq - 1
+    const int64_t n_clear = (int64_t)(W_STATUS - W_HIST0) + 2 * n_tiles;   // histograms and status words
+    for (int64_t i = t; i < n_clear; i += stride) ws[W_HIST0 + i] = 0u;
+    for (int64_t i = t; i < nq; i += stride) out[k + i] = (int32_t)(n + i);   // question tokens: positions n .. n + nq - 1
 }
 
 // Streams all n scores through f(index, key, valid): 16-byte loads, eight per thread in flight, every load issued
@@ -64,7 +78,7 @@ __global__ __launch_bounds__(1024) void select_init_kernel(uint32_t* __restrict_
 // the end carry valid = false), so f may use wave-wide votes.  The few scores before the first and after the last
 // aligned 16 bytes go through block 0.
 constexpr int STREAM_U = 8;
-constexpr int STREAM_BLOCKS = 512;   // few workgroups: each ends with atomics on shared words (min / max, histogram bins)
+constexpr int STREAM_BLOCKS = 512;   // few workgroups: each ends with atomics on shared words (histogram bins)
 template <class F>
 __device__ __forceinline__ void stream_scores(const float* __restrict__ scores, int64_t n, F&& f) {
     typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -93,59 +107,36 @@ __device__ __forceinline__ void stream_scores(const float* __restrict__ scores, 
     }
 }
 
-__global__ __launch_bounds__(256) void select_minmax_kernel(const float* __restrict__ scores, int64_t n,
-                                                            uint32_t* __restrict__ ws) {
-    __shared__ uint32_t w_min[4], w_max[4];
-    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-    stream_scores(scores, n, [&](int64_t, uint32_t key, bool valid) {
-        if (valid) { kmin = min(kmin, key); kmax = max(kmax, key); }
-    });
-    for (int o = 32; o > 0; o >>= 1) {
-        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
-        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
-    }
-    if ((threadIdx.x & 63) == 0) { w_min[threadIdx.x >> 6] = kmin; w_max[threadIdx.x >> 6] = kmax; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        State* s = reinterpret_cast<State*>(ws + W_STATE);
-        atomicMin(&s->kmin, min(min(w_min[0], w_min[1]), min(w_min[2], w_min[3])));
-        atomicMax(&s->kmax, max(max(w_max[0], w_max[1]), max(w_max[2], w_max[3])));
-    }
-}
-
 // Histogram of this level's digit over the keys that match the digits fixed so far.  LEVEL 1 also lists those
 // keys' indices; LEVEL 2 walks that list when it is complete, else all scores.
 template <int LEVEL>
 __global__ __launch_bounds__(256) void select_hist_kernel(const float* __restrict__ scores, int64_t n,
-                                                          uint32_t* __restrict__ ws) {
-    __shared__ uint32_t hist[BINS];
+                                                          uint32_t* __restrict__ ws, size_t w_cand, uint32_t cand_cap) {
+    constexpr int NB = LEVEL == 2 ? 16 : BINS;
+    constexpr int SHIFT = LEVEL == 0 ? SHIFT0 : (LEVEL == 1 ? SHIFT1 : SHIFT2);
+    constexpr size_t W_HIST = LEVEL == 0 ? W_HIST0 : (LEVEL == 1 ? W_HIST1 : W_HIST2);
+    __shared__ uint32_t hist[NB];
+    __shared__ uint32_t wg_list[LEVEL == 1 ? WG_LIST : 1];
+    __shared__ uint32_t wg_count, wg_base;
     State* sp = reinterpret_cast<State*>(ws + W_STATE);
-    const State s = *sp;
-    int width, shift;
-    level_digit(s, LEVEL, width, shift);
-    if (width == 0) return;
-    const uint32_t dm = (1u << width) - 1u;
-    for (int i = threadIdx.x; i < BINS; i += 256) hist[i] = 0u;
+    const uint32_t prefix = sp->prefix, mask = sp->mask, cand_count = sp->cand_count;
+    for (int i = threadIdx.x; i < NB; i += 256) hist[i] = 0u;
+    if (threadIdx.x == 0) wg_count = 0u;
     __syncthreads();
     // LEVEL 1 lists its candidates: first in LDS, then one reservation in the global list per workgroup (an atomic
     // per candidate on one global word would serialise: about 8 ns each)
-    __shared__ uint32_t wg_list[WG_LIST];
-    __shared__ uint32_t wg_count, wg_base;
-    if (threadIdx.x == 0) wg_count = 0u;
-    __syncthreads();
     auto visit = [&](int64_t idx, uint32_t key, bool valid) {
-        const uint32_t rk = key - s.kmin;
-        if (valid && (rk & s.mask) == s.prefix) {
-            atomicAdd(&hist[(rk >> shift) & dm], 1u);
+        if (valid && (key & mask) == prefix) {
+            atomicAdd(&hist[(key >> SHIFT) & (uint32_t)(NB - 1)], 1u);
             if (LEVEL == 1) {
                 const uint32_t slot = atomicAdd(&wg_count, 1u);
                 if (slot < (uint32_t)WG_LIST) wg_list[slot] = (uint32_t)idx;
             }
         }
     };
-    if (LEVEL == 2 && s.cand_count <= (uint32_t)CAND_CAP) {
-        for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < (int64_t)s.cand_count; j += (int64_t)gridDim.x * 256)
-            visit(0, score_key(scores[ws[W_CAND + j]]), true);
+    if (LEVEL == 2 && cand_count <= cand_cap) {
+        for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < (int64_t)cand_count; j += (int64_t)gridDim.x * 256)
+            visit(0, score_key(scores[ws[w_cand + j]]), true);
     } else {
         stream_scores(scores, n, visit);
     }
@@ -153,183 +144,176 @@ __global__ __launch_bounds__(256) void select_hist_kernel(const float* __restric
     if (LEVEL == 1) {
         // a workgroup with more candidates than its LDS list holds makes the global count overflow on purpose:
         // the last level then re-reads the scores instead of the list
-        if (threadIdx.x == 0) wg_base = atomicAdd(&sp->cand_count, wg_count <= (uint32_t)WG_LIST ? wg_count : (uint32_t)CAND_CAP + 1u);
+        if (threadIdx.x == 0) wg_base = atomicAdd(&sp->cand_count, wg_count <= (uint32_t)WG_LIST ? wg_count : cand_cap + 1u);
         __syncthreads();
         if (wg_count <= (uint32_t)WG_LIST)
             for (uint32_t i = threadIdx.x; i < wg_count; i += 256)
-                if (wg_base + i < (uint32_t)CAND_CAP) ws[W_CAND + wg_base + i] = wg_list[i];
+                if (wg_base + i < cand_cap) ws[w_cand + wg_base + i] = wg_list[i];
     }
-    __syncthreads();
-    for (int i = threadIdx.x; i < BINS; i += 256) {
+    for (int i = threadIdx.x; i < NB; i += 256) {
         const uint32_t c = hist[i];
         if (c != 0u) atomicAdd(&ws[W_HIST + i], c);
     }
 }
 
 // One workgroup: the digit of the k-th largest key is the largest d whose suffix count reaches `remaining`.
+// Thread t owns PER consecutive bins; suffix sums run from the last bin down.  Afterwards `remaining` counts the keys
+// still to take among those with the chosen digits; after LEVEL 2 the prefix is the threshold key itself.
 template <int LEVEL>
 __global__ __launch_bounds__(1024) void select_pick_kernel(uint32_t* __restrict__ ws) {
+    constexpr int NB = LEVEL == 2 ? 16 : BINS;
+    constexpr int PER = LEVEL == 2 ? 1 : BINS / 1024;
+    constexpr int SHIFT = LEVEL == 0 ? SHIFT0 : (LEVEL == 1 ? SHIFT1 : SHIFT2);
+    constexpr size_t W_HIST = LEVEL == 0 ? W_HIST0 : (LEVEL == 1 ? W_HIST1 : W_HIST2);
     __shared__ uint32_t wave_tot[16];
     State* sp = reinterpret_cast<State*>(ws + W_STATE);
-    const State s = *sp;
-    int width, shift;
-    level_digit(s, LEVEL, width, shift);
+    const uint32_t prefix = sp->prefix, mask = sp->mask, remaining = sp->remaining;   // read before any thread writes
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (width != 0) {
-        // thread t owns bins 4t .. 4t+3; suffix sums run from the last bin down
-        uint32_t c[4], own = 0u;
+    uint32_t c[PER], own = 0u;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { c[e] = ws[W_HIST + 4 * tid + e]; own += c[e]; }
-        uint32_t suf = own;   // sum over threads >= t of this wave
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t t = (uint32_t)__shfl_down((int)suf, o);
-            if (lane + o < 64) suf += t;
-        }
-        if (lane == 0) wave_tot[wave] = suf;
-        __syncthreads();
-        for (int w2 = wave + 1; w2 < 16; ++w2) suf += wave_tot[w2];
-        uint32_t above = suf - own;   // keys with a digit beyond this thread's bins
-        if (suf >= s.remaining && above < s.remaining) {
+    for (int e = 0; e < PER; ++e) {
+        c[e] = (PER * tid + e < NB) ? ws[W_HIST + PER * tid + e] : 0u;
+        own += c[e];
+    }
+    uint32_t suf = own;   // sum over threads >= t of this wave
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = (uint32_t)__shfl_down((int)suf, o);
+        if (lane + o < 64) suf += t;
+    }
+    if (lane == 0) wave_tot[wave] = suf;
+    __syncthreads();
+    for (int w2 = wave + 1; w2 < 16; ++w2) suf += wave_tot[w2];
+    uint32_t above = suf - own;   // keys with a digit beyond this thread's bins
+    if (suf >= remaining && above < remaining) {   // exactly one thread
 #pragma unroll
-            for (int e = 3; e >= 0; --e) {
-                if (above + c[e] >= s.remaining) {
-                    sp->prefix = s.prefix | ((uint32_t)(4 * tid + e) << shift);
-                    sp->mask = s.mask | (((1u << width) - 1u) << shift);
-                    sp->remaining = s.remaining - above;
-                    break;
-                }
-                above += c[e];
+        for (int e = PER - 1; e >= 0; --e) {
+            if (above + c[e] >= remaining) {
+                sp->prefix = prefix | ((uint32_t)(PER * tid + e) << SHIFT);
+                sp->mask = mask | ((uint32_t)(NB - 1) << SHIFT);
+                sp->remaining = remaining - above;
+                break;
             }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int e = 0; e < 4; ++e) ws[W_HIST + 4 * tid + e] = 0u;
-    }
-    if (LEVEL == 2) {
-        __syncthreads();
-        if (tid == 0) {
-            sp->thr_key = sp->prefix + s.kmin;
-            sp->need_eq = sp->remaining;
+            above += c[e];
         }
     }
 }
 
-// Unit u (one wave) owns the contiguous range [u * per_unit, (u + 1) * per_unit), per_unit a multiple of 64.
-__global__ __launch_bounds__(256) void select_count_kernel(const float* __restrict__ scores, int64_t n, int64_t per_unit,
-                                                           uint32_t* __restrict__ ws) {
-    const State* sp = reinterpret_cast<const State*>(ws + W_STATE);
-    const uint32_t thr = sp->thr_key;
-    const int lane = threadIdx.x & 63;
-    const int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t begin = u * per_unit, end = min(n, begin + per_unit);
-    uint32_t gt = 0u, eq = 0u;
-    for (int64_t i = begin + lane; i < end; i += 64) {
-        const uint32_t key = score_key(scores[i]);
-        gt += key > thr;
-        eq += key == thr;
-    }
-    for (int o = 32; o > 0; o >>= 1) {
-        gt += (uint32_t)__shfl_xor((int)gt, o);
-        eq += (uint32_t)__shfl_xor((int)eq, o);
-    }
-    if (lane == 0) { ws[W_GT + u] = gt; ws[W_EQ + u] = eq; }
-}
+// ---- pass 3: count, scan over the tiles (decoupled look-back) and emit, in one kernel ---------------------------
+// A tile's status word: bits 62..63 = 0 nothing yet / 1 the tile's own counts / 2 the counts of all tiles up to and
+// including it; bits 31..61 = keys equal to the threshold; bits 0..30 = keys above it.  The word is the whole
+// message (no other memory is exchanged between workgroups), so relaxed device-scope accesses suffice.  Tiles are
+// numbered by a ticket taken when a workgroup starts: every tile with a lower number has then started too and
+// publishes without waiting for anything but lower-numbered tiles, so every wait below ends.
+constexpr uint64_t ST_OWN = 1ull << 62, ST_INCL = 2ull << 62;
+__device__ __forceinline__ uint64_t st_pack(uint64_t flag, uint32_t gt, uint32_t eq) { return flag | ((uint64_t)eq << 31) | gt; }
 
-// Exclusive scans over the units: equal keys seen before each unit, then output offsets (keys above the threshold
-// plus the share of the equal keys that is still needed, lowest index first).
-__global__ __launch_bounds__(1024) void select_scan_kernel(uint32_t* __restrict__ ws, int n_units) {
-    __shared__ uint32_t wave_tot[16];
-    const State* sp = reinterpret_cast<const State*>(ws + W_STATE);
-    const uint32_t need_eq = sp->need_eq;
+__global__ __launch_bounds__(1024, 8) void select_emit_kernel(const float* __restrict__ scores, int64_t n,
+                                                           uint32_t* __restrict__ ws, int32_t* __restrict__ out) {
+    constexpr int SLOTS = 32;   // keys per thread; wave w owns keys [2048 w, 2048 (w + 1)) of the tile, slot j = 64 of them
+    __shared__ uint32_t s_tile, s_gt[16], s_eq[16], s_base_gt, s_base_eq;
+    State* sp = reinterpret_cast<State*>(ws + W_STATE);
+    uint64_t* status = reinterpret_cast<uint64_t*>(ws + W_STATUS);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    constexpr int PER = MAX_UNITS / 1024;
-    auto block_exclusive = [&](uint32_t own) -> uint32_t {   // sum of `own` over the threads before this one
-        uint32_t inc = own;
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t t = (uint32_t)__shfl_up((int)inc, o);
-            if (lane >= o) inc += t;
+    if (tid == 0) s_tile = atomicAdd(&sp->ticket, 1u);
+    const uint32_t thr = sp->prefix, need_eq = sp->remaining;   // (level 2 left the threshold key and the equal keys to take)
+    __syncthreads();
+    const int64_t tile = s_tile;
+    const int64_t first = tile * TILE + wave * (64 * SLOTS) + lane;   // this lane's keys: first + 64 j
+    // all loads in flight together, addressed as (tile base: uniform) + (32-bit offset in the tile); offsets clamped
+    // to the last score
+    const float* __restrict__ tile_scores = scores + tile * TILE;
+    const uint32_t off0 = (uint32_t)(wave * (64 * SLOTS) + lane);
+    const uint32_t last = (uint32_t)min((int64_t)TILE - 1, n - 1 - tile * TILE);
+    float raw[SLOTS];
+#pragma unroll
+    for (int j = 0; j < SLOTS; ++j) raw[j] = tile_scores[min(off0 + 64u * j, last)];
+    uint32_t gt_bits = 0u, eq_bits = 0u;   // bit j: this lane's key of slot j lies above / equals the threshold
+#pragma unroll
+    for (int j = 0; j < SLOTS; ++j) {
+        const uint32_t key = score_key(raw[j]);
+        const bool valid = off0 + 64u * j <= last;
+        gt_bits |= (uint32_t)(valid && key > thr) << j;
+        eq_bits |= (uint32_t)(valid && key == thr) << j;
+    }
+    uint32_t w_cnt = (uint32_t)__popc(gt_bits) | ((uint32_t)__popc(eq_bits) << 16);   // wave totals, packed (<= 2048 each)
+    for (int o = 32; o > 0; o >>= 1) w_cnt += (uint32_t)__shfl_xor((int)w_cnt, o);
+    const uint32_t w_gt = w_cnt & 0xFFFFu, w_eq = w_cnt >> 16;
+    if (lane == 0) { s_gt[wave] = w_gt; s_eq[wave] = w_eq; }
+    __syncthreads();
+    if (wave == 0) {
+        uint32_t t_gt = 0u, t_eq = 0u;   // the tile's own counts
+#pragma unroll
+        for (int w2 = 0; w2 < 16; ++w2) { t_gt += s_gt[w2]; t_eq += s_eq[w2]; }
+        if (lane == 0 && tile > 0)
+            __hip_atomic_store(&status[tile], st_pack(ST_OWN, t_gt, t_eq), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // look back: lane l examines tile (tile - 1 - l - 64 r); tiles below 0 count as "all before: nothing"
+        uint32_t b_gt = 0u, b_eq = 0u;
+        for (int64_t hi = tile - 1; ; hi -= 64) {
+            const int64_t t = hi - lane;
+            uint64_t st = ST_INCL;
+            if (t >= 0) {
+                do {
+                    st = __hip_atomic_load(&status[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((st >> 62) == 0ull) __builtin_amdgcn_s_sleep(1);
+                } while ((st >> 62) == 0ull);
+            }
+            const uint64_t incl = __ballot((st >> 62) == 2ull);
+            // the nearest tile that knows its inclusive counts ends the walk: lanes up to it contribute
+            const int stop = incl ? (int)__builtin_ctzll(incl) : 63;
+            uint32_t g = lane <= stop ? (uint32_t)(st & 0x7FFFFFFFull) : 0u;
+            uint32_t e = lane <= stop ? (uint32_t)((st >> 31) & 0x7FFFFFFFull) : 0u;
+            for (int o = 32; o > 0; o >>= 1) {
+                g += (uint32_t)__shfl_xor((int)g, o);
+                e += (uint32_t)__shfl_xor((int)e, o);
+            }
+            b_gt += g;
+            b_eq += e;
+            if (incl) break;
         }
-        __syncthreads();
-        if (lane == 63) wave_tot[wave] = inc;
-        __syncthreads();
-        uint32_t before = 0u;
-        for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2];
-        return before + inc - own;
-    };
-    uint32_t gt[PER], eq[PER], own = 0u;
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-        const int u = PER * tid + e;
-        gt[e] = u < n_units ? ws[W_GT + u] : 0u;
-        eq[e] = u < n_units ? ws[W_EQ + u] : 0u;
-        own += eq[e];
+        if (lane == 0) {
+            __hip_atomic_store(&status[tile], st_pack(ST_INCL, b_gt + t_gt, b_eq + t_eq), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            s_base_gt = b_gt;
+            s_base_eq = b_eq;
+        }
     }
-    uint32_t seen = block_exclusive(own);
-    uint32_t out_own = 0u, seen_at[PER], take[PER];
+    __syncthreads();
+    uint32_t gt_seen = s_base_gt, eq_seen = s_base_eq;   // keys above / equal to the threshold before this wave's first key
+    for (int w2 = 0; w2 < wave; ++w2) { gt_seen += s_gt[w2]; eq_seen += s_eq[w2]; }
+    // key i is chosen if it lies above the threshold, or equals it and fewer than need_eq equal keys precede it; its
+    // place is (keys above the threshold before i) + min(equal keys before i, need_eq)
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
-        seen_at[e] = seen;
-        take[e] = gt[e] + (need_eq > seen ? min(eq[e], need_eq - seen) : 0u);
-        out_own += take[e];
-        seen += eq[e];
-    }
-    uint32_t pos = block_exclusive(out_own);
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-        const int u = PER * tid + e;
-        if (u < n_units) { ws[W_POS + u] = pos; ws[W_SEEN + u] = seen_at[e]; }
-        pos += take[e];
-    }
-}
-
-__global__ __launch_bounds__(256) void select_emit_kernel(const float* __restrict__ scores, int64_t n, int64_t per_unit,
-                                                          const uint32_t* __restrict__ ws, int32_t* __restrict__ out) {
-    const State* sp = reinterpret_cast<const State*>(ws + W_STATE);
-    const uint32_t thr = sp->thr_key, need_eq = sp->need_eq;
-    const int lane = threadIdx.x & 63;
-    const int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t begin = u * per_unit, end = min(n, begin + per_unit);
-    if (begin >= end) return;
-    uint32_t pos = ws[W_POS + u], eq_seen = ws[W_SEEN + u];
-    const uint64_t below = (1ull << lane) - 1ull;
-    for (int64_t base = begin; base < end; base += 64) {   // wave-uniform trip count
-        const int64_t i = base + lane;
-        const uint32_t key = i < end ? score_key(scores[i]) : 0u;
-        const bool gt = i < end && key > thr, eq = i < end && key == thr;
-        const uint64_t beq = __ballot(eq);
-        const bool sel = gt || (eq && eq_seen + (uint32_t)__popcll(beq & below) < need_eq);
-        const uint64_t bsel = __ballot(sel);
-        if (sel) out[pos + (uint32_t)__popcll(bsel & below)] = (int32_t)i;
-        pos += (uint32_t)__popcll(bsel);
-        eq_seen += (uint32_t)__popcll(beq);
+    for (int j = 0; j < SLOTS; ++j) {
+        const bool gt = (gt_bits >> j) & 1u, eq = (eq_bits >> j) & 1u;
+        const uint64_t bg = __ballot(gt), be = __ballot(eq);
+        const uint32_t g_before = gt_seen + __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
+        const uint32_t e_before = eq_seen + __builtin_amdgcn_mbcnt_hi((uint32_t)(be >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)be, 0u));
+        if (gt || (eq && e_before < need_eq)) out[g_before + min(e_before, need_eq)] = (int32_t)(first + 64 * j);
+        gt_seen += (uint32_t)__popcll(bg);
+        eq_seen += (uint32_t)__popcll(be);
     }
 }
 
 }  // namespace
 
-size_t select_workspace_bytes() { return W_END * sizeof(uint32_t); }
+size_t select_workspace_bytes() { return select_workspace_words((int64_t)MAX_TILES * TILE) * sizeof(uint32_t); }
 
 hipError_t launch_select_large(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index, uint32_t* ws,
-                               hipStream_t st) {
-    select_init_kernel<<<dim3(1), dim3(1024), 0, st>>>(ws, n, k, nq, q_index);
+                               size_t ws_bytes, hipStream_t st) {
+    Layout lay;
+    if (!make_layout(n, ws_bytes / sizeof(uint32_t), &lay)) return hipErrorInvalidValue;
+    const int64_t n_clear = (int64_t)(W_STATUS - W_HIST0) + 2 * lay.n_tiles + nq;
+    select_init_kernel<<<dim3((unsigned)std::min<int64_t>(256, (n_clear + 255) / 256)), dim3(256), 0, st>>>(ws, n, k, nq, lay.n_tiles, q_index);
     if (k <= 0 || n <= 0) return hipGetLastError();
     // (k == n needs no special case: the threshold is then the smallest key, and every key equal to it is needed)
     const int grid = (int)std::min<int64_t>(STREAM_BLOCKS, (n + 2047) / 2048);
-    select_minmax_kernel<<<dim3(grid), dim3(256), 0, st>>>(scores, n, ws);
-    select_hist_kernel<0><<<dim3(grid), dim3(256), 0, st>>>(scores, n, ws);
+    select_hist_kernel<0><<<dim3(grid), dim3(256), 0, st>>>(scores, n, ws, lay.w_cand, lay.cand_cap);
     select_pick_kernel<0><<<dim3(1), dim3(1024), 0, st>>>(ws);
-    select_hist_kernel<1><<<dim3(grid), dim3(256), 0, st>>>(scores, n, ws);
+    select_hist_kernel<1><<<dim3(grid), dim3(256), 0, st>>>(scores, n, ws, lay.w_cand, lay.cand_cap);
     select_pick_kernel<1><<<dim3(1), dim3(1024), 0, st>>>(ws);
-    select_hist_kernel<2><<<dim3(grid), dim3(256), 0, st>>>(scores, n, ws);
+    select_hist_kernel<2><<<dim3(grid), dim3(256), 0, st>>>(scores, n, ws, lay.w_cand, lay.cand_cap);
     select_pick_kernel<2><<<dim3(1), dim3(1024), 0, st>>>(ws);
-    // units of at least 1024 scores, at most MAX_UNITS of them
-    int64_t per_unit = std::max<int64_t>(1024, (n + MAX_UNITS - 1) / MAX_UNITS);
-    per_unit = (per_unit + 63) / 64 * 64;
-    const int n_units = (int)((n + per_unit - 1) / per_unit);
-    const int blocks = (n_units + 3) / 4;
-    select_count_kernel<<<dim3(blocks), dim3(256), 0, st>>>(scores, n, per_unit, ws);
-    select_scan_kernel<<<dim3(1), dim3(1024), 0, st>>>(ws, n_units);
-    select_emit_kernel<<<dim3(blocks), dim3(256), 0, st>>>(scores, n, per_unit, ws, q_index);
+    select_emit_kernel<<<dim3((unsigned)lay.n_tiles), dim3(1024), 0, st>>>(scores, n, ws, q_index);
     return hipGetLastError();
 }
 
