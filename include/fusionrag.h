@@ -179,6 +179,22 @@ fr_status fr_score_select_shared(fr_ctx* ctx, const void* q_question, int32_t nq
 fr_status fr_select_topk(fr_ctx* ctx, const float* scores, int64_t n, int64_t k, int32_t nq,
                          int32_t* q_index_out, void* stream);
 
+/* fr_select_topk for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It needs no context and calls no allocating routine: the scratch of the
+ * multi-workgroup selection (about 4.2 MB: state, histograms, per-tile status words, candidate list) is a static
+ * device array inside the library, one copy per GPU, held until the process ends.  Same kernels and same result as
+ * fr_select_topk.
+ *   ctx     NULL, or a context that only receives the error message of a failing call (fr_last_error)
+ *   scores, n, k, nq, q_index_out, stream: as in fr_select_topk; the tensors live on the current device, which is
+ *           also the stream's
+ * n > FR_SELECT_STATIC_MAX_SCORES is refused with FR_ERR_WORKSPACE before anything is launched.  The array's address
+ * is resolved at the first call on a device (or by fr_create on that device), so make one of the two eagerly before
+ * capturing a graph.  All calls on one GPU share that GPU's array: calls that overlap in time (different streams)
+ * race; calls on one stream are ordered and each clears what it needs. */
+#define FR_SELECT_STATIC_MAX_SCORES (1 << 24)
+fr_status fr_select_topk_static(fr_ctx* ctx, const float* scores, int64_t n, int64_t k, int32_t nq,
+                                int32_t* q_index_out, void* stream);
+
 /* KV deviation of one layer (eq. 7): deviation_out[t] = sum over the n_kv_heads * head_dim components c of
  * (kv_a[t, c] - kv_b[t, c])^2, accumulated in fp32.  Followed by fr_select_topk it is the CacheBlend selector
  * (eq. 8), which the paper compares Query-Guided Selection against.  The paper takes the key half of layer 2.

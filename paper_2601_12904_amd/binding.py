@@ -17,6 +17,7 @@ FR_F32, FR_BF16 = 0, 1
 FR_ROPE_INTERLEAVED, FR_ROPE_HALF = 0, 1
 FR_NORM_PER_CHUNK, FR_NORM_GLOBAL, FR_NORM_RAW = 0, 1, 2
 FR_MAX_CHUNKS = 256
+FR_SELECT_STATIC_MAX_SCORES = 1 << 24
 STATUS_NAMES = {0: "FR_OK", 1: "FR_ERR_INVALID_ARG", 2: "FR_ERR_UNSUPPORTED", 3: "FR_ERR_WORKSPACE",
                 4: "FR_ERR_DEVICE"}
 FR_OPT_ATTN_SOFTMAX = 1
@@ -29,7 +30,7 @@ FR_DECODE_KERNEL_AUTO, FR_DECODE_KERNEL_GENERIC = 0, 1
 FR_ATTN_SOFTMAX_AUTO, FR_ATTN_SOFTMAX_RUNNING_MAX = 0, 1
 FR_ATTN_SPLIT_AUTO, FR_ATTN_SPLIT_OFF, FR_ATTN_SPLIT_ON = 0, 1, 2
 EXPORTS = ("fr_create", "fr_destroy", "fr_last_error", "fr_workspace_bytes", "fr_set_option", "fr_attn_kernel_times", "fr_topk_count", "fr_rope_shift",
-           "fr_score_select", "fr_score_select_shared", "fr_select_topk", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_writeback", "fr_sparse_prefill_attn_shared", "fr_shared_batch_workspace_bytes", "fr_sparse_prefill_attn_shared_batch", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
+           "fr_score_select", "fr_score_select_shared", "fr_select_topk", "fr_select_topk_static", "fr_kv_deviation", "fr_sparse_prefill_attn", "fr_sparse_prefill_attn_writeback", "fr_sparse_prefill_attn_shared", "fr_shared_batch_workspace_bytes", "fr_sparse_prefill_attn_shared_batch", "fr_decode_attn", "fr_mark_stale_rows", "fr_kv_scatter", "fr_rmsnorm", "fr_linear",
            "fr_linear_swiglu", "fr_qkv_rope")
 
 
@@ -89,6 +90,8 @@ def load() -> ctypes.CDLL:
     lib.fr_score_select_shared.restype = i32
     lib.fr_select_topk.argtypes = [vp, vp, i64, i64, i32, vp, vp]
     lib.fr_select_topk.restype = i32
+    lib.fr_select_topk_static.argtypes = [vp, vp, i64, i64, i32, vp, vp]
+    lib.fr_select_topk_static.restype = i32
     lib.fr_kv_deviation.argtypes = [vp, vp, vp, i64, vp, vp]
     lib.fr_kv_deviation.restype = i32
     lib.fr_sparse_prefill_attn.argtypes = [vp, vp, vp, i32, vp, vp, i64, vp, vp, vp, vp, vp]
@@ -147,6 +150,16 @@ def _stream(stream) -> Optional[int]:
 
 def fr_topk_count(L_ctx: int, ratio: float) -> int:
     return int(load().fr_topk_count(int(L_ctx), float(ratio)))
+
+
+def fr_select_topk_static(scores, n: int, k: int, nq: int, q_index_out, stream=None, ctx: "Context" = None):
+    """fr_select_topk without a context and without any allocation (the library's static scratch); `ctx`, if given,
+    only receives the error message."""
+    lib = load()
+    st = lib.fr_select_topk_static(ctx._h if ctx is not None else None, _ptr(scores), int(n), int(k), int(nq),
+                                   _ptr(q_index_out), _stream(stream))
+    if st != FR_OK:
+        raise FusionRAGError(st, lib.fr_last_error(ctx._h).decode() if ctx is not None else "fr_select_topk_static failed")
 
 
 class Context:

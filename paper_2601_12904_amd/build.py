@@ -13,7 +13,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libfusionrag.so")
 
-SOURCES = ["fr_api.cpp", "k_rope.hip", "k_scatter.hip", "k_score_simt.hip", "k_score_mfma.hip", "k_score_raw.hip", "k_select.hip", "k_select_large.hip", "k_deviation.hip", "k_decode.hip",
+SOURCES = ["fr_api.cpp", "k_rope.hip", "k_scatter.hip", "k_score_simt.hip", "k_score_mfma.hip", "k_score_raw.hip", "k_select.hip", "k_select_large.hip", "fr_select_static.hip", "k_deviation.hip", "k_decode.hip",
            "k_attn_simt.hip", "k_attn_mfma.hip", "k_gemm.hip"]
 
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",

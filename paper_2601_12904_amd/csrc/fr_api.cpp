@@ -181,6 +181,7 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.store_k = store_copy_bytes ? (void*)(w.base + o_sk) : nullptr;
     w.store_v = store_copy_bytes ? (void*)(w.base + o_sv) : nullptr;
     ctx->has_device = true;
+    (void)select_static_prepare();   // this device's static scratch of fr_select_topk_static (no allocation; failure is reported there)
     *out = ctx;
     return FR_OK;
 }
