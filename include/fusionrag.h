@@ -95,9 +95,10 @@ int64_t fr_workspace_bytes(const fr_ctx* ctx);
  * range: AUTO (default) fixes each row's exponent reference at the maximum over its first 32 visible keys
  * and recomputes, with a running maximum, only the workgroups whose sums overflowed; RUNNING_MAX uses the
  * running maximum everywhere.  Both give the same softmax; the option exists so that tests reach both.
- * FR_OPT_ATTN_SPLIT: AUTO (default) lets two workgroups share the key range of every (row tile, KV head) when
- * there are too few of those to fill the chip (few recomputed rows, e.g. the offline stage of eq. 10); OFF / ON
- * force one or the other.  Same results up to fp32 summation order.
+ * FR_OPT_ATTN_SPLIT: AUTO (default) deals the key range of every (row tile, KV head) to two or more workgroups when
+ * there are too few of those to fill the chip (few recomputed rows, e.g. question-only prefill or the offline stage of
+ * eq. 10); OFF: never; ON: two workgroups each whenever the partial results fit the workspace.  Same results up to fp32
+ * summation order.
  * FR_OPT_DECODE_KERNEL: AUTO (default) lets fr_decode_attn form the logits on the matrix cores where it can (bf16,
  * head_dim 128); GENERIC forces the all-vector-ALU kernel that every other shape uses (so that tests reach both).
  * FR_OPT_GEMM_TILE: output features per workgroup of the projection kernels, 0 (default: 256 where the feature count

@@ -140,6 +140,12 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     const size_t o_cid = take((size_t)max_tokens * 4);
     const size_t o_sel = take(select_workspace_bytes());
     const size_t o_qsum = take(score_raw_workspace_bytes(s));
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, ctx->device) != hipSuccess) {
+        delete ctx;
+        return FR_ERR_DEVICE;
+    }
+    w.n_cu = prop.multiProcessorCount;
     w.attn_flags_elems = (size_t)(max_tokens / 32 + 1) * s.Hkv;   // one per (row tile of >= 32 rows, KV head)
     const size_t o_flags = take(w.attn_flags_elems * 4);
     w.kv_images_bytes = (s.dtype == FR_BF16 && s.d == 128) ? (size_t)((max_tokens + 63) / 64) * s.Hkv * 36864 : 0;
@@ -527,18 +533,18 @@ static fr_status prefill_attn_impl(fr_ctx* ctx, const void* q_rows, const int32_
         return fail(ctx, FR_ERR_INVALID_ARG, "q_index / lse_out must be 4-byte aligned");
     if ((st = need_device(ctx)) != FR_OK) return st;
     hipStream_t hs = (hipStream_t)stream;
-    const int32_t* inv = nullptr;
-    if (k_new) {
-        hipError_t e = launch_inv_index(q_index, R, L, ctx->ws.inv_index, hs);
-        if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
-        inv = ctx->ws.inv_index;
-    }
     if (writeback && !k_new) return fail(ctx, FR_ERR_INVALID_ARG, "the write-back needs k_new / v_new");
     hipError_t e;
-    if (attn_mfma_supported(s)) {
-        e = launch_attn_mfma(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, ctx->ws,
+    if (attn_mfma_supported(s)) {   // (the tiled path finds the fresh rows of a key tile while it packs the tile)
+        e = launch_attn_mfma(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, out, lse_out, ctx->ws,
                              ctx->attn_softmax_mode, ctx->attn_split_mode, nullptr, &ctx->attn_timer, writeback, hs);
     } else {
+        const int32_t* inv = nullptr;   // position -> fresh row map
+        if (k_new) {
+            e = launch_inv_index(q_index, R, L, ctx->ws.inv_index, hs);
+            if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
+            inv = ctx->ws.inv_index;
+        }
         e = launch_attn_simt(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, hs);
         if (e == hipSuccess && writeback)   // the generic kernel has no packing pass to fuse it into
             e = launch_kv_scatter(s, k_new, v_new, q_index, R, const_cast<void*>(k_cache), const_cast<void*>(v_cache), hs);
@@ -611,9 +617,10 @@ fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const i
     if (R == 0) return FR_OK;
     if ((st = need_device(ctx)) != FR_OK) return st;
     hipStream_t hs = (hipStream_t)stream;
-    hipError_t e = launch_inv_index(q_index, R, L, ctx->ws.inv_index, hs);
-    if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
+    hipError_t e = hipSuccess;
     if (!attn_mfma_supported(s)) {   // no tiled kernel for this shape: gathered keys and values, generic kernel
+        e = launch_inv_index(q_index, R, L, ctx->ws.inv_index, hs);
+        if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
         if ((st = gather_from_store(ctx, k_store, v_store, sh.ct, chunk_store_row0, dl, L, hs)) != FR_OK) return st;
         e = launch_attn_simt(s, q_rows, q_index, R, ctx->ws.store_k, ctx->ws.store_v, L, k_new, v_new, ctx->ws.inv_index, out,
                              lse_out, hs);
@@ -623,7 +630,7 @@ fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const i
     e = launch_rope_table(s, dl, n_chunks, ctx->ws.rope_table, hs);
     if (e != hipSuccess) return hip_fail(ctx, "rope table launch", e);
     sh.table = ctx->ws.rope_table;
-    e = launch_attn_mfma(s, q_rows, q_index, R, k_store, v_store, L, k_new, v_new, ctx->ws.inv_index, out, lse_out, ctx->ws,
+    e = launch_attn_mfma(s, q_rows, q_index, R, k_store, v_store, L, k_new, v_new, out, lse_out, ctx->ws,
                          ctx->attn_softmax_mode, ctx->attn_split_mode, &sh, &ctx->attn_timer, false, hs);
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
     return FR_OK;
@@ -632,7 +639,7 @@ fr_status fr_sparse_prefill_attn_shared(fr_ctx* ctx, const void* q_rows, const i
 // Scratch of one query of a batch inside the caller's workspace, every part 256-byte aligned.
 namespace {
 struct BatchScratch {
-    size_t inv, srow, cid, table, images, flags, end;
+    size_t srow, cid, table, images, flags, end;
     size_t images_bytes, flags_elems;
 };
 BatchScratch batch_scratch(const Shape& s, int64_t L, int64_t R, size_t base) {
@@ -643,7 +650,6 @@ BatchScratch batch_scratch(const Shape& s, int64_t L, int64_t R, size_t base) {
         off += round_up(bytes, 256);
         return o;
     };
-    b.inv = take((size_t)L * 4);
     b.srow = take((size_t)L * 4);
     b.cid = take((size_t)L * 4);
     b.table = take((size_t)FR_MAX_CHUNKS * (s.d / 2) * sizeof(float2));
@@ -729,13 +735,9 @@ fr_status fr_sparse_prefill_attn_shared_batch(fr_ctx* ctx, const fr_shared_query
             SharedBatchQuery& w = work[i];
             const BatchScratch b = batch_scratch(s, w.L, w.R, off);
             off = b.end;
-            int32_t* inv = reinterpret_cast<int32_t*>(base + b.inv);
             float2* table = reinterpret_cast<float2*>(base + b.table);
-            hipError_t e = launch_inv_index(w.q_index, w.R, w.L, inv, hs);
-            if (e != hipSuccess) return hip_fail(ctx, "index map launch", e);
-            e = launch_rope_table(s, deltas[i], w.shared.ct.n, table, hs);
+            hipError_t e = launch_rope_table(s, deltas[i], w.shared.ct.n, table, hs);
             if (e != hipSuccess) return hip_fail(ctx, "rope table launch", e);
-            w.inv = inv;
             w.shared.table = table;
             w.store_row_map = reinterpret_cast<int32_t*>(base + b.srow);
             w.chunk_id_map = reinterpret_cast<int32_t*>(base + b.cid);

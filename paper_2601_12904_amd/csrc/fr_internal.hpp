@@ -46,16 +46,17 @@ struct Workspace {
     int32_t* chunk_id_map = nullptr;    // [max_tokens] prompt position -> chunk
     float* qsum = nullptr;              // [Hkv][d] question queries summed per KV head (raw scores), then partial sums
     uint32_t* select_tmp = nullptr; // state, histogram, per-wave counts and candidate list of the selection kernels
-    int32_t* attn_flags = nullptr;  // per attention workgroup: 1 = redo with a running maximum
+    int32_t* attn_flags = nullptr;  // per (row tile, KV head) of an attention launch: 1 = redo with a running maximum
+    size_t attn_flags_elems = 0;
+    int n_cu = 0;                   // compute units of the device
     void* store_k = nullptr;        // shapes without a tiled path: a query's keys / values gathered from a shared
     void* store_v = nullptr;        // chunk store ([max_tokens, Hkv, d] each), for the generic kernels
     float* gemm_partials = nullptr; // partial sums of the GEMM tiles that are split along K
     size_t gemm_partials_bytes = 0;
-    size_t attn_flags_elems = 0;
     float2* rope_rows = nullptr;    // [max_tokens][d/2] (cos, sin) of the recomputed rows' positions
     float* decode_partials = nullptr;    // [DECODE_MAX_UNITS][Hq][d + 2] partial softmax results of fr_decode_attn
     float2* decode_rot = nullptr;        // [DECODE_MAX_UNITS][d/2] (cos, sin) of the segments' position shifts
-    float* attn_partials = nullptr;      // partial results of the split attention launch
+    float* attn_partials = nullptr;      // partial results of an attention launch whose items are computed in parts
     size_t attn_partials_bytes = 0;
     unsigned char* kv_images = nullptr;  // [Hkv][ceil(max_tokens / 64)] LDS-ready K / V^T tile images, 32 KB each
     size_t kv_images_bytes = 0;
@@ -172,18 +173,17 @@ hipError_t launch_attn_simt(const Shape& s, const void* q_rows, const int32_t* q
 bool attn_mfma_supported(const Shape& s);
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R,
                             const void* k_cache, const void* v_cache, int64_t L, const void* k_new,
-                            const void* v_new, const int32_t* inv, void* out, float* lse,
+                            const void* v_new, void* out, float* lse,
                             const Workspace& ws, int softmax_mode, int split_mode, const struct SharedStoreArgs* shared,
                             struct KernelTimer* timer, bool writeback, hipStream_t st);
 // Several queries over one shared chunk store in one attention launch (Sec. 4.3).  Each query brings its scratch:
-// inverse index map, prompt maps, rotation table, tile images and recompute flags (sizes: attn_mfma_images_bytes,
-// attn_mfma_flags_elems).  R > 0 for every query.
+// prompt maps, rotation table, tile images and recompute flags (sizes: attn_mfma_images_bytes, attn_mfma_flags_elems).
+// R > 0 for every query.
 constexpr int ATTN_MAX_BATCH = 16;
 struct SharedBatchQuery {
     const void* q_rows; const int32_t* q_index; int R; int64_t L;
     const void* k_new; const void* v_new; void* out; float* lse;
     SharedStoreArgs shared;          // chunk table, store rows (host), rotation table (device)
-    const int32_t* inv;              // device [L], already built
     int32_t* store_row_map; int32_t* chunk_id_map;   // device [L] each
     unsigned char* images; size_t images_bytes;
     int32_t* flags; size_t flags_elems;
@@ -192,12 +192,13 @@ size_t attn_mfma_images_bytes(const Shape& s, int64_t L);
 size_t attn_mfma_flags_elems(const Shape& s, int64_t R);
 hipError_t launch_attn_mfma_shared_batch(const Shape& s, int n, const SharedBatchQuery* qs, const void* k_store,
                                          const void* v_store, int softmax_mode, struct KernelTimer* timer, hipStream_t st);
-// The attention launch splits the key range in two on its own up to ATTN_SPLIT_AUTO_ITEMS (row tile, KV head)
-// items (about 1.5 x the 256 CUs: beyond that the items alone keep the chip busy and the partial results' traffic
-// costs more than the better balance gains), and on request (FR_ATTN_SPLIT_ON) up to ATTN_SPLIT_MAX_ITEMS, which
-// sizes the partial-result buffer.
+// A one-query attention launch with few (row tile, KV head) items deals every item's key tiles to several workgroups
+// (parts), on its own up to ATTN_SPLIT_AUTO_ITEMS items (beyond that the items alone keep the chip busy and the partial
+// results' traffic costs more than the better balance gains): two parts, more (up to ATTN_MAX_PARTS) while that still
+// leaves at most one piece per compute unit.  FR_ATTN_SPLIT_ON asks for two parts at any size the partial-result buffer
+// takes.
 constexpr int ATTN_SPLIT_AUTO_ITEMS = 400;
-constexpr int ATTN_SPLIT_MAX_ITEMS = 768;
+constexpr int ATTN_MAX_PARTS = 4;
 size_t attn_mfma_partials_bytes(const Shape& s, int64_t max_tokens);
 
 void launch_gemm_set_tile(int features_per_workgroup);   // 0 = choose, 128, 256

@@ -90,7 +90,6 @@ struct Geometry {
     static constexpr int TRW = 64 / G;   // token rows per wave
     static constexpr int TR = 4 * TRW;   // token rows per workgroup
     int g, tile, row0;
-    int split, item;   // which part of the key range this workgroup walks; ordinal of (row tile, KV head)
     int x, h, wave;
     int col_row[2], col_head[2], col_pos[2];
     int wp_max;    // no key beyond it is visible to any row of this wave
@@ -99,20 +98,18 @@ struct Geometry {
 
     // ordinal counts the row tiles of a query from the longest one; ordinal < n_row_tiles
     __device__ __forceinline__ void init(const int32_t* __restrict__ q_index, int R, int Hkv, int n_row_tiles,
-                                         int g_, int split_, int ordinal) {
-        init_rows(Hkv, n_row_tiles, g_, split_, ordinal);
+                                         int g_, int ordinal) {
+        init_rows(Hkv, n_row_tiles, g_, ordinal);
         init_positions(q_index, R);
     }
     // The part that does not read the Q index: which rows and heads the lane's two columns are.
-    __device__ __forceinline__ void init_rows(int Hkv, int n_row_tiles, int g_, int split_, int ordinal) {
+    __device__ __forceinline__ void init_rows(int Hkv, int n_row_tiles, int g_, int ordinal) {
         const int tid = threadIdx.x, lane = tid & 63;
         wave = tid >> 6;
         x = lane & 31;
         h = lane >> 5;
         g = g_;
-        split = split_;
         tile = n_row_tiles - 1 - ordinal;                   // longest tiles first
-        item = ordinal * Hkv + g;
         row0 = tile * TR;
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
@@ -133,6 +130,38 @@ struct Geometry {
         n_plain = min((p_first + 1) / KT, n_kt - 1);
     }
 };
+
+// ---- which keys of a 64-key tile are fresh ---------------------------------------------------------------
+// fresh[t] = row r of k_new / v_new that holds the recomputed entry of position 64 kt + t (q_index[r] == that
+// position), else -1.  The Q index is strictly ascending: wave 0 finds the first row at or behind the tile's first
+// position by a 64-ary search (every round probes 64 evenly spaced rows at once: two dependent loads for up to 4096
+// rows, where a binary search needs twelve), then the at most 64 rows that can fall into the tile are read in one go.
+// All 256 threads call it; `fresh` is LDS, valid after the call's closing barrier.
+__device__ __forceinline__ void tile_fresh_rows(const int32_t* __restrict__ q_index, int R, int kt, int32_t* fresh) {
+    const int tid = threadIdx.x;
+    if (tid < KT) fresh[tid] = -1;
+    __syncthreads();
+    if (tid < 64) {
+        const int target = kt * KT;
+        int lo = 0, hi = R;   // the first row with q_index[row] >= target lies in [lo, hi]
+        while (lo < hi) {
+            const int step = (hi - lo + 63) >> 6;
+            const int probe = lo + tid * step;
+            const bool below = probe < hi && q_index[probe] < target;
+            const int cnt = __popcll(__ballot(below));   // probes are ascending, so the ones below the target come first
+            if (cnt == 0) { hi = lo; break; }
+            const int last_below = lo + (cnt - 1) * step;
+            hi = min(hi, last_below + step);
+            lo = last_below + 1;
+        }
+        const int row = lo + tid;
+        if (row < R) {
+            const int pos = q_index[row];
+            if (pos < target + KT) fresh[pos - target] = row;
+        }
+    }
+    __syncthreads();
+}
 
 // ---- packing pre-pass: grid (key tiles, KV heads) ---------------------------------------------------------
 // Second half of both packing kernels: the thread's 4 key vectors and 4 value vectors (st_vec = 16-byte vector
@@ -175,30 +204,29 @@ template <bool WRITEBACK>
 __global__ __launch_bounds__(256) void pack_kv_images_kernel(const __bf16* k_cache, const __bf16* v_cache, int L,
                                                              const __bf16* __restrict__ k_new,
                                                              const __bf16* __restrict__ v_new,
-                                                             const int32_t* __restrict__ inv, int Hkv, int n_img_tiles,
-                                                             unsigned char* __restrict__ images) {
+                                                             const int32_t* __restrict__ q_index, int R, int Hkv,
+                                                             int n_img_tiles, unsigned char* __restrict__ images) {
     __shared__ __attribute__((aligned(16))) unsigned char img[IMG_BYTES];
+    __shared__ int32_t fresh[KT];
     const int tid = threadIdx.x, kt = blockIdx.x, g = blockIdx.y;
     const int st_vec = tid & 15;   // 16-byte vector (8 dims) within a 256-byte head row
     const int st_key = tid >> 4;   // K: keys st_key + 16 i;  V: keys 4 st_key + i
+    const bool have_new = k_new != nullptr;   // else the cache already holds the fresh rows
+    if (have_new) tile_fresh_rows(q_index, R, kt, fresh);
     u32x4 kreg[4], vreg[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {   // a key past the end is clamped: it lies beyond every row's position
-        const int jk = min(kt * KT + st_key + 16 * i, L - 1);
-        const int jv = min(kt * KT + 4 * st_key + i, L - 1);
-        const __bf16* pk = k_cache + ((size_t)jk * Hkv + g) * D;
-        const __bf16* pv = v_cache + ((size_t)jv * Hkv + g) * D;
-        if (inv != nullptr) {
-            const int rk = inv[jk], rv = inv[jv];
-            if (rk >= 0) pk = k_new + ((size_t)rk * Hkv + g) * D;
-            if (rv >= 0) pv = v_new + ((size_t)rv * Hkv + g) * D;
-        }
+        const int tk = st_key + 16 * i, tv = 4 * st_key + i;
+        const int jk = min(kt * KT + tk, L - 1), jv = min(kt * KT + tv, L - 1);
+        const int rk = have_new ? fresh[jk - kt * KT] : -1, rv = have_new ? fresh[jv - kt * KT] : -1;
+        const __bf16* pk = rk >= 0 ? k_new + ((size_t)rk * Hkv + g) * D : k_cache + ((size_t)jk * Hkv + g) * D;
+        const __bf16* pv = rv >= 0 ? v_new + ((size_t)rv * Hkv + g) * D : v_cache + ((size_t)jv * Hkv + g) * D;
         kreg[i] = *reinterpret_cast<const u32x4*>(pk + 8 * st_vec);
         vreg[i] = *reinterpret_cast<const u32x4*>(pv + 8 * st_vec);
-        if (WRITEBACK && inv != nullptr) {   // (a clamped key past the end repeats key L-1: the same bytes again)
-            if (inv[jk] >= 0)
+        if (WRITEBACK) {   // (a clamped key past the end repeats key L-1: the same bytes again)
+            if (rk >= 0)
                 *reinterpret_cast<u32x4*>(const_cast<__bf16*>(k_cache) + ((size_t)jk * Hkv + g) * D + 8 * st_vec) = kreg[i];
-            if (inv[jv] >= 0)
+            if (rv >= 0)
                 *reinterpret_cast<u32x4*>(const_cast<__bf16*>(v_cache) + ((size_t)jv * Hkv + g) * D + 8 * st_vec) = vreg[i];
         }
     }
@@ -235,19 +263,21 @@ __global__ __launch_bounds__(256) void pack_kv_images_shared_kernel(const __bf16
                                                                     const float2* __restrict__ table,
                                                                     int L, const __bf16* __restrict__ k_new,
                                                                     const __bf16* __restrict__ v_new,
-                                                                    const int32_t* __restrict__ inv, int Hkv,
+                                                                    const int32_t* __restrict__ q_index, int R, int Hkv,
                                                                     int n_img_tiles, unsigned char* __restrict__ images) {
     __shared__ __attribute__((aligned(16))) unsigned char img[IMG_BYTES];
+    __shared__ int32_t fresh[KT];
     const int tid = threadIdx.x, kt = blockIdx.x, g = blockIdx.y;
     const int st_vec = tid & 15, st_key = tid >> 4;
     const u32x4 zero = {0u, 0u, 0u, 0u};
+    tile_fresh_rows(q_index, R, kt, fresh);
     int jk[4], jv[4], rk[4], rv[4], sk[4], sv[4], ck[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {   // the maps first, all at once: no load below depends on more than one of them
         jk[i] = min(kt * KT + st_key + 16 * i, L - 1);
         jv[i] = min(kt * KT + 4 * st_key + i, L - 1);
-        rk[i] = inv[jk[i]];
-        rv[i] = inv[jv[i]];
+        rk[i] = fresh[jk[i] - kt * KT];
+        rv[i] = fresh[jv[i] - kt * KT];
         sk[i] = store_row[jk[i]];
         sv[i] = store_row[jv[i]];
         ck[i] = chunk_id[jk[i]];
@@ -493,20 +523,20 @@ __device__ __forceinline__ void store_output(const Geometry<G>& ge, f32x16 (&o)[
     }
 }
 
-// Partial result of one workgroup when the key range of a (row tile, KV head) is split over NS workgroups: the
-// 128 output accumulators, the two sums and the two exponent references of every lane, register-major
-// (float r of thread t at [r * 256 + t]: every store and load is one coalesced 1 KB line per wave).
+// Partial result of one part of an item: the 128 output accumulators, the two sums and the two exponent references
+// of every lane, register-major (float r of thread t at [r * 256 + t]: every store and load is one coalesced 1 KB
+// line per wave).  Part p of item (ordinal, KV head g) lives at ((ordinal * n_parts + p) * Hkv + g) * PART_FLOATS.
 constexpr int PART_REGS = 132;
 constexpr int PART_FLOATS = PART_REGS * 256;
 
 // One launch serves up to ATTN_MAX_BATCH queries with their own rows, index sets, tile images and outputs (Sec. 4.3:
 // queries of a batch share nothing but the chunk store the images were built from).  The table travels as a kernel
-// argument.  blockIdx.x = ((query * max_row_tiles + ordinal) * NS + part) * Hkv + KV head: consecutive blocks land on
-// different XCDs, so with 8 KV heads each XCD's L2 serves the images of one head; the queries follow one another, each
-// with its row tiles longest first, so that the short tiles at the end of one query run beside the long ones of the
-// next and no more than about two queries' images are in use at a time (interleaving the queries was measured: their
-// images then compete for the caches and the batch gains nothing over one launch per query).  A query with fewer row
-// tiles than the longest one leaves its surplus blocks empty.
+// argument.  blockIdx.x = (query * max_row_tiles + ordinal) * Hkv + KV head (launches without parts): consecutive blocks land
+// on different XCDs, so with 8 KV heads each XCD's L2 serves the images of one head; the queries follow one another,
+// each with its row tiles longest first, so that the short tiles at the end of one query run beside the long ones of
+// the next and no more than about two queries' images are in use at a time (interleaving the queries was measured:
+// their images then compete for the caches and the batch gains nothing over one launch per query).  A query with fewer
+// row tiles than the longest one leaves its surplus blocks empty.
 struct AttnQuery {
     const __bf16* q_rows;
     const int32_t* q_index;
@@ -521,47 +551,130 @@ struct AttnBatch {
     int n, max_row_tiles;
 };
 struct BlockWork {
-    int g, split, ordinal, query;
-    __device__ __forceinline__ void init(int max_row_tiles, int n_split, int Hkv) {
+    int g, ordinal, query;
+    __device__ __forceinline__ void init(int max_row_tiles, int Hkv) {
         int t = (int)blockIdx.x;
         g = t % Hkv; t /= Hkv;
-        split = t % n_split; t /= n_split;
         ordinal = t % max_row_tiles;
         query = t / max_row_tiles;
     }
 };
 
-// ---- fast kernel ---------------------------------------------------------------------------------
-// grid.x = n_row_tiles * Hkv * NS.  Dynamic LDS: the larger of the K/V rings and the epilogue's staging.
-// NS = 1: the workgroup walks all key tiles of its rows and writes the output.  NS = 2 (few row tiles, CUs
-// would idle): it walks one half of them and leaves a partial result; every part uses the same exponent
-// reference (each derives it from the first 32 keys), so the parts simply add up in attn_combine_kernel.
-template <int G, int NS>
-__global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch batch, float* __restrict__ partials,
-                                                             int Hq, int Hkv, float scale_log2e) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    Rings& rg = *reinterpret_cast<Rings*>(smem_raw);
-    BlockWork bw;
-    bw.init(batch.max_row_tiles, NS, Hkv);
-    const AttnQuery& aq = batch.q[bw.query];
-    const int n_row_tiles = aq.n_row_tiles;
-    if (bw.ordinal >= n_row_tiles) return;
+// ---- classic online softmax (running maximum) for one (row tile, KV head): the whole key range, one workgroup.
+//      Runs where the fixed exponent reference overflowed, and everywhere under FR_ATTN_SOFTMAX_RUNNING_MAX.
+//      `smem` holds max(IMG_BYTES, EPILOGUE_LDS) bytes; every thread of the workgroup calls it. ------------------------
+template <int G>
+__device__ __forceinline__ void running_max_item(const AttnQuery& aq, int g, int ordinal, int Hq, int Hkv,
+                                                 float scale_log2e, unsigned char* smem) {
     const __bf16* __restrict__ q_rows = aq.q_rows;
-    const int32_t* __restrict__ q_index = aq.q_index;
-    const unsigned char* __restrict__ images = aq.images;
-    __bf16* __restrict__ out = aq.out;
-    float* __restrict__ lse_out = aq.lse;
-    int32_t* __restrict__ redo_flags = aq.flags;
+    const int R = aq.R, n_img_tiles = aq.n_img_tiles;
+    unsigned char* k_img = smem;
+    unsigned char* v_img = smem + K_IMG_BYTES;
+    Geometry<G> ge;
+    ge.init(aq.q_index, R, Hkv, aq.n_row_tiles, g, ordinal);
+    const int h = ge.h;
+    FragOffsets fo;
+    fo.init(ge.x, h);
+    bf16x8 qf[2][8];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const __bf16* qp = q_rows + ((size_t)min(ge.col_row[nb], R - 1) * Hq + ge.col_head[nb]) * D + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    }
+    f32x16 o[4][2];
+#pragma unroll
+    for (int md = 0; md < 4; ++md)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
+    float lsum[2] = {0.f, 0.f};
+    float m2[2] = {NEG_BIG, NEG_BIG};
+    ImageStager sg;
+    sg.init(aq.images, ge.g, n_img_tiles);
+    for (int kt = 0; kt < ge.n_kt; ++kt) {
+        sg.load(kt);
+        __syncthreads();
+        sg.write(k_img);
+        __syncthreads();
+        if (kt * KT > ge.wp_max) continue;   // wave-uniform; the barriers stay outside
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            f32x16 s[2];
+            qk_half(k_img, mb, qf, fo, s);
+            mask_half<true>(s, ge.col_pos, kt * KT + 32 * mb, h);
+            bf16x8 pf[2][2];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                float t = s[nb][0];
+#pragma unroll
+                for (int v = 1; v < 16; ++v) t = fmaxf(t, s[nb][v]);
+                t = fmaxf(t, __shfl_xor(t, 32));
+                const float m_new = fmaxf(m2[nb], t * scale_log2e);
+                const float alpha = __builtin_amdgcn_exp2f(m2[nb] - m_new);
+                m2[nb] = m_new;
+                float psum = 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nb][v], scale_log2e, -m_new));
+                    psum += p;
+                    pf[nb][v >> 3][v & 7] = (__bf16)p;
+                }
+                lsum[nb] = lsum[nb] * alpha + psum;
+#pragma unroll
+                for (int md = 0; md < 4; ++md)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[md][nb][v] *= alpha;
+            }
+            pv_half(v_img, mb, pf, fo, o);
+        }
+    }
+    float l[2];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) l[nb] = lsum[nb] + __shfl_xor(lsum[nb], 32);
+    __syncthreads();
+    store_output<G>(ge, o, l, m2, R, Hq, smem, aq.out, aq.lse);
+}
+
+// Overflow check of a finished item: with a fixed reference a runaway logit shows up as inf / nan in the sums.
+// Returns (workgroup-uniform) whether any column of the workgroup is affected; l = the columns' softmax sums.
+__device__ __forceinline__ int sums_overflowed(const f32x16 (&o)[4][2], const float (&lsum)[2], float (&l)[2]) {
+    bool bad = false;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        l[nb] = lsum[nb] + __shfl_xor(lsum[nb], 32);
+        float chk = l[nb];
+#pragma unroll
+        for (int md = 0; md < 4; ++md)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) chk += fabsf(o[md][nb][v]);
+        bad = bad || !(chk < INFINITY) || !(l[nb] > 0.f);
+    }
+    return __syncthreads_or(bad ? 1 : 0);   // also: every wave is done with the rings
+}
+
+// ---- fast path: key tiles [kb, ke) of one (row tile, KV head) ---------------------------------------------
+// part < 0: the piece is the whole item; the workgroup finishes it: overflow check, then either the output or the
+// item's flag (the kernel that follows recomputes flagged items with a running maximum).  part >= 0: the piece is
+// share `part` of `n_parts` of the item's key tiles; it leaves its partial sums, and attn_combine_kernel finishes
+// the item.  Every part uses the same exponent reference (each derives it from keys 0..31), so the parts simply add up.
+template <int G>
+__device__ __forceinline__ void process_piece(const AttnQuery& aq, int g, int ordinal, int part, int n_parts,
+                                              float* __restrict__ partials, int Hq, int Hkv, float scale_log2e,
+                                              unsigned char* smem_raw) {
+    Rings& rg = *reinterpret_cast<Rings*>(smem_raw);
+    const __bf16* __restrict__ q_rows = aq.q_rows;
     const int R = aq.R, n_img_tiles = aq.n_img_tiles;
     // ---- prologue.  Everything that does not depend on the Q index is requested first (the query fragments, and K
     //      image 0 for the exponent reference), then the Q index itself, so that the three memory round trips of the
     //      prologue overlap instead of following one another. ------------------------------------------------------
     Geometry<G> ge;
-    ge.init_rows(Hkv, n_row_tiles, bw.g, bw.split, bw.ordinal);
+    ge.init_rows(Hkv, aq.n_row_tiles, g, ordinal);
     const int x = ge.x, h = ge.h;
     FragOffsets fo;
     fo.init(x, h);
-    const unsigned char* head_images = images + (size_t)ge.g * n_img_tiles * IMG_BYTES;
+    const unsigned char* head_images = aq.images + (size_t)ge.g * n_img_tiles * IMG_BYTES;
     const int wave = __builtin_amdgcn_readfirstlane(ge.wave), lane = threadIdx.x & 63;
     dma_image(head_images, rg.k[2], wave, lane);   // K image 0 into ring slot 2: the exponent reference comes from it
 
@@ -573,14 +686,15 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
     }
-    ge.init_positions(q_index, R);
-    // this workgroup's key tiles [kb, ke)
-    const int per_split = (ge.n_kt + NS - 1) / NS;
-    const int kb = ge.split * per_split, ke = min(ge.n_kt, kb + per_split);
-    float* part = (NS > 1) ? partials + ((size_t)ge.item * NS + ge.split) * PART_FLOATS + threadIdx.x : nullptr;
-    if (NS > 1 && kb >= ke) {   // fewer key tiles than parts: this one adds nothing
-        for (int r = 0; r < PART_REGS; ++r) part[r * 256] = 0.f;
-        return;                 // (the hardware waits for the outstanding copy before it retires the wave)
+    ge.init_positions(aq.q_index, R);
+    const int n_kt = ge.n_kt;
+    // this piece's key tiles [kb, ke): shares of ceil(n_kt / n_parts) tiles, so part 0 is never empty
+    const int per_part = part < 0 ? n_kt : (n_kt + n_parts - 1) / n_parts;
+    const int kb = part < 0 ? 0 : part * per_part, ke = min(n_kt, kb + per_part);
+    float* part_dst = part < 0 ? nullptr : partials + (((size_t)ordinal * n_parts + part) * Hkv + g) * PART_FLOATS + threadIdx.x;
+    if (kb >= ke) {   // fewer key tiles than parts: this one adds nothing
+        for (int r = 0; r < PART_REGS; ++r) part_dst[r * 256] = 0.f;
+        return;       // (the hardware waits for the outstanding copy before it retires the wave)
     }
     f32x16 o[4][2];
 #pragma unroll
@@ -592,7 +706,6 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
     float lsum[2] = {0.f, 0.f};
 
     // K images kb and kb + 1 and V image kb land in LDS
-    const int n_kt = ge.n_kt;
     const unsigned char* first_image = head_images + (size_t)kb * IMG_BYTES;
     dma_image(first_image, rg.k[0], wave, lane);
     dma_image(first_image + K_IMG_BYTES, rg.vt[0], wave, lane);
@@ -619,8 +732,8 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
         t = fmaxf(t, __shfl_xor(t, 32));   // key 0 (held by the h = 0 lane) is visible to every row
         mref[nb] = t * scale_log2e;
     }
-    __syncthreads();                                      // ring slot 2 is free again before the loop copies into it
-    if (NS > 1 && kb > 0) qk_half(rg.k[0], 0, qf, fo, s_a);   // logits of this part's first 32 keys (else: those above)
+    __syncthreads();                                // ring slot 2 is free again before the loop copies into it
+    if (kb > 0) qk_half(rg.k[0], 0, qf, fo, s_a);   // logits of this part's first 32 keys (else: those above)
     bf16x8 pf_a[2][2], pf_b[2][2];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
@@ -672,166 +785,112 @@ __global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch bat
     }
     pv_half(rg.vt[k2], 1, pf_b, fo, o);   // the last half: V image ke-1 now sits in slot k2
 
-    if (NS > 1) {   // leave the partial result; attn_combine_kernel adds the parts, checks and stores
+    if (part >= 0) {   // leave the partial result; attn_combine_kernel adds the parts, checks and stores
+        float* dst = part_dst;
 #pragma unroll
         for (int md = 0; md < 4; ++md)
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) part[((2 * md + nb) * 16 + v) * 256] = o[md][nb][v];
+                for (int v = 0; v < 16; ++v) dst[((2 * md + nb) * 16 + v) * 256] = o[md][nb][v];
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
-            part[(128 + nb) * 256] = lsum[nb];
-            part[(130 + nb) * 256] = mref[nb];
+            dst[(128 + nb) * 256] = lsum[nb];
+            dst[(130 + nb) * 256] = mref[nb];
         }
         return;
     }
-
-    // overflow check: with a fixed reference a runaway logit shows up as inf / nan in the sums
     float l[2];
-    bool bad = false;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        l[nb] = lsum[nb] + __shfl_xor(lsum[nb], 32);
-        float chk = l[nb];
-#pragma unroll
-        for (int md = 0; md < 4; ++md)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) chk += fabsf(o[md][nb][v]);
-        bad = bad || !(chk < INFINITY) || !(l[nb] > 0.f);
-    }
-    const int any_bad = __syncthreads_or(bad ? 1 : 0);   // also: every wave is done with the rings
-    if (threadIdx.x == 0) redo_flags[ge.item] = any_bad;
+    const int any_bad = sums_overflowed(o, lsum, l);
+    if (threadIdx.x == 0) aq.flags[ordinal * Hkv + g] = any_bad;   // raised: the item is recomputed with a running maximum
     if (any_bad) return;
-    store_output<G>(ge, o, l, mref, R, Hq, smem_raw, out, lse_out);
+    store_output<G>(ge, o, l, mref, R, Hq, smem_raw, aq.out, aq.lse);
 }
 
-// ---- combine: adds the two parts of every (row tile, KV head), then checks and stores like the fast kernel's
-//      own epilogue.  grid.x = n_row_tiles * Hkv (the ordinals of the unsplit launch), LDS = the epilogue's staging.
+// blockIdx.x = ((query * max_row_tiles + ordinal) * n_parts + part) * Hkv + KV head.  n_parts = 1: every item whole.
+// n_parts > 1 (one query, few items: the chip would idle behind the longest ones): the key tiles of every item are
+// dealt to n_parts workgroups in equal consecutive shares; items are launched longest first, so the pieces are too.
+// Dynamic LDS: the larger of the K/V rings and the epilogue's staging.
 template <int G>
-__global__ __launch_bounds__(256) void attn_combine_kernel(const int32_t* __restrict__ q_index, int R,
-                                                           const float* __restrict__ partials, __bf16* __restrict__ out,
-                                                           float* __restrict__ lse_out, int32_t* __restrict__ redo_flags,
-                                                           int Hq, int Hkv, int n_row_tiles) {
+__global__ __launch_bounds__(256) void attn_fixed_ref_kernel(const AttnBatch batch, float* __restrict__ partials, int n_parts,
+                                                             int Hq, int Hkv, float scale_log2e) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    Geometry<G> ge;
-    ge.init(q_index, R, Hkv, n_row_tiles, (int)blockIdx.x % Hkv, 0, (int)blockIdx.x / Hkv);
-    const float* p0 = partials + (size_t)ge.item * 2 * PART_FLOATS + threadIdx.x;
-    const float* p1 = p0 + PART_FLOATS;
-    f32x16 o[4][2];
-#pragma unroll
-    for (int md = 0; md < 4; ++md)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = (2 * md + nb) * 16 + v;
-                o[md][nb][v] = p0[r * 256] + p1[r * 256];
-            }
-    float l[2], mref[2];
-    bool bad = false;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const float lsum = p0[(128 + nb) * 256] + p1[(128 + nb) * 256];
-        mref[nb] = p0[(130 + nb) * 256];
-        l[nb] = lsum + __shfl_xor(lsum, 32);
-        float chk = l[nb];
+    int t = (int)blockIdx.x;
+    const int g = t % Hkv; t /= Hkv;
+    const int part = t % n_parts; t /= n_parts;
+    const int ordinal = t % batch.max_row_tiles, query = t / batch.max_row_tiles;
+    const AttnQuery& aq = batch.q[query];
+    if (ordinal >= aq.n_row_tiles) return;
+    process_piece<G>(aq, g, ordinal, n_parts > 1 ? part : -1, n_parts, partials, Hq, Hkv, scale_log2e, smem_raw);
+}
+
+// ---- combine: adds the parts of every item, then checks and stores like the fast path's own epilogue; on overflow
+//      the item is recomputed with a running maximum.  grid.x = n_row_tiles * Hkv, LDS = max(epilogue staging, one image).
+template <int G>
+__global__ __launch_bounds__(256, 2) void attn_combine_kernel(const AttnQuery aq, const float* __restrict__ partials,
+                                                              int n_parts, int Hq, int Hkv, float scale_log2e) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    const int g = (int)blockIdx.x % Hkv, ordinal = (int)blockIdx.x / Hkv;
+    {
+        Geometry<G> ge;
+        ge.init(aq.q_index, aq.R, Hkv, aq.n_row_tiles, g, ordinal);
+        const float* p0 = partials + (((size_t)ordinal * n_parts) * Hkv + g) * PART_FLOATS + threadIdx.x;
+        const size_t part_stride = (size_t)Hkv * PART_FLOATS;
+        f32x16 o[4][2];
+        float lsum[2], mref[2];
 #pragma unroll
         for (int md = 0; md < 4; ++md)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) chk += fabsf(o[md][nb][v]);
-        bad = bad || !(chk < INFINITY) || !(l[nb] > 0.f);
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[md][nb][v] = p0[((2 * md + nb) * 16 + v) * 256];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            lsum[nb] = p0[(128 + nb) * 256];
+            mref[nb] = p0[(130 + nb) * 256];   // part 0 is never empty; every part derives the same reference
+        }
+        for (int part = 1; part < n_parts; ++part) {   // 64 loads in flight per lane, then their sums
+            const float* pp = p0 + part * part_stride;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                f32x16 t[2][2];
+#pragma unroll
+                for (int m2 = 0; m2 < 2; ++m2)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) t[m2][nb][v] = pp[((2 * (2 * half + m2) + nb) * 16 + v) * 256];
+#pragma unroll
+                for (int m2 = 0; m2 < 2; ++m2)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) o[2 * half + m2][nb] += t[m2][nb];
+            }
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) lsum[nb] += pp[(128 + nb) * 256];
+        }
+        float l[2];
+        if (!sums_overflowed(o, lsum, l)) {
+            store_output<G>(ge, o, l, mref, aq.R, Hq, smem_raw, aq.out, aq.lse);
+            return;
+        }
     }
-    const int any_bad = __syncthreads_or(bad ? 1 : 0);
-    if (threadIdx.x == 0) redo_flags[blockIdx.x] = any_bad;
-    if (any_bad) return;
-    store_output<G>(ge, o, l, mref, R, Hq, smem_raw, out, lse_out);
+    // the sums overflowed the fixed exponent reference (rare): the item again, with a running maximum
+    __syncthreads();
+    running_max_item<G>(aq, g, ordinal, Hq, Hkv, scale_log2e, smem_raw);
 }
 
-// ---- safe kernel: classic online softmax, runs only where the fast kernel raised its flag ----------
+// ---- the items of a launch without parts with the running maximum: the flagged ones (use_flags), or all of them
+//      (FR_ATTN_SOFTMAX_RUNNING_MAX) ---------------------------------------------------------------------------
 template <int G>
 __global__ __launch_bounds__(256) void attn_running_max_kernel(const AttnBatch batch, int use_flags, int Hq, int Hkv,
                                                                float scale_log2e) {
-    BlockWork bw;
-    bw.init(batch.max_row_tiles, 1, Hkv);
-    const AttnQuery& aq = batch.q[bw.query];
-    const int n_row_tiles = aq.n_row_tiles;
-    if (bw.ordinal >= n_row_tiles) return;
-    if (use_flags && aq.flags[bw.ordinal * Hkv + bw.g] == 0) return;
-    const __bf16* __restrict__ q_rows = aq.q_rows;
-    const int32_t* __restrict__ q_index = aq.q_index;
-    const unsigned char* __restrict__ images = aq.images;
-    __bf16* __restrict__ out = aq.out;
-    float* __restrict__ lse_out = aq.lse;
-    const int R = aq.R, n_img_tiles = aq.n_img_tiles;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    unsigned char* k_img = smem_raw;
-    unsigned char* v_img = smem_raw + K_IMG_BYTES;
-    Geometry<G> ge;
-    ge.init(q_index, R, Hkv, n_row_tiles, bw.g, 0, bw.ordinal);
-    const int x = ge.x, h = ge.h;
-    FragOffsets fo;
-    fo.init(x, h);
-    bf16x8 qf[2][8];
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const __bf16* qp = q_rows + ((size_t)min(ge.col_row[nb], R - 1) * Hq + ge.col_head[nb]) * D + 8 * h;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-    }
-    f32x16 o[4][2];
-#pragma unroll
-    for (int md = 0; md < 4; ++md)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
-    float lsum[2] = {0.f, 0.f};
-    float m2[2] = {NEG_BIG, NEG_BIG};
-    ImageStager sg;
-    sg.init(images, ge.g, n_img_tiles);
-    for (int kt = 0; kt < ge.n_kt; ++kt) {
-        sg.load(kt);
-        __syncthreads();
-        sg.write(k_img);
-        __syncthreads();
-        if (kt * KT > ge.wp_max) continue;   // wave-uniform; the barriers stay outside
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            f32x16 s[2];
-            qk_half(k_img, mb, qf, fo, s);
-            mask_half<true>(s, ge.col_pos, kt * KT + 32 * mb, h);
-            bf16x8 pf[2][2];
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                float t = s[nb][0];
-#pragma unroll
-                for (int v = 1; v < 16; ++v) t = fmaxf(t, s[nb][v]);
-                t = fmaxf(t, __shfl_xor(t, 32));
-                const float m_new = fmaxf(m2[nb], t * scale_log2e);
-                const float alpha = __builtin_amdgcn_exp2f(m2[nb] - m_new);
-                m2[nb] = m_new;
-                float psum = 0.f;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nb][v], scale_log2e, -m_new));
-                    psum += p;
-                    pf[nb][v >> 3][v & 7] = (__bf16)p;
-                }
-                lsum[nb] = lsum[nb] * alpha + psum;
-#pragma unroll
-                for (int md = 0; md < 4; ++md)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) o[md][nb][v] *= alpha;
-            }
-            pv_half(v_img, mb, pf, fo, o);
-        }
-    }
-    float l[2];
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) l[nb] = lsum[nb] + __shfl_xor(lsum[nb], 32);
-    __syncthreads();
-    store_output<G>(ge, o, l, m2, R, Hq, smem_raw, out, lse_out);
+    BlockWork bw;
+    bw.init(batch.max_row_tiles, Hkv);
+    const AttnQuery& aq = batch.q[bw.query];
+    if (bw.ordinal >= aq.n_row_tiles) return;
+    if (use_flags && aq.flags[bw.ordinal * Hkv + bw.g] == 0) return;
+    running_max_item<G>(aq, bw.g, bw.ordinal, Hq, Hkv, scale_log2e, smem_raw);
 }
 
 // Where one query's packing pass leaves its results.
@@ -844,24 +903,22 @@ struct QueryScratch {
     size_t flags_elems;
 };
 
+constexpr size_t LDS_FAST = sizeof(Rings) > EPILOGUE_LDS ? sizeof(Rings) : EPILOGUE_LDS;
+constexpr size_t LDS_SAFE = (size_t)IMG_BYTES > EPILOGUE_LDS ? (size_t)IMG_BYTES : EPILOGUE_LDS;
+
 // Raises the kernels' dynamic LDS limit, once per process (C++ initialises a function-local static exactly once,
 // also when several host threads arrive together).
 template <int G>
 hipError_t set_kernel_attributes() {
     static const hipError_t once = [] {
-        const size_t lds_fast = sizeof(Rings) > EPILOGUE_LDS ? sizeof(Rings) : EPILOGUE_LDS;
-        const size_t lds_safe = (size_t)IMG_BYTES > EPILOGUE_LDS ? (size_t)IMG_BYTES : EPILOGUE_LDS;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 1>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G, 2>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fast);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fixed_ref_kernel<G>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_FAST);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_combine_kernel<G>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)EPILOGUE_LDS);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_SAFE);
         if (e != hipSuccess) return e;
         return hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_running_max_kernel<G>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_safe);
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_SAFE);
     }();
     return once;
 }
@@ -869,9 +926,8 @@ hipError_t set_kernel_attributes() {
 // Packing pass of one query: tile images of its effective K/V into sc.images; fills the query's line of the table.
 template <int G>
 hipError_t pack_query(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
-                      const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
-                      float* lse, const QueryScratch& sc, const SharedStoreArgs* shared, bool writeback, AttnQuery* aq,
-                      hipStream_t st) {
+                      const void* v_cache, int64_t L, const void* k_new, const void* v_new, void* out, float* lse,
+                      const QueryScratch& sc, const SharedStoreArgs* shared, bool writeback, AttnQuery* aq, hipStream_t st) {
     constexpr int TR = Geometry<G>::TR;
     const int n_row_tiles = (R + TR - 1) / TR;
     const int n_img_tiles = (int)((L + KT - 1) / KT);
@@ -881,12 +937,12 @@ hipError_t pack_query(const Shape& s, const void* q_rows, const int32_t* q_index
     if (shared == nullptr) {
         if (writeback)
             pack_kv_images_kernel<true><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
-                (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
-                k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, sc.images);
+                (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new, q_index, R,
+                s.Hkv, n_img_tiles, sc.images);
         else
             pack_kv_images_kernel<false><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
-                (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new,
-                k_new != nullptr ? inv : nullptr, s.Hkv, n_img_tiles, sc.images);
+                (const __bf16*)k_cache, (const __bf16*)v_cache, (int)L, (const __bf16*)k_new, (const __bf16*)v_new, q_index, R,
+                s.Hkv, n_img_tiles, sc.images);
     } else {   // k_cache / v_cache are the shared chunk store
         ChunkRows rows;
         int max_len = (int)L - shared->ct.off[shared->ct.n];
@@ -899,11 +955,11 @@ hipError_t pack_query(const Shape& s, const void* q_rows, const int32_t* q_index
         if (s.rope_layout == FR_ROPE_INTERLEAVED)
             pack_kv_images_shared_kernel<FR_ROPE_INTERLEAVED><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
                 (const __bf16*)k_cache, (const __bf16*)v_cache, sc.store_row_map, sc.chunk_id_map, shared->table, (int)L,
-                (const __bf16*)k_new, (const __bf16*)v_new, inv, s.Hkv, n_img_tiles, sc.images);
+                (const __bf16*)k_new, (const __bf16*)v_new, q_index, R, s.Hkv, n_img_tiles, sc.images);
         else
             pack_kv_images_shared_kernel<FR_ROPE_HALF><<<dim3(n_img_tiles, s.Hkv), block, 0, st>>>(
                 (const __bf16*)k_cache, (const __bf16*)v_cache, sc.store_row_map, sc.chunk_id_map, shared->table, (int)L,
-                (const __bf16*)k_new, (const __bf16*)v_new, inv, s.Hkv, n_img_tiles, sc.images);
+                (const __bf16*)k_new, (const __bf16*)v_new, q_index, R, s.Hkv, n_img_tiles, sc.images);
     }
     aq->q_rows = (const __bf16*)q_rows;
     aq->q_index = q_index;
@@ -918,74 +974,66 @@ hipError_t pack_query(const Shape& s, const void* q_rows, const int32_t* q_index
     return hipGetLastError();
 }
 
-// The attention launches over the packed queries of `batch`.
+// Launches the key-tile loop; with a live timer its event pair rides on the kernel's own dispatch (start and end of its
+// execution), so the stream carries no extra marker packets and the kernels before and after it are not held up.
 template <int G>
-hipError_t run_batch(const Shape& s, AttnBatch& batch, float* partials, size_t partials_bytes, int mode,
-                     int split_mode, KernelTimer* timer, hipStream_t st) {
-    const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
-    const size_t lds_fast = sizeof(Rings) > EPILOGUE_LDS ? sizeof(Rings) : EPILOGUE_LDS;
-    const size_t lds_safe = (size_t)IMG_BYTES > EPILOGUE_LDS ? (size_t)IMG_BYTES : EPILOGUE_LDS;
-    int max_row_tiles = 0, max_img_tiles = 0;
-    for (int i = 0; i < batch.n; ++i) {
-        max_row_tiles = std::max(max_row_tiles, batch.q[i].n_row_tiles);
-        max_img_tiles = std::max(max_img_tiles, batch.q[i].n_img_tiles);
-    }
-    batch.max_row_tiles = max_row_tiles;
-    const dim3 grid(max_row_tiles * batch.n * s.Hkv), block(256);
-    // Few (row tile, KV head) items: the chip would idle behind the longest ones, so each is walked by two
-    // workgroups.  Not worth the partial results' traffic once the items alone fill the CUs, nor for short prompts;
-    // a batch of queries fills the chip by itself.
-    // (Letting the part that finishes last add the other's sums inside the same kernel was measured too: the
-    // device-scope fences it needs write back and invalidate the whole L2 at every arrival and cost 110 us.)
-    const bool fits = batch.n == 1 && (size_t)grid.x * 2 * PART_FLOATS * sizeof(float) <= partials_bytes;
-    const bool split = fits && (split_mode == FR_ATTN_SPLIT_ON ||
-                                (split_mode == FR_ATTN_SPLIT_AUTO && (int)grid.x <= ATTN_SPLIT_AUTO_ITEMS && max_img_tiles >= 32));
-    // Kernel timer: the event pair rides on the kernel's own dispatch (start and end of its execution), so the
-    // stream carries no extra marker packets and the kernels before and after it are not held up.
-    const bool timed = timer != nullptr && timer->n_slots > 0 && mode != FR_ATTN_SOFTMAX_RUNNING_MAX;
-    const int slot = timed ? (int)(timer->n_recorded % timer->n_slots) : 0;
-    int use_flags = 1;
-    if (mode == FR_ATTN_SOFTMAX_RUNNING_MAX) {
-        use_flags = 0;   // recompute every workgroup with the running maximum
-    } else if (split) {
-        if (timed) {
-            hipExtLaunchKernelGGL((attn_fixed_ref_kernel<G, 2>), dim3(grid.x * 2), block, (uint32_t)lds_fast, st,
-                                  timer->start[slot], timer->stop[slot], 0u, batch, partials, s.Hq, s.Hkv, scale_log2e);
-            ++timer->n_recorded;
-        } else {
-            attn_fixed_ref_kernel<G, 2><<<dim3(grid.x * 2), block, lds_fast, st>>>(batch, partials, s.Hq, s.Hkv, scale_log2e);
-        }
-        const AttnQuery& q0 = batch.q[0];
-        attn_combine_kernel<G><<<grid, block, EPILOGUE_LDS, st>>>(q0.q_index, q0.R, partials, q0.out, q0.lse, q0.flags,
-                                                                  s.Hq, s.Hkv, q0.n_row_tiles);
+void launch_tile_loop(const AttnBatch& batch, dim3 grid, float* partials, int n_parts, const Shape& s, float scale_log2e,
+                      KernelTimer* timer, bool timed, hipStream_t st) {
+    if (timed) {
+        const int slot = (int)(timer->n_recorded % timer->n_slots);
+        hipExtLaunchKernelGGL((attn_fixed_ref_kernel<G>), grid, dim3(256), (uint32_t)LDS_FAST, st, timer->start[slot],
+                              timer->stop[slot], 0u, batch, partials, n_parts, s.Hq, s.Hkv, scale_log2e);
+        ++timer->n_recorded;
     } else {
-        if (timed) {
-            hipExtLaunchKernelGGL((attn_fixed_ref_kernel<G, 1>), grid, block, (uint32_t)lds_fast, st, timer->start[slot],
-                                  timer->stop[slot], 0u, batch, (float*)nullptr, s.Hq, s.Hkv, scale_log2e);
-            ++timer->n_recorded;
-        } else {
-            attn_fixed_ref_kernel<G, 1><<<grid, block, lds_fast, st>>>(batch, nullptr, s.Hq, s.Hkv, scale_log2e);
-        }
+        attn_fixed_ref_kernel<G><<<grid, dim3(256), LDS_FAST, st>>>(batch, partials, n_parts, s.Hq, s.Hkv, scale_log2e);
     }
-    attn_running_max_kernel<G><<<grid, block, lds_safe, st>>>(batch, use_flags, s.Hq, s.Hkv, scale_log2e);
-    return hipGetLastError();
+}
+
+// Parts per item of a one-query launch of `items` (row tile, KV head) items over n_img_tiles key tiles.  With few items
+// the chip would idle behind the longest ones (rows ascend by position: the question rows' tiles walk the whole prompt),
+// so every item's key tiles are dealt to several workgroups.  Measured on a 17k-token prompt (256 compute units, one
+// workgroup each): two parts pay up to about 400 items (recompute ratios up to 15 %; at 30 %, 680 items, the partial
+// results' traffic and the combine pass cost more than the balance gains); below half a workgroup per compute unit more
+// parts pay until there is about one piece per compute unit (question-only prefill, 64 items: 4 parts, 0.24 -> 0.17 ms);
+// in between two parts stay best (168 items at 5 %, 128 items of the offline stage: three or four parts lose 3-15 %).
+int choose_parts(int split_mode, int items, int n_img_tiles, int n_cu, size_t partials_bytes) {
+    int parts = 1;
+    if (split_mode == FR_ATTN_SPLIT_ON) parts = 2;
+    if (split_mode == FR_ATTN_SPLIT_AUTO && n_img_tiles >= 32 && items <= ATTN_SPLIT_AUTO_ITEMS)
+        parts = std::max(2, std::min(ATTN_MAX_PARTS, n_cu / std::max(items, 1)));
+    while (parts > 1 && (size_t)items * parts * PART_FLOATS * sizeof(float) > partials_bytes) --parts;
+    return parts;
 }
 
 template <int G>
 hipError_t launch(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
-                  const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv, void* out,
-                  float* lse, const Workspace& ws, int mode, int split_mode, const SharedStoreArgs* shared,
-                  KernelTimer* timer, bool writeback, hipStream_t st) {
+                  const void* v_cache, int64_t L, const void* k_new, const void* v_new, void* out, float* lse,
+                  const Workspace& ws, int mode, int split_mode, const SharedStoreArgs* shared, KernelTimer* timer,
+                  bool writeback, hipStream_t st) {
     hipError_t e = set_kernel_attributes<G>();
     if (e != hipSuccess) return e;
+    const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
     const QueryScratch sc{ws.store_row_map, ws.chunk_id_map, ws.kv_images, ws.kv_images_bytes, ws.attn_flags,
                           ws.attn_flags_elems};
     AttnBatch batch;
     batch.n = 1;
-    e = pack_query<G>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, sc, shared, writeback,
-                      &batch.q[0], st);
+    e = pack_query<G>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, out, lse, sc, shared, writeback, &batch.q[0], st);
     if (e != hipSuccess) return e;
-    return run_batch<G>(s, batch, ws.attn_partials, ws.attn_partials_bytes, mode, split_mode, timer, st);
+    batch.max_row_tiles = batch.q[0].n_row_tiles;
+    const int items = batch.q[0].n_row_tiles * s.Hkv;
+    const dim3 grid(items);
+    if (mode == FR_ATTN_SOFTMAX_RUNNING_MAX) {   // every item with the running maximum
+        attn_running_max_kernel<G><<<grid, dim3(256), LDS_SAFE, st>>>(batch, 0, s.Hq, s.Hkv, scale_log2e);
+        return hipGetLastError();
+    }
+    const int n_parts = choose_parts(split_mode, items, batch.q[0].n_img_tiles, ws.n_cu, ws.attn_partials_bytes);
+    const bool timed = timer != nullptr && timer->n_slots > 0;
+    launch_tile_loop<G>(batch, dim3(items * n_parts), ws.attn_partials, n_parts, s, scale_log2e, timer, timed, st);
+    if (n_parts > 1)   // adds the parts, stores, and recomputes the items whose sums overflowed
+        attn_combine_kernel<G><<<grid, dim3(256), LDS_SAFE, st>>>(batch.q[0], ws.attn_partials, n_parts, s.Hq, s.Hkv, scale_log2e);
+    else               // recomputes the items whose workgroups raised their flag
+        attn_running_max_kernel<G><<<grid, dim3(256), LDS_SAFE, st>>>(batch, 1, s.Hq, s.Hkv, scale_log2e);
+    return hipGetLastError();
 }
 
 template <int G>
@@ -993,25 +1041,36 @@ hipError_t launch_shared_batch(const Shape& s, int n, const SharedBatchQuery* qs
                                const void* v_store, int mode, KernelTimer* timer, hipStream_t st) {
     hipError_t e = set_kernel_attributes<G>();
     if (e != hipSuccess) return e;
+    const float scale_log2e = (1.0f / sqrtf((float)s.d)) * 1.4426950408889634f;
     AttnBatch batch;
     batch.n = n;
+    batch.max_row_tiles = 0;
     for (int i = 0; i < n; ++i) {
         const SharedBatchQuery& q = qs[i];
         const QueryScratch sc{q.store_row_map, q.chunk_id_map, q.images, q.images_bytes, q.flags, q.flags_elems};
-        e = pack_query<G>(s, q.q_rows, q.q_index, q.R, k_store, v_store, q.L, q.k_new, q.v_new, q.inv, q.out, q.lse, sc,
-                          &q.shared, false, &batch.q[i], st);
+        e = pack_query<G>(s, q.q_rows, q.q_index, q.R, k_store, v_store, q.L, q.k_new, q.v_new, q.out, q.lse, sc, &q.shared,
+                          false, &batch.q[i], st);
         if (e != hipSuccess) return e;
+        batch.max_row_tiles = std::max(batch.max_row_tiles, batch.q[i].n_row_tiles);
     }
-    return run_batch<G>(s, batch, nullptr, 0, mode, FR_ATTN_SPLIT_OFF, timer, st);
+    // a batch of queries fills the chip by itself: every item whole, one workgroup each
+    const dim3 grid(batch.max_row_tiles * n * s.Hkv);
+    if (mode == FR_ATTN_SOFTMAX_RUNNING_MAX) {
+        attn_running_max_kernel<G><<<grid, dim3(256), LDS_SAFE, st>>>(batch, 0, s.Hq, s.Hkv, scale_log2e);
+    } else {
+        launch_tile_loop<G>(batch, grid, nullptr, 1, s, scale_log2e, timer, timer != nullptr && timer->n_slots > 0, st);
+        attn_running_max_kernel<G><<<grid, dim3(256), LDS_SAFE, st>>>(batch, 1, s.Hq, s.Hkv, scale_log2e);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace
 
+// Partial results of a launch in parts: one slot of 132 KB per piece.
 size_t attn_mfma_partials_bytes(const Shape& s, int64_t max_tokens) {
     const int64_t tr = 4 * (64 / s.G);   // token rows per workgroup
-    int64_t items = ((max_tokens + tr - 1) / tr) * s.Hkv;
-    if (items > ATTN_SPLIT_MAX_ITEMS) items = ATTN_SPLIT_MAX_ITEMS;
-    return (size_t)items * 2 * PART_FLOATS * sizeof(float);
+    const int64_t items = std::min<int64_t>(((max_tokens + tr - 1) / tr) * s.Hkv, ATTN_SPLIT_AUTO_ITEMS);
+    return (size_t)(2 * items) * PART_FLOATS * sizeof(float);   // two parts of the most items that are split without being asked
 }
 
 bool attn_mfma_supported(const Shape& s) {
@@ -1019,15 +1078,15 @@ bool attn_mfma_supported(const Shape& s) {
 }
 
 hipError_t launch_attn_mfma(const Shape& s, const void* q_rows, const int32_t* q_index, int R, const void* k_cache,
-                            const void* v_cache, int64_t L, const void* k_new, const void* v_new, const int32_t* inv,
-                            void* out, float* lse, const Workspace& ws, int mode, int split_mode,
-                            const SharedStoreArgs* shared, KernelTimer* timer, bool writeback, hipStream_t st) {
+                            const void* v_cache, int64_t L, const void* k_new, const void* v_new, void* out, float* lse,
+                            const Workspace& ws, int mode, int split_mode, const SharedStoreArgs* shared,
+                            KernelTimer* timer, bool writeback, hipStream_t st) {
     if (R == 0) return hipSuccess;
     switch (s.G) {
-        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
-        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
-        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
-        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
+        case 1: return launch<1>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
+        case 2: return launch<2>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
+        case 4: return launch<4>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
+        default: return launch<8>(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, out, lse, ws, mode, split_mode, shared, timer, writeback, st);
     }
 }
 
