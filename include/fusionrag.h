@@ -102,10 +102,11 @@ int64_t fr_workspace_bytes(const fr_ctx* ctx);
  * FR_OPT_DECODE_KERNEL: AUTO (default) lets fr_decode_attn form the logits on the matrix cores where it can (bf16,
  * head_dim 128); GENERIC forces the all-vector-ALU kernel that every other shape uses (so that tests reach both).
  * FR_OPT_GEMM_TILE: output features per workgroup of the projection kernels, 0 (default: 256 where the feature count
- * is a multiple of 256, else 128), 128 or 256; process-wide, for tests and tuning.
+ * is a multiple of 256, else 128), 128 or 256; for tests and tuning.
  * FR_OPT_GEMM_TAIL_SPLIT: 1 (default): when the output tiles of a projection do not fill the last round of
  * workgroups (one per CU), the tiles of that round are split along K over several workgroups each and a second small
- * kernel adds the parts; 0: never.  Same results up to fp32 summation order; process-wide, for tests and tuning.
+ * kernel adds the parts; 0: never.  Same results up to fp32 summation order; for tests and tuning.  (Like every
+ * option these two belong to the context they are set on.)
  * FR_OPT_ATTN_KERNEL_TIMER: value n in [0, 256]: the tiled attention launch attaches an event pair to the dispatch of
  * its dominant kernel (the key-tile loop) on the call's stream, start and end of that kernel's execution, and keeps
  * the last n pairs; 0 (default) switches the timer off.  Read with fr_attn_kernel_times.  For benchmarks: the events

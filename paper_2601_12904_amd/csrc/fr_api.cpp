@@ -238,12 +238,12 @@ fr_status fr_set_option(fr_ctx* ctx, int32_t option, int64_t value) {
         case FR_OPT_GEMM_TILE:
             if (value != 0 && value != 128 && value != 256)
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_GEMM_TILE: %lld is not 0, 128 or 256", (long long)value);
-            launch_gemm_set_tile((int)value);
+            ctx->gemm_tuning.tile = (int)value;
             return FR_OK;
         case FR_OPT_GEMM_TAIL_SPLIT:
             if (value != 0 && value != 1)
                 return fail(ctx, FR_ERR_INVALID_ARG, "FR_OPT_GEMM_TAIL_SPLIT: %lld is not 0 or 1", (long long)value);
-            launch_gemm_set_split((int)value);
+            ctx->gemm_tuning.tail_split = (int)value;
             return FR_OK;
         case FR_OPT_ATTN_SPLIT:
             if (value != FR_ATTN_SPLIT_AUTO && value != FR_ATTN_SPLIT_OFF && value != FR_ATTN_SPLIT_ON)
@@ -547,7 +547,7 @@ static fr_status prefill_attn_impl(fr_ctx* ctx, const void* q_rows, const int32_
         }
         e = launch_attn_simt(s, q_rows, q_index, R, k_cache, v_cache, L, k_new, v_new, inv, out, lse_out, hs);
         if (e == hipSuccess && writeback)   // the generic kernel has no packing pass to fuse it into
-            e = launch_kv_scatter(s, k_new, v_new, q_index, R, const_cast<void*>(k_cache), const_cast<void*>(v_cache), hs);
+            e = launch_kv_scatter(s, k_new, v_new, q_index, R, const_cast<void*>(k_cache), const_cast<void*>(v_cache), L, hs);
     }
     if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
     return FR_OK;
@@ -822,7 +822,7 @@ fr_status fr_kv_scatter(fr_ctx* ctx, const void* k_new, const void* v_new, const
         return fail(ctx, FR_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     if (reinterpret_cast<uintptr_t>(q_index) & 3u) return fail(ctx, FR_ERR_INVALID_ARG, "q_index must be 4-byte aligned");
     if ((st = need_device(ctx)) != FR_OK) return st;
-    hipError_t e = launch_kv_scatter(ctx->shape, k_new, v_new, q_index, R, k_cache, v_cache, (hipStream_t)stream);
+    hipError_t e = launch_kv_scatter(ctx->shape, k_new, v_new, q_index, R, k_cache, v_cache, L, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "scatter launch", e);
     return FR_OK;
 }
@@ -874,7 +874,7 @@ fr_status fr_linear(fr_ctx* ctx, const void* a, const void* w, int32_t M, int32_
     if (!out || !aligned16(out) || !aligned16(residual))
         return fail(ctx, FR_ERR_INVALID_ARG, "fr_linear: out is NULL or out / residual not 16-byte aligned");
     if ((st = need_device(ctx)) != FR_OK) return st;
-    hipError_t e = launch_linear(a, w, M, N, K, residual, out, ctx->ws.gemm_partials, ctx->ws.gemm_partials_bytes, (hipStream_t)stream);
+    hipError_t e = launch_linear(a, w, M, N, K, residual, out, ctx->ws.gemm_partials, ctx->ws.gemm_partials_bytes, ctx->gemm_tuning, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "linear launch", e);
     return FR_OK;
 }
@@ -889,7 +889,7 @@ fr_status fr_linear_swiglu(fr_ctx* ctx, const void* a, const void* w_gate_up, in
     if (M == 0) return FR_OK;
     if (!out || !aligned16(out)) return fail(ctx, FR_ERR_INVALID_ARG, "fr_linear_swiglu: out is NULL or misaligned");
     if ((st = need_device(ctx)) != FR_OK) return st;
-    hipError_t e = launch_linear_swiglu(a, w_gate_up, M, F, K, out, ctx->ws.gemm_partials, ctx->ws.gemm_partials_bytes, (hipStream_t)stream);
+    hipError_t e = launch_linear_swiglu(a, w_gate_up, M, F, K, out, ctx->ws.gemm_partials, ctx->ws.gemm_partials_bytes, ctx->gemm_tuning, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "swiglu launch", e);
     return FR_OK;
 }
@@ -910,7 +910,7 @@ fr_status fr_qkv_rope(fr_ctx* ctx, const void* a, const void* w_qkv, int32_t M, 
         return fail(ctx, FR_ERR_INVALID_ARG, "fr_qkv_rope: positions / q_out / k_out / v_out is NULL or misaligned");
     if ((st = need_device(ctx)) != FR_OK) return st;
     hipError_t e = launch_qkv_rope(s, a, w_qkv, M, K, positions, ctx->ws.rope_rows, q_out, k_out, v_out, ctx->ws.gemm_partials,
-                                   ctx->ws.gemm_partials_bytes, (hipStream_t)stream);
+                                   ctx->ws.gemm_partials_bytes, ctx->gemm_tuning, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(ctx, "qkv launch", e);
     return FR_OK;
 }

@@ -75,6 +75,14 @@ struct KernelTimer {
 };
 }  // namespace fr
 
+namespace fr {
+// Tuning switches of the projection kernels, kept per context (FR_OPT_GEMM_TILE, FR_OPT_GEMM_TAIL_SPLIT).
+struct GemmTuning {
+    int tile = 0;         // output features per workgroup: 0 = choose, 128, 256
+    int tail_split = 1;   // 0 = the tiles of a launch's last, partly filled round are never split along K
+};
+}  // namespace fr
+
 struct fr_ctx {
     fr::Shape shape;
     int64_t max_tokens = 0;
@@ -86,6 +94,7 @@ struct fr_ctx {
     int attn_softmax_mode = FR_ATTN_SOFTMAX_AUTO;
     int attn_split_mode = FR_ATTN_SPLIT_AUTO;
     int decode_generic = 0;
+    fr::GemmTuning gemm_tuning;
     fr::KernelTimer attn_timer;
     std::string err;
 };
@@ -102,7 +111,7 @@ hipError_t launch_rope_shift(const Shape& s, const void* src, void* dst, const C
                              int64_t dst_stride, const ChunkRows* src_rows, hipStream_t st);
 hipError_t launch_clear_words(uint32_t* words, int64_t n_words, hipStream_t st);
 hipError_t launch_kv_scatter(const Shape& s, const void* k_new, const void* v_new, const int32_t* q_index,
-                             int R, void* k_cache, void* v_cache, hipStream_t st);
+                             int R, void* k_cache, void* v_cache, int64_t L, hipStream_t st);
 
 hipError_t launch_score_simt(const Shape& s, const void* q, int nq, const void* k_ctx, const ChunkTable& ct,
                              int norm, const Workspace& ws, float* scores, hipStream_t st);
@@ -201,18 +210,16 @@ constexpr int ATTN_SPLIT_AUTO_ITEMS = 400;
 constexpr int ATTN_MAX_PARTS = 4;
 size_t attn_mfma_partials_bytes(const Shape& s, int64_t max_tokens);
 
-void launch_gemm_set_tile(int features_per_workgroup);   // 0 = choose, 128, 256
-void launch_gemm_set_split(int on);                      // 0 = the last round's tiles are never split along K
 // `partials` (gemm_partials_bytes() bytes, or NULL: no split) holds the partial sums of the tiles of a launch's last,
 // partly filled round, which are computed by several workgroups each.
 size_t gemm_partials_bytes();
 hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
-                         float* partials, size_t partials_bytes, hipStream_t st);
+                         float* partials, size_t partials_bytes, const GemmTuning& tune, hipStream_t st);
 hipError_t launch_linear_swiglu(const void* a, const void* w_gate_up, int M, int F, int K, void* out, float* partials,
-                                size_t partials_bytes, hipStream_t st);
+                                size_t partials_bytes, const GemmTuning& tune, hipStream_t st);
 hipError_t launch_qkv_rope(const Shape& s, const void* a, const void* w_qkv, int M, int K, const int32_t* positions,
                            float2* rope_rows, void* q_out, void* k_out, void* v_out, float* partials,
-                           size_t partials_bytes, hipStream_t st);
+                           size_t partials_bytes, const GemmTuning& tune, hipStream_t st);
 hipError_t launch_rmsnorm(const void* x, const void* gain, int R, int hidden, float eps, void* out, hipStream_t st);
 
 // ---- element helpers (device) ------------------------------------------------------------

@@ -98,9 +98,9 @@ struct Geometry {
 
     // ordinal counts the row tiles of a query from the longest one; ordinal < n_row_tiles
     __device__ __forceinline__ void init(const int32_t* __restrict__ q_index, int R, int Hkv, int n_row_tiles,
-                                         int g_, int ordinal) {
+                                         int n_img_tiles, int g_, int ordinal) {
         init_rows(Hkv, n_row_tiles, g_, ordinal);
-        init_positions(q_index, R);
+        init_positions(q_index, R, n_img_tiles);
     }
     // The part that does not read the Q index: which rows and heads the lane's two columns are.
     __device__ __forceinline__ void init_rows(int Hkv, int n_row_tiles, int g_, int ordinal) {
@@ -120,13 +120,14 @@ struct Geometry {
         }
     }
     // The positions of the rows, from the Q index.
-    __device__ __forceinline__ void init_positions(const int32_t* __restrict__ q_index, int R) {
+    // (a position beyond the prompt breaks the caller's contract; the walk then ends with the last image that exists)
+    __device__ __forceinline__ void init_positions(const int32_t* __restrict__ q_index, int R, int n_img_tiles) {
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) col_pos[nb] = q_index[min(col_row[nb], R - 1)];
         const int p_first = q_index[row0];                   // rows ascend: every key <= p_first is visible to all
         const int p_max = q_index[min(R, row0 + TR) - 1];    // the workgroup's furthest key
         wp_max = q_index[min(row0 + wave * TRW + TRW, R) - 1];   // a wave past the end copies the last row
-        n_kt = p_max / KT + 1;
+        n_kt = min(p_max / KT + 1, n_img_tiles);
         n_plain = min((p_first + 1) / KT, n_kt - 1);
     }
 };
@@ -157,7 +158,7 @@ __device__ __forceinline__ void tile_fresh_rows(const int32_t* __restrict__ q_in
         const int row = lo + tid;
         if (row < R) {
             const int pos = q_index[row];
-            if (pos < target + KT) fresh[pos - target] = row;
+            if (pos >= target && pos < target + KT) fresh[pos - target] = row;   // (pos < target only for an index that is not ascending)
         }
     }
     __syncthreads();
@@ -571,7 +572,7 @@ __device__ __forceinline__ void running_max_item(const AttnQuery& aq, int g, int
     unsigned char* k_img = smem;
     unsigned char* v_img = smem + K_IMG_BYTES;
     Geometry<G> ge;
-    ge.init(aq.q_index, R, Hkv, aq.n_row_tiles, g, ordinal);
+    ge.init(aq.q_index, R, Hkv, aq.n_row_tiles, n_img_tiles, g, ordinal);
     const int h = ge.h;
     FragOffsets fo;
     fo.init(ge.x, h);
@@ -686,7 +687,7 @@ __device__ __forceinline__ void process_piece(const AttnQuery& aq, int g, int or
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
     }
-    ge.init_positions(aq.q_index, R);
+    ge.init_positions(aq.q_index, R, n_img_tiles);
     const int n_kt = ge.n_kt;
     // this piece's key tiles [kb, ke): shares of ceil(n_kt / n_parts) tiles, so part 0 is never empty
     const int per_part = part < 0 ? n_kt : (n_kt + n_parts - 1) / n_parts;
@@ -833,7 +834,7 @@ __global__ __launch_bounds__(256, 2) void attn_combine_kernel(const AttnQuery aq
     const int g = (int)blockIdx.x % Hkv, ordinal = (int)blockIdx.x / Hkv;
     {
         Geometry<G> ge;
-        ge.init(aq.q_index, aq.R, Hkv, aq.n_row_tiles, g, ordinal);
+        ge.init(aq.q_index, aq.R, Hkv, aq.n_row_tiles, aq.n_img_tiles, g, ordinal);
         const float* p0 = partials + (((size_t)ordinal * n_parts) * Hkv + g) * PART_FLOATS + threadIdx.x;
         const size_t part_stride = (size_t)Hkv * PART_FLOATS;
         f32x16 o[4][2];

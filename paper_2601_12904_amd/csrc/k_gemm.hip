@@ -402,12 +402,8 @@ __global__ void rope_rows_table_kernel(const int32_t* __restrict__ positions, in
     table[(size_t)r * half_d + p] = make_float2((float)cs, (float)sn);
 }
 
-int g_gemm_tile = 0;   // 0: choose; 128 / 256: features per workgroup (set through launch_gemm_set_tile, for tests)
-
-int g_gemm_split = 1;               // 0: never split the tail (for tests)
-
 template <int EPI, int WF>
-hipError_t launch_gemm_wf(GemmArgs g, hipStream_t st) {
+hipError_t launch_gemm_wf(GemmArgs g, const GemmTuning& tune, hipStream_t st) {
     using TL = Tiling<WF>;
     // once per process (a function-local static is initialised exactly once, also under concurrent first calls)
     struct Setup { hipError_t err; int n_cu; };
@@ -429,7 +425,7 @@ hipError_t launch_gemm_wf(GemmArgs g, hipStream_t st) {
     // round then takes 1 / n_parts of a tile's time, and the launch rest / n_cu rounds less.
     const int n_tiles = ((g.N + TL::BF - 1) / TL::BF) * ((g.M + BR - 1) / BR);
     const int rest = n_tiles % n_cu;
-    int n_parts = (rest == 0 || g_gemm_split == 0) ? 1 : std::min(n_cu / rest, 8);
+    int n_parts = (rest == 0 || tune.tail_split == 0) ? 1 : std::min(n_cu / rest, 8);
     // A part pays its own pipeline fill, a 128 KB dump of partial sums and its share of the second kernel (13 us for 128
     // tiles in two parts).  Measured at 2970 rows: K = 14336, 384 tiles, two parts of 112 K tiles: 9 % less time;
     // K = 4096, 576 tiles, four parts of 16: 8 % less; K = 4096, 384 tiles, two parts of 32: 4 % less; K = 4096,
@@ -448,39 +444,37 @@ hipError_t launch_gemm_wf(GemmArgs g, hipStream_t st) {
 }
 
 template <int EPI>
-hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
+hipError_t launch_gemm(const GemmArgs& g, const GemmTuning& tune, hipStream_t st) {
     // (Feeding the weight fragments from memory straight into registers, to halve the LDS traffic, was tried: 16-byte
     // pieces of 32 rows per load instruction cost far more in the memory pipeline than they save: 400-500 TFLOP/s.)
-    const bool wide = (g_gemm_tile == 256) || (g_gemm_tile == 0 && g.N % 256 == 0);
-    return wide ? launch_gemm_wf<EPI, 4>(g, st) : launch_gemm_wf<EPI, 2>(g, st);
+    const bool wide = (tune.tile == 256) || (tune.tile == 0 && g.N % 256 == 0);
+    return wide ? launch_gemm_wf<EPI, 4>(g, tune, st) : launch_gemm_wf<EPI, 2>(g, tune, st);
 }
 
 }  // namespace
 
-void launch_gemm_set_tile(int features_per_workgroup) { g_gemm_tile = features_per_workgroup; }
-void launch_gemm_set_split(int on) { g_gemm_split = on; }
 size_t gemm_partials_bytes() { return (size_t)256 * 8 * PARTIAL_FLOATS_PER_WAVE * sizeof(float); }   // 256 parts of 8 waves
 
 hipError_t launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
-                         float* partials, size_t partials_bytes, hipStream_t st) {
+                         float* partials, size_t partials_bytes, const GemmTuning& tune, hipStream_t st) {
     GemmArgs g{};
     g.partials = partials; g.partials_bytes = partials_bytes;
     g.a = (const __bf16*)a; g.w = (const __bf16*)w; g.M = M; g.N = N; g.K = K;
     g.out = (__bf16*)out; g.residual = (const __bf16*)residual;
-    return residual ? launch_gemm<EPI_RESIDUAL>(g, st) : launch_gemm<EPI_STORE>(g, st);
+    return residual ? launch_gemm<EPI_RESIDUAL>(g, tune, st) : launch_gemm<EPI_STORE>(g, tune, st);
 }
 
 hipError_t launch_linear_swiglu(const void* a, const void* w_gate_up, int M, int F, int K, void* out, float* partials,
-                                size_t partials_bytes, hipStream_t st) {
+                                size_t partials_bytes, const GemmTuning& tune, hipStream_t st) {
     GemmArgs g{};
     g.partials = partials; g.partials_bytes = partials_bytes;
     g.a = (const __bf16*)a; g.w = (const __bf16*)w_gate_up; g.M = M; g.N = 2 * F; g.K = K; g.out = (__bf16*)out;
-    return launch_gemm<EPI_SWIGLU>(g, st);
+    return launch_gemm<EPI_SWIGLU>(g, tune, st);
 }
 
 hipError_t launch_qkv_rope(const Shape& s, const void* a, const void* w_qkv, int M, int K, const int32_t* positions,
                            float2* rope_rows, void* q_out, void* k_out, void* v_out, float* partials,
-                           size_t partials_bytes, hipStream_t st) {
+                           size_t partials_bytes, const GemmTuning& tune, hipStream_t st) {
     rope_rows_table_kernel<<<dim3(M), dim3(64), 0, st>>>(positions, M, s.d / 2, s.d, s.rope_base, s.rope_index_base,
                                                           rope_rows);
     GemmArgs g{};
@@ -488,7 +482,7 @@ hipError_t launch_qkv_rope(const Shape& s, const void* a, const void* w_qkv, int
     g.a = (const __bf16*)a; g.w = (const __bf16*)w_qkv; g.M = M; g.N = (s.Hq + 2 * s.Hkv) * s.d; g.K = K;
     g.q_out = (__bf16*)q_out; g.k_out = (__bf16*)k_out; g.v_out = (__bf16*)v_out; g.rope = rope_rows;
     g.Hq = s.Hq; g.Hkv = s.Hkv; g.d = s.d;
-    return launch_gemm<EPI_QKV_ROPE>(g, st);
+    return launch_gemm<EPI_QKV_ROPE>(g, tune, st);
 }
 
 hipError_t launch_rmsnorm(const void* x, const void* gain, int R, int hidden, float eps, void* out, hipStream_t st) {

@@ -57,12 +57,16 @@ class SelectivePrefillStack:
 
     def forward(self, h: torch.Tensor, q_index: torch.Tensor, k_cached: List[torch.Tensor], k_cache: List[torch.Tensor],
                 v_cache: List[torch.Tensor], chunk_offsets, src_pos0, nq: int, L: int, select_every_layer: bool = False,
-                k_select: int = 0, q_index_scratch: Optional[torch.Tensor] = None) -> torch.Tensor:
+                k_select: int = 0, q_index_scratch: Optional[torch.Tensor] = None,
+                capture: Optional[dict] = None) -> torch.Tensor:
         """h [R, hidden] is updated in place and returned; k_cache / v_cache [L, Hkv, d] per layer end up holding
-        the stitched cache with the recomputed rows written back."""
+        the stitched cache with the recomputed rows written back.  `capture`, if given, maps layer numbers to dicts
+        that receive copies of the layer's input and output rows ("h_in", "h_out"): tests feed the input to the oracle."""
         c, R = self.ctx, h.shape[0]
         s = self._scratch(R)
         for l, w in enumerate(self.layers):
+            if capture is not None and l in capture:
+                capture[l]["h_in"] = h.clone()
             c.fr_rmsnorm(h, w.g1, R, self.hidden, self.eps, s["x"])
             c.fr_qkv_rope(s["x"], w.w_qkv, R, self.hidden, q_index, s["q"], s["k"], s["v"])
             c.fr_rope_shift(k_cached[l], k_cache[l], chunk_offsets, src_pos0)
@@ -75,4 +79,6 @@ class SelectivePrefillStack:
             c.fr_rmsnorm(h, w.g2, R, self.hidden, self.eps, s["x"])
             c.fr_linear_swiglu(s["x"], w.w_gate_up, R, self.ffn, self.hidden, s["act"])
             c.fr_linear(s["act"], w.w_down, R, self.hidden, self.ffn, h, h)
+            if capture is not None and l in capture:
+                capture[l]["h_out"] = h.clone()
         return h

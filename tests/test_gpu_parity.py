@@ -414,6 +414,25 @@ def test_kv_scatter_bit_exact(name, seed):
     ctx.close()
 
 
+def test_kv_scatter_ignores_positions_outside_the_cache():
+    """A Q index entry outside [0, L) breaks the caller's contract; the kernel's own bounds check drops that row
+    instead of writing outside the cache, and every other row is written as usual."""
+    w = workloads()["tiny_f32"](0)
+    dt = w.shape.dtype
+    k_ctx, _, _, qi = staged(w)
+    k_cache, v_cache = assembled_cache(w, k_ctx)
+    ctx = H.make_ctx(w.shape, w.L, w.n_chunks, w.nq)
+    bad = qi.copy()
+    bad[0], bad[-1] = -3, w.L + 5
+    kc, vc = H.dev(k_cache, dt), H.dev(v_cache, dt)
+    ctx.fr_kv_scatter(H.dev(w.k_full[qi], dt), H.dev(w.v_full[qi], dt), torch.from_numpy(bad.astype(np.int32)).cuda(),
+                      len(qi), kc, vc, w.L)
+    torch.cuda.synchronize()
+    want_k, want_v = orc.kv_scatter(qi[1:-1], w.k_full[qi[1:-1]], w.v_full[qi[1:-1]], k_cache, v_cache)
+    assert np.array_equal(H.host(kc), want_k.astype(np.float64)) and np.array_equal(H.host(vc), want_v.astype(np.float64))
+    ctx.close()
+
+
 @pytest.mark.parametrize("name,seed", CASES)
 def test_chained_layer(name, seed):
     """The four calls back to back on one stream, no host work in between, against the oracle chain."""

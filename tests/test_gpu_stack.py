@@ -223,3 +223,68 @@ def test_full_size_layer_sampled():
     H.assert_close(H.host(v_cache[idx]), v_new, "bf16", "fresh V rows written back")
     H.assert_close(H.host(h[torch.from_numpy(rows).cuda()]), ho, "bf16", "layer output, sampled rows")
     ctx.close()
+
+
+@pytest.fixture(scope="module")
+def full_stack_run():
+    """The 32-layer stack of the full-stack configuration (hidden 4096, FFN 14336, config 2's prompt, 2970 rows) run
+    once on the GPU; inputs and outputs of layers 1, 15 and 31 are kept for the teacher-forced checks below."""
+    from paper_2601_12904_amd import stack as S
+    hidden, ffn, n_layers = 4096, 14336, 32
+    Hq, Hkv, d = SHAPE.n_q_heads, SHAPE.n_kv_heads, SHAPE.head_dim
+    w = synth.config_17k(seed=0)
+    rng = np.random.default_rng(21)
+    k = orc.topk_count(w.L_ctx, w.ratio)
+    qi = np.concatenate([np.sort(rng.choice(w.L_ctx, size=k, replace=False)), w.L_ctx + np.arange(w.nq)]).astype(np.int64)
+    R = len(qi)
+    ctx = H.make_ctx(SHAPE, w.L, w.n_chunks, w.nq)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(9)
+    layers = [S.random_layer(hidden, ffn, Hq, Hkv, d, gen) for _ in range(n_layers)]
+    st = S.SelectivePrefillStack(ctx, layers, hidden, ffn)
+    sig = 1.0 / np.sqrt(d)
+    bf16 = torch.bfloat16
+    k_cached = [(torch.randn((w.L_ctx, Hkv, d), generator=gen, device="cuda") * sig).to(bf16) for _ in range(n_layers)]
+    k_cache = [torch.zeros((w.L, Hkv, d), dtype=bf16, device="cuda") for _ in range(n_layers)]
+    v_cache = [torch.zeros((w.L, Hkv, d), dtype=bf16, device="cuda") for _ in range(n_layers)]
+    v_src = {}
+    for l, vc in enumerate(v_cache):
+        vc[: w.L_ctx] = (torch.randn((w.L_ctx, Hkv, d), generator=gen, device="cuda") * sig).to(bf16)
+        if l in (1, 15, 31):
+            v_src[l] = H.host(vc[: w.L_ctx])
+    h = torch.randn((R, hidden), generator=gen, device="cuda").to(bf16)
+    capture = {1: {}, 15: {}, 31: {}}
+    st.forward(h, torch.from_numpy(qi.astype(np.int32)).cuda(), k_cached, k_cache, v_cache, w.chunk_offsets, w.src_pos0,
+               w.nq, w.L, capture=capture)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(h.float()).all())
+    run = dict(w=w, qi=qi, layers=layers, capture=capture, v_src=v_src,
+               k_cached={l: H.host(k_cached[l]) for l in capture},
+               k_cache={l: k_cache[l] for l in capture}, v_cache={l: v_cache[l] for l in capture})
+    yield run
+    ctx.close()
+
+
+@pytest.mark.parametrize("layer", [1, 15, 31])
+def test_full_size_stack_layers_teacher_forced(full_stack_run, layer):
+    """Layers 1, 15 and 31 of the 32-layer run, each checked on its own: the oracle is given the rows the GPU fed into
+    that layer (so errors of the layers before do not accumulate into the comparison) and follows the pipeline store
+    by store; compared are the fresh K/V the layer wrote back (all rows) and its output on sampled rows."""
+    r = full_stack_run
+    w, qi, lw = r["w"], r["qi"], r["layers"][layer]
+    Hq, Hkv, d = SHAPE.n_q_heads, SHAPE.n_kv_heads, SHAPE.head_dim
+    rnd = lambda t: synth.round_to_storage(np.asarray(t, dtype=np.float32), "bf16").astype(np.float64)
+    wd = {n: H.host(getattr(lw, n)) for n in ("g1", "w_qkv", "w_o", "g2", "w_gate_up", "w_down")}
+    kc, vc = np.zeros((w.L, Hkv, d)), np.zeros((w.L, Hkv, d))
+    kc[: w.L_ctx] = rnd(orc.rope_shift(r["k_cached"][layer], w.chunk_offsets, w.src_pos0, None, SHAPE.rope_base))
+    vc[: w.L_ctx] = r["v_src"][layer]
+    rng = np.random.default_rng(100 + layer)
+    R = len(qi)
+    rows = np.unique(np.concatenate([[0, R - 1], rng.choice(R, size=10, replace=False)]))
+    h_in = H.host(r["capture"][layer]["h_in"])
+    ho, k_new, v_new = orc.selective_prefill_layer(h_in, qi, kc, vc, wd, Hq, Hkv, d, SHAPE.rope_base, 1e-5, round_fn=rnd, rows=rows)
+    idx = torch.from_numpy(qi).cuda()
+    H.assert_close(H.host(r["k_cache"][layer][idx]), k_new, "bf16", f"layer {layer}: fresh K rows written back")
+    H.assert_close(H.host(r["v_cache"][layer][idx]), v_new, "bf16", f"layer {layer}: fresh V rows written back")
+    got = H.host(r["capture"][layer]["h_out"][torch.from_numpy(rows).cuda()])
+    H.assert_close(got, ho, "bf16", f"layer {layer}: output rows")
