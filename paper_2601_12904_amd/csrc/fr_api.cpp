@@ -176,6 +176,12 @@ fr_status fr_create(const fr_layer_desc* desc, int64_t max_tokens, int32_t max_c
     w.store_row_map = (int32_t*)(w.base + o_srow);
     w.chunk_id_map = (int32_t*)(w.base + o_cid);
     w.select_tmp = (uint32_t*)(w.base + o_sel);
+    if (hipMemset(w.select_tmp, 0, select_zeroed_bytes()) != hipSuccess) {   // the selection expects (and leaves) it zero
+        (void)hipFree(w.base);
+        w.base = nullptr;
+        delete ctx;
+        return FR_ERR_DEVICE;
+    }
     w.qsum = (float*)(w.base + o_qsum);
     w.attn_flags = (int32_t*)(w.base + o_flags);
     w.kv_images = (unsigned char*)(w.base + o_img);

@@ -141,6 +141,7 @@ constexpr size_t select_workspace_words(int64_t max_n) {   // scratch that serve
     return SELECT_FIXED_WORDS + 2 * (size_t)((max_n + SELECT_TILE - 1) / SELECT_TILE) + SELECT_CAND_WORDS;
 }
 size_t select_workspace_bytes();                    // scratch for any n up to 2^31 - 1
+size_t select_zeroed_bytes();                       // its leading part that must be zero when handed over (calls leave it zero)
 // Resolves this device's copy of the static scratch of fr_select_topk_static (once per device; no allocation).
 hipError_t select_static_prepare();
 hipError_t launch_select_large(const float* scores, int64_t n, int64_t k, int nq, int32_t* q_index, uint32_t* tmp,

@@ -67,7 +67,8 @@ extern "C" fr_status fr_select_topk_static(fr_ctx* ctx, const float* scores, int
     uint32_t* tmp = nullptr;
     hipError_t e = scratch_of_current_device(&tmp);
     if (e != hipSuccess) return fail(ctx, FR_ERR_DEVICE, hipGetErrorString(e));
-    // the kernels clear what must start at zero (state, histograms, status words) themselves
+    // what must start at zero (state, histograms, status words) is zero when the library is loaded, and every call
+    // clears it again before it ends
     e = fr::launch_select(scores, n, k, nq, q_index_out, tmp, SCRATCH_WORDS * sizeof(uint32_t), (hipStream_t)stream);
     if (e != hipSuccess) return fail(ctx, FR_ERR_DEVICE, hipGetErrorString(e));
     return FR_OK;
