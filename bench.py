@@ -25,12 +25,12 @@ import torch
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E peak
 
-# HBM traffic of the dominant kernel per launch, as read from hardware counters in a separate profiling run of this
+# HBM traffic of the attention call (packing pass + tile loop + combine pass) per launch, as read from hardware counters in a separate profiling run of this
 # script (`rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`, scaled by a plain copy of known size).  A bench run reads no
 # counters itself, so the figure is quoted from the profile named here, together with the commit it was taken at, and
 # only for the exact workload and launch configuration that was profiled; everything else reports null.
 TRAFFIC_FROM_PROFILE = {
-    "llama3_8b_layer_16x1024+512": {"bytes": None, "profile": "profiles/bench_config2_hbm_traffic.md", "commit": None},
+    "llama3_8b_layer_16x1024+512": {"bytes": 703.8e6, "profile": "profiles/bench_config2_hbm_traffic.md", "commit": "aa48ae9"},
 }
 
 
@@ -221,6 +221,27 @@ def bench_stack(args):
         t_every.append(run(True))
         t_once.append(run(False))
     ms_every, ms_once = float(np.mean(t_every)), float(np.mean(t_once))
+    # The same stack with every row recomputed (the full-prefill end of the paper's comparison; no selection): one
+    # untimed pass, two timed.
+    full = None
+    if args.ratio is None:
+        qi_full = torch.arange(w.L, dtype=torch.int32, device="cuda")
+        h_full = torch.randn((w.L, hidden), generator=gen, device="cuda").to(bf)
+
+        def run_full():
+            h = h_full.clone()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st.forward(h, qi_full, k_cached, k_cache, v_cache, w.chunk_offsets, w.src_pos0, w.nq, w.L,
+                       select_every_layer=False, k_select=k, q_index_scratch=scratch)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3
+
+        run_full()
+        ms_full = float(np.mean([run_full() for _ in range(2)]))
+        full = {"rows": int(w.L), "ms": round(ms_full, 2), "ttft_reduction_selection_every_layer": round(ms_full / ms_every, 2),
+                "ttft_reduction_selection_once": round(ms_full / ms_once, 2)}
+        del h_full, qi_full
     gemm_flops = 2.0 * R * n_layers * (hidden * (Hq + 2 * Hkv) * d + Hq * d * hidden + 3 * hidden * ffn)
     # the projections of one layer, each between two events on the launch stream (the stack's dominant kernels)
     sb, lw = st._scratch(R), layers[0]
@@ -278,6 +299,7 @@ def bench_stack(args):
                    "ffn": ffn, "recompute_ratio": w.ratio, "rows": R, "seed": args.seed,
                    "selection": "score_select executed in every layer (result discarded); rows chosen once"},
         "ms_selection_once": round(ms_once, 3),
+        **({"full_recompute": full} if full else {}),
         "gemm_tflop": round(gemm_flops / 1e12, 2), "attn_tflop": round(attn_flops / 1e12, 2),
         "overall_tflops": round((gemm_flops + attn_flops) / (ms_once * 1e-3) / 1e12, 1),
         "gemm_call_ms": {n: round(v, 4) for n, v in gemm_ms.items()},

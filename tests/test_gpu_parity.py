@@ -221,12 +221,12 @@ def test_select_topk_exact(n, k, nq):
 
 
 @pytest.mark.parametrize("n,k,nq", [(32769, 4915, 3), (40000, 40000, 2), (33000, 1, 0), (300000, 45000, 9),
-                                    (1 << 20, 157286, 0), (1234567, 1234, 1), (5000001, 750000, 2)])
+                                    (1 << 20, 157286, 0), (1234567, 1234, 1), (9000001, 1350000, 2)])
 def test_select_topk_many_workgroups(n, k, nq):
     """Score vectors beyond one workgroup's registers take the multi-pass selection: same definition, same oracle.
     `narrow_cluster` puts more keys into one 24-bit prefix than the candidate list holds (the last level then re-reads
     the scores); `ties` and `constant` exercise the equal-key budget across waves and tiles.  The largest case spans
-    three groups of tiles of the emitting pass's two-level scan."""
+    two steps of the emitting pass's look-back over the tiles before a tile."""
     ctx = H.make_ctx(synth.TINY_F32, 4096, 4, 16)
     rng = np.random.default_rng(n ^ k)
     for kind in ("signed", "ties", "clustered", "full_range", "constant", "narrow_cluster"):
