@@ -904,7 +904,7 @@ def main():
         "ms_per_step_as_hip_graph": round(ms_graph, 4),
         "attn_tflops": round(attn_tflops, 2),
         "attn_flops": attn_flops,
-        "hbm_gbps": {n: round(v, 1) for n, v in hbm.items()},
+        "call_gbps_cache_resident": {n: round(v, 1) for n, v in hbm.items()},   # algorithmic bytes over call time: 24-67 MB working sets that stay in the last-level cache, not HBM bandwidth
         "rope_shift_all_layers": {"layers": nl, "ms": round(rope_all_ms, 4), "gbps": round(rope_all_gbps, 1),
                                   "frac_of_hbm_peak": round(rope_all_gbps / PEAK_HBM_GBPS, 4)},
         "score_raw_all_layers": {"layers": nl, "ms": round(raw_all_ms, 4), "gbps": round(raw_all_gbps, 1),
