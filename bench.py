@@ -130,8 +130,12 @@ def parity_sample(w, qi, out_gpu, dt, n_rows: int = 48):
     want, _ = orc.sparse_prefill_attn(w.q_full[qi], qi, kc, vc, w.k_full[qi], w.v_full[qi], rows=rows)
     got = out_gpu[torch.from_numpy(rows).cuda()].to(torch.float32).cpu().numpy().astype(np.float64)
     scale = float(np.max(np.abs(want)))
+    ew = np.abs(got - want) / (np.abs(want) + 1e-3 * scale)
+    # the maximum sits on elements that are themselves a few thousandths of the tensor's scale, where the absolute error
+    # of a bf16 pipeline (about 2e-3 of the scale) is as large as the element; the quantiles show the bulk
     return {"rows": int(len(rows)), "max_rel_err": float(np.max(np.abs(got - want)) / scale),
-            "elementwise_rel_err": float(np.max(np.abs(got - want) / (np.abs(want) + 1e-3 * scale))),
+            "elementwise_rel_err": float(np.max(ew)), "elementwise_rel_err_median": float(np.median(ew)),
+            "elementwise_rel_err_p99": float(np.quantile(ew, 0.99)),
             "tolerance": 2e-2 if dt == "bf16" else 1e-5}
 
 

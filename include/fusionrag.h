@@ -97,8 +97,9 @@ int64_t fr_workspace_bytes(const fr_ctx* ctx);
  * running maximum everywhere.  Both give the same softmax; the option exists so that tests reach both.
  * FR_OPT_ATTN_SPLIT: AUTO (default) deals the key range of every (row tile, KV head) to two or more workgroups when
  * there are too few of those to fill the chip (few recomputed rows, e.g. question-only prefill or the offline stage of
- * eq. 10); OFF: never; ON: two workgroups each whenever the partial results fit the workspace.  Same results up to fp32
- * summation order.
+ * eq. 10); OFF: never; ON: two workgroups each whenever the partial results fit the workspace.  Same results up to the
+ * summation order and the partial sums' storage format (half precision after a per-column power-of-two scale: 11
+ * significant bits of a column's largest partial value, finer than the bf16 output).
  * FR_OPT_DECODE_KERNEL: AUTO (default) lets fr_decode_attn form the logits on the matrix cores where it can (bf16,
  * head_dim 128); GENERIC forces the all-vector-ALU kernel that every other shape uses (so that tests reach both).
  * FR_OPT_GEMM_TILE: output features per workgroup of the projection kernels, 0 (default: 256 where the feature count

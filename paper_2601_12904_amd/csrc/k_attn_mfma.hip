@@ -524,11 +524,43 @@ __device__ __forceinline__ void store_output(const Geometry<G>& ge, f32x16 (&o)[
     }
 }
 
-// Partial result of one part of an item: the 128 output accumulators, the two sums and the two exponent references
-// of every lane, register-major (float r of thread t at [r * 256 + t]: every store and load is one coalesced 1 KB
-// line per wave).  Part p of item (ordinal, KV head g) lives at ((ordinal * n_parts + p) * Hkv + g) * PART_FLOATS.
-constexpr int PART_REGS = 132;
-constexpr int PART_FLOATS = PART_REGS * 256;
+// Partial result of one part of an item, per lane: its 128 output accumulators as half-precision pairs (the 64 of a
+// column block scaled by a power of two that brings the largest of them into [0.5, 1): 11 significant bits of that
+// column's largest value, four times finer than the bf16 the output is rounded to), the two sums, the two exponent
+// references and the two scale exponents as 32-bit words: 70 words instead of 132.  Register-major (word r of thread t
+// at [r * 256 + t]: every store and load is one coalesced 1 KB line per wave).  Part p of item (ordinal, KV head g)
+// lives at ((ordinal * n_parts + p) * Hkv + g) * PART_FLOATS.  Infinities and NaNs survive the packing (the combine
+// pass must still see an overflow).
+constexpr int PART_REGS = 70;
+constexpr int PART_FLOATS = PART_REGS * 256;   // 32-bit words
+typedef _Float16 __attribute__((ext_vector_type(2))) f16x2;
+
+__device__ __forceinline__ void store_partial(float* __restrict__ dst_f, const f32x16 (&o)[4][2], const float (&lsum)[2],
+                                              const float (&mref)[2]) {
+    uint32_t* dst = reinterpret_cast<uint32_t*>(dst_f);
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        float m = 0.f;
+#pragma unroll
+        for (int md = 0; md < 4; ++md)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) m = fmaxf(m, fabsf(o[md][nb][v]));
+        // m = f 2^e with f in [0.5, 1); an infinite m keeps e = 0: the infinity is stored as it is
+        const int e = (m < INFINITY) ? __builtin_amdgcn_frexp_expf(m) : 0;
+#pragma unroll
+        for (int md = 0; md < 4; ++md)
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                f16x2 h;
+                h[0] = (_Float16)__builtin_ldexpf(o[md][nb][v], -e);
+                h[1] = (_Float16)__builtin_ldexpf(o[md][nb][v + 1], -e);
+                dst[(nb * 32 + md * 8 + v / 2) * 256] = __builtin_bit_cast(uint32_t, h);
+            }
+        dst[(64 + nb) * 256] = __float_as_uint(lsum[nb]);
+        dst[(66 + nb) * 256] = __float_as_uint(mref[nb]);
+        dst[(68 + nb) * 256] = (uint32_t)e;
+    }
+}
 
 // One launch serves up to ATTN_MAX_BATCH queries with their own rows, index sets, tile images and outputs (Sec. 4.3:
 // queries of a batch share nothing but the chunk store the images were built from).  The table travels as a kernel
@@ -787,18 +819,7 @@ __device__ __forceinline__ void process_piece(const AttnQuery& aq, int g, int or
     pv_half(rg.vt[k2], 1, pf_b, fo, o);   // the last half: V image ke-1 now sits in slot k2
 
     if (part >= 0) {   // leave the partial result; attn_combine_kernel adds the parts, checks and stores
-        float* dst = part_dst;
-#pragma unroll
-        for (int md = 0; md < 4; ++md)
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) dst[((2 * md + nb) * 16 + v) * 256] = o[md][nb][v];
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            dst[(128 + nb) * 256] = lsum[nb];
-            dst[(130 + nb) * 256] = mref[nb];
-        }
+        store_partial(part_dst, o, lsum, mref);
         return;
     }
     float l[2];
@@ -835,39 +856,42 @@ __global__ __launch_bounds__(256, 2) void attn_combine_kernel(const AttnQuery aq
     {
         Geometry<G> ge;
         ge.init(aq.q_index, aq.R, Hkv, aq.n_row_tiles, aq.n_img_tiles, g, ordinal);
-        const float* p0 = partials + (((size_t)ordinal * n_parts) * Hkv + g) * PART_FLOATS + threadIdx.x;
+        const uint32_t* p0 = reinterpret_cast<const uint32_t*>(partials + (((size_t)ordinal * n_parts) * Hkv + g) * PART_FLOATS) + threadIdx.x;
         const size_t part_stride = (size_t)Hkv * PART_FLOATS;
         f32x16 o[4][2];
-        float lsum[2], mref[2];
+        float lsum[2] = {0.f, 0.f}, mref[2];
 #pragma unroll
         for (int md = 0; md < 4; ++md)
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[md][nb][v] = p0[((2 * md + nb) * 16 + v) * 256];
+                for (int v = 0; v < 16; ++v) o[md][nb][v] = 0.f;
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            lsum[nb] = p0[(128 + nb) * 256];
-            mref[nb] = p0[(130 + nb) * 256];   // part 0 is never empty; every part derives the same reference
-        }
-        for (int part = 1; part < n_parts; ++part) {   // 64 loads in flight per lane, then their sums
-            const float* pp = p0 + part * part_stride;
+        for (int nb = 0; nb < 2; ++nb) mref[nb] = __uint_as_float(p0[(66 + nb) * 256]);   // part 0 is never empty; every part derives the same reference
+        for (int part = 0; part < n_parts; ++part) {   // a part's 70 loads are in flight together, then unpacked and added
+            const uint32_t* pp = p0 + part * part_stride;
+            uint32_t w[2][32];
+            uint32_t tail[2][2];
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                f32x16 t[2][2];
+            for (int nb = 0; nb < 2; ++nb) {
 #pragma unroll
-                for (int m2 = 0; m2 < 2; ++m2)
-#pragma unroll
-                    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) t[m2][nb][v] = pp[((2 * (2 * half + m2) + nb) * 16 + v) * 256];
-#pragma unroll
-                for (int m2 = 0; m2 < 2; ++m2)
-#pragma unroll
-                    for (int nb = 0; nb < 2; ++nb) o[2 * half + m2][nb] += t[m2][nb];
+                for (int j2 = 0; j2 < 32; ++j2) w[nb][j2] = pp[(nb * 32 + j2) * 256];
+                tail[nb][0] = pp[(64 + nb) * 256];
+                tail[nb][1] = pp[(68 + nb) * 256];
             }
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) lsum[nb] += pp[(128 + nb) * 256];
+            for (int nb = 0; nb < 2; ++nb) {
+                const int e = (int)tail[nb][1];
+#pragma unroll
+                for (int md = 0; md < 4; ++md)
+#pragma unroll
+                    for (int v = 0; v < 16; v += 2) {
+                        const f16x2 h = __builtin_bit_cast(f16x2, w[nb][md * 8 + v / 2]);
+                        o[md][nb][v] += __builtin_ldexpf((float)h[0], e);
+                        o[md][nb][v + 1] += __builtin_ldexpf((float)h[1], e);
+                    }
+                lsum[nb] += __uint_as_float(tail[nb][0]);
+            }
         }
         float l[2];
         if (!sums_overflowed(o, lsum, l)) {

@@ -220,7 +220,7 @@ def test_select_topk_exact(n, k, nq):
     ctx.close()
 
 
-@pytest.mark.parametrize("n,k,nq", [(32769, 4915, 3), (40000, 40000, 2), (33000, 1, 0), (300000, 45000, 9),
+@pytest.mark.parametrize("n,k,nq", [(32769, 4915, 3), (40000, 40000, 2), (33000, 1, 0), (40000, 0, 5), (300000, 45000, 9),
                                     (1 << 20, 157286, 0), (1234567, 1234, 1), (9000001, 1350000, 2)])
 def test_select_topk_many_workgroups(n, k, nq):
     """Score vectors beyond one workgroup's registers take the multi-pass selection: same definition, same oracle.
