@@ -30,7 +30,7 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E peak
 # counters itself, so the figure is quoted from the profile named here, together with the commit it was taken at, and
 # only for the exact workload and launch configuration that was profiled; everything else reports null.
 TRAFFIC_FROM_PROFILE = {
-    "llama3_8b_layer_16x1024+512": {"bytes": 703.8e6, "profile": "profiles/bench_config2_hbm_traffic.md", "commit": "aa48ae9"},
+    "llama3_8b_layer_16x1024+512": {"bytes": 593.5e6, "profile": "profiles/bench_config2_hbm_traffic.md", "commit": "5001ffd"},
 }
 
 
